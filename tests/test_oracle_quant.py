@@ -1,0 +1,174 @@
+"""Pins for the oracle's quantizer (Section 5) that do not come from the oracle
+itself: the four invariants of the format, closed-form groups, brute-force
+optimality of every code, rounding-mode and packing examples."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import fg_oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _gold(name):
+    out = {}
+    for line in open(os.path.join(GOLD, name)):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, v = line.split()[:2]
+        out[k] = float(v)
+    return out
+
+
+def _rand16(shape, std, seed):
+    return (np.random.default_rng(seed).standard_normal(shape) * std).astype(np.float16)
+
+
+def test_format_constants_match_paper():
+    g = _gold("paper_quant_format.txt")
+    assert O.BITS == g["bits"] and O.GROUP == g["group"] and O.QMAX == g["levels"]
+    assert O.bytes_per_element(True) == 0.5 + 8 / 64 == 0.625
+    assert O.bytes_per_element(False) == 2.0
+
+
+@pytest.mark.parametrize("std,seed", [(0.02, 1), (1.0, 2), (30.0, 3)])
+def test_invariants(std, seed):
+    x = _rand16((37, 64 * 9), std, seed)
+    codes, meta = O.quantize_groupwise(x)
+    assert codes.dtype == np.uint8 and codes.shape == (37, 64 * 9 // 2)
+    assert meta.dtype == np.float32 and meta.shape == (37, 9, 2)
+    c = O.unpack_codes(codes)
+    assert c.min() >= 0 and c.max() <= 15
+    xg = x.astype(np.float64).reshape(37, 9, 64)
+    cg = c.reshape(37, 9, 64).astype(np.float64)
+    mn = meta[..., 0].astype(np.float64)[..., None]
+    sc = meta[..., 1].astype(np.float64)[..., None]
+    # every dequantized element within scale/2 of the original (evaluated in double)
+    err = np.abs(xg - (mn + cg * sc))
+    assert np.all(err <= sc / 2 * (1 + 2.0 ** -20))
+    # min and max of each group: codes 0 and 15, values round-trip exactly through FP16
+    xh = O.dequantize_groupwise(codes, meta).reshape(37, 9, 64)
+    imin = xg.argmin(axis=2)[..., None]
+    imax = xg.argmax(axis=2)[..., None]
+    assert np.all(np.take_along_axis(cg, imin, 2) == 0)
+    assert np.all(np.take_along_axis(cg, imax, 2) == 15)
+    assert np.array_equal(np.take_along_axis(xh, imin, 2), np.take_along_axis(xg, imin, 2).astype(np.float32))
+    assert np.array_equal(np.take_along_axis(xh, imax, 2).astype(np.float16),
+                          np.take_along_axis(xg, imax, 2).astype(np.float16))
+    # stored min is the true min, stored scale is (max-min)/15 to binary32 rounding
+    assert np.array_equal(meta[..., 0], xg.min(axis=2).astype(np.float32))
+    ref_scale = (xg.max(axis=2) - xg.min(axis=2)) / 15.0
+    assert np.allclose(meta[..., 1], ref_scale, rtol=2 ** -23, atol=0)
+
+
+def test_bruteforce_each_code_is_nearest_level():
+    """For every element, no other of the 16 levels min + c*scale is closer."""
+    x = _rand16((16, 256), 0.5, 7)
+    codes, meta = O.quantize_groupwise(x)
+    c = O.unpack_codes(codes).reshape(16, 4, 64).astype(np.int64)
+    xg = x.astype(np.float64).reshape(16, 4, 64)
+    mn = meta[..., 0].astype(np.float64)
+    sc = meta[..., 1].astype(np.float64)
+    levels = mn[..., None] + np.arange(16)[None, None, :] * sc[..., None]      # [16,4,16]
+    d = np.abs(xg[..., None] - levels[:, :, None, :])                           # [16,4,64,16]
+    best = d.min(axis=-1)
+    chosen = np.take_along_axis(d, c[..., None], -1)[..., 0]
+    # the chosen level is optimal up to the binary32 rounding of the quotient
+    assert np.all(chosen <= best + sc[..., None] * 2.0 ** -20)
+
+
+def test_closed_form_integer_group():
+    """A group holding 0..15 four times: min 0, scale 1, codes equal the values."""
+    v = np.tile(np.arange(16), 4).astype(np.float16)[None, :]
+    codes, meta = O.quantize_groupwise(v)
+    assert meta[0, 0, 0] == 0.0 and meta[0, 0, 1] == 1.0
+    assert np.array_equal(O.unpack_codes(codes)[0], np.tile(np.arange(16), 4))
+    assert np.array_equal(O.dequantize_groupwise(codes, meta)[0], v[0].astype(np.float32))
+
+
+def test_closed_form_affine_group():
+    """x = -3 + 0.5*k for k in 0..15 (exact in FP16): scale 0.5, code k."""
+    k = np.tile(np.arange(16), 4)
+    v = (-3.0 + 0.5 * k).astype(np.float16)[None, :]
+    codes, meta = O.quantize_groupwise(v)
+    assert meta[0, 0, 0] == -3.0 and meta[0, 0, 1] == 0.5
+    assert np.array_equal(O.unpack_codes(codes)[0], k)
+
+
+def test_ties_round_to_even():
+    """With min 0 and max 15 the scale is exactly 1, so 0.5, 1.5, 2.5, 3.5 are
+    exact ties: nearest-even gives 0, 2, 2, 4."""
+    v = np.zeros(64, np.float16)
+    v[1] = 15.0
+    v[2:6] = [0.5, 1.5, 2.5, 3.5]
+    v[6:9] = [0.49, 1.51, 14.5]
+    codes, meta = O.quantize_groupwise(v[None, :])
+    c = O.unpack_codes(codes)[0]
+    assert list(c[2:6]) == [0, 2, 2, 4]
+    assert list(c[6:9]) == [0, 2, 14]
+    assert c[0] == 0 and c[1] == 15
+
+
+def test_constant_group_is_exact():
+    v = np.full((2, 128), 0.37, np.float16)
+    v[1, 64:] = -2.5
+    codes, meta = O.quantize_groupwise(v)
+    assert np.all(codes == 0)
+    assert np.all(meta[..., 1] == 0)
+    assert np.array_equal(O.dequantize_groupwise(codes, meta), v.astype(np.float32))
+
+
+def test_packing_hand_example():
+    """Even element in the low nibble: codes 1,2,3,4,15,0,9,10 -> 0x21 0x43 0x0F 0xA9."""
+    c = np.array([[1, 2, 3, 4, 15, 0, 9, 10]], np.uint8)
+    b = O.pack_codes(c)
+    assert list(b[0]) == [0x21, 0x43, 0x0F, 0xA9]
+    assert np.array_equal(O.unpack_codes(b), c)
+    r = np.random.default_rng(0).integers(0, 16, size=(5, 128)).astype(np.uint8)
+    assert np.array_equal(O.unpack_codes(O.pack_codes(r)), r)
+
+
+def test_groups_are_independent_and_along_last_axis():
+    """Changing one group's data changes only that group's codes and meta."""
+    x = _rand16((3, 192), 1.0, 11)
+    c0, m0 = O.quantize_groupwise(x)
+    y = x.copy()
+    y[1, 64:128] *= np.float16(3.0)
+    c1, m1 = O.quantize_groupwise(y)
+    same = np.ones((3, 3), bool)
+    same[1, 1] = False
+    assert np.array_equal(m0[same], m1[same])
+    assert not np.array_equal(m0[1, 1], m1[1, 1])
+    cc0 = c0.reshape(3, 3, 32)
+    cc1 = c1.reshape(3, 3, 32)
+    assert np.array_equal(cc0[same], cc1[same])
+
+
+def test_independent_library_formulation():
+    """The same definition spelled with torch CPU tensor ops (library min / max /
+    round, which rounds half to even) gives identical bits."""
+    import torch
+    x = _rand16((64, 512), 0.02, 5)
+    codes, meta = O.quantize_groupwise(x)
+    t = torch.from_numpy(x).float().reshape(64, 8, 64)
+    mn = t.amin(dim=2, keepdim=True)
+    mx = t.amax(dim=2, keepdim=True)
+    sc = (mx - mn) / 15.0
+    q = torch.clamp(torch.round((t - mn) / sc), 0, 15).to(torch.uint8).reshape(64, 512)
+    assert np.array_equal(O.unpack_codes(codes), q.numpy())
+    assert np.array_equal(meta[..., 0], mn[..., 0].numpy())
+    assert np.array_equal(meta[..., 1], sc[..., 0].numpy())
+
+
+def test_rejects_bad_arguments():
+    with pytest.raises(ValueError):
+        O.quantize_groupwise(np.zeros((2, 96), np.float16))
+    with pytest.raises(ValueError):
+        O.quantize_groupwise(np.zeros((2, 64), np.float32))
+    with pytest.raises(ValueError):
+        O.quantize_groupwise(np.zeros((2, 64), np.float16), group=32)
+    bad = np.zeros((1, 64), np.float16)
+    bad[0, 3] = np.inf
+    with pytest.raises(ValueError):
+        O.quantize_groupwise(bad)
