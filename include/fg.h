@@ -1,0 +1,226 @@
+/*
+ * fg.h — C ABI of the MI355X (gfx950) generation path for OPT-style decoders whose
+ * weights and attention (KV) cache are compressed with group-wise 4-bit asymmetric
+ * quantization (FlexGen, arXiv 2303.06865).
+ *
+ * Conventions shared by every call
+ *   - Returns 0 (FG_OK) or a negative fg_status.  Never throws, never aborts.
+ *   - Every buffer is a caller-owned DEVICE pointer unless the comment says "host".
+ *     The library allocates no device memory: scratch space is the caller's `ws`
+ *     argument, sized by the matching *_workspace_bytes call.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued asynchronously on it; the call returns before the GPU finishes, except
+ *     fg_generate with a non-NULL `stats`, which synchronises the stream to read timers.
+ *   - Arguments are validated on the host before anything is launched, so every error
+ *     path can be exercised without a GPU (a NULL/shape/unsupported error is returned
+ *     before the first HIP call).
+ *   - FP16 means IEEE binary16.  Matrices are row-major.
+ *
+ * Storage formats
+ *   FG_F16    plain FP16.
+ *   FG_Q4G64  Section 5 of the paper: groups of 64 consecutive elements of the last
+ *             (contiguous) dimension share one pair {float min, float scale}, with
+ *             scale = (max-min)/15, and each element is stored as the 4-bit code
+ *             round((x-min)/scale) (ties to even; a constant group has scale 0 and codes 0).
+ *             codes: cols/2 bytes per row, element 2j in the low nibble of byte j;
+ *             meta : cols/64 pairs per row, 8 bytes each {min, scale} (binary32).
+ *             An element is recovered as min + code*scale.  0.625 bytes per element.
+ */
+#ifndef FG_H
+#define FG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FG_OK = 0,
+  FG_ERR_NULL = -1,        /* a required pointer is NULL */
+  FG_ERR_SHAPE = -2,       /* a dimension is <= 0, not a multiple of 64 where required, t >= cap, ... */
+  FG_ERR_UNSUPPORTED = -3, /* bits != 4, group != 64, unknown dtype, head size not 64 or 128 */
+  FG_ERR_WORKSPACE = -4,   /* ws is NULL or smaller than the matching *_workspace_bytes */
+  FG_ERR_DEVICE = -5       /* a HIP runtime call failed (see fg_last_device_error) */
+} fg_status;
+
+typedef enum { FG_F16 = 0, FG_Q4G64 = 1 } fg_dtype;
+
+/* A weight matrix [rows = output features, cols = input features], row-major.
+ * FG_F16:   data = FP16 values, meta = NULL.
+ * FG_Q4G64: data = packed codes (rows*cols/2 bytes), meta = rows*cols/64 {min,scale} pairs;
+ *           groups run along cols (the contraction dimension); cols % 64 == 0. */
+typedef struct {
+  const void* data;
+  const void* meta;
+  int32_t dtype; /* fg_dtype */
+  int32_t reserved;
+  int64_t rows, cols;
+} fg_mat;
+
+/* Model shape in the paper's notation (Section 3): h1 hidden size, h2 hidden size of the
+ * MLP, nh attention heads (head size dh = h1/nh must be 64 or 128), vocabulary size,
+ * number of learned position rows, LayerNorm epsilon. */
+typedef struct {
+  int32_t h1, nh, h2, vocab, max_pos;
+  float ln_eps;
+} fg_model_cfg;
+
+/* One decoder layer (Section 3: wQ, wK, wV, wO, w1, w2; OPT's pre-LayerNorm placement).
+ * wqkv stacks Wq, Wk, Wv along rows: [3*h1, h1].  wo [h1,h1], w1 [h2,h1], w2 [h1,h2].
+ * Biases are FP16 vectors and may be NULL (= 0).  LayerNorm gamma/beta are FP16 [h1]. */
+typedef struct {
+  fg_mat wqkv, wo, w1, w2;
+  const void *bqkv, *bo, *b1, *b2;
+  const void *ln1_g, *ln1_b, *ln2_g, *ln2_b;
+} fg_layer_weights;
+
+/* The KV cache of one layer for `batch` sequences, logical layout [batch, nh, cap, dh].
+ * FG_Q4G64: k_codes/v_codes hold dh/2 bytes per (sequence, head, row); k_meta/v_meta hold
+ *           dh/64 {min,scale} pairs per (sequence, head, row).  Groups run along the hidden
+ *           dimension of a token row (Section 5), so no group straddles a head.
+ * FG_F16:   k_codes/v_codes hold dh FP16 values per (sequence, head, row); metas are NULL. */
+typedef struct {
+  void *k_codes, *k_meta, *v_codes, *v_meta;
+  int32_t dtype; /* fg_dtype */
+  int32_t batch;
+  int32_t cap; /* rows allocated per (sequence, head); >= s + n - 1 */
+  int32_t reserved;
+} fg_kv_cache;
+
+/* Timers and byte counts written by fg_generate (host memory). */
+typedef struct {
+  double prefill_s;             /* token step 1: all layers, all GPU batches, first token */
+  double decode_s;              /* token steps 2..n */
+  int64_t tokens;               /* bls * n */
+  int64_t weight_bytes_per_step;/* stored bytes of all layer matrices (read once per block and step) */
+  int64_t kv_bytes_last_step;   /* stored K+V bytes attended to in the last decode step */
+  double* decode_step_s;        /* host array of n-1 doubles or NULL: seconds of each decode step */
+} fg_stats;
+
+const char* fg_error_string(int status);
+/* Text of the HIP error behind the last FG_ERR_DEVICE of the calling thread ("" if none). */
+const char* fg_last_device_error(void);
+/* 10000*major + 100*minor + patch */
+int fg_version(void);
+
+/* ---- Section 5: group-wise quantization ------------------------------------------------
+ * Quantize x [rows, cols] FP16 (device, row-major, contiguous) into FG_Q4G64:
+ * codes_out rows*cols/2 bytes, meta_out rows*cols/64 pairs.  group must be 64 and bits 4
+ * (FG_ERR_UNSUPPORTED otherwise); cols % 64 == 0 and rows >= 0 (rows == 0 is a no-op).
+ * The same routine serves weight matrices (groups along the input dimension) and KV token
+ * rows (groups along the hidden dimension).  Results are bit-exact functions of the input:
+ * binary32 arithmetic, IEEE division, no fused multiply-add. */
+int fg_quantize_groupwise(const void* x_f16, int64_t rows, int64_t cols, int group, int bits,
+                          void* codes_out, void* meta_out, void* stream);
+
+/* Inverse map of Section 5 (stored 4-bit -> values before computation): out_f32[r][c] =
+ * min + code*scale evaluated as one binary32 multiply then one binary32 add. */
+int fg_dequantize_groupwise(const void* codes, const void* meta, int64_t rows, int64_t cols,
+                            void* out_f32, void* stream);
+
+/* ---- Section 3 pieces, exported so each can be checked on its own ---------------------- */
+
+/* Row-wise LayerNorm of x [rows, cols] FP16 with FP16 gamma/beta, statistics in binary32,
+ * FP16 result.  cols % 8 == 0. */
+int fg_layernorm(const void* x_f16, const void* gamma_f16, const void* beta_f16, int64_t rows,
+                 int64_t cols, float eps, void* out_f16, void* stream);
+
+/* out[m, w.rows] = act(x[m, w.cols] . W^T + bias) + residual   (Section 3: x . w)
+ * x, residual (nullable), out are FP16 row-major; bias FP16 (nullable); relu != 0 applies
+ * max(.,0) before the residual is added.  FG_Q4G64 weights are dequantized inside the kernel
+ * (never materialised in HBM).  w.cols % 64 == 0; w.rows % 8 == 0; m >= 0.
+ * ws must hold fg_linear_workspace_bytes(&w, m) bytes (may be 0 => ws may be NULL). */
+int fg_linear(const fg_mat* w, const void* bias_f16, const void* x_f16, int64_t m,
+              const void* residual_f16, int relu, void* out_f16, void* ws, size_t ws_bytes,
+              void* stream);
+size_t fg_linear_workspace_bytes(const fg_mat* w, int64_t m);
+
+/* Store K and V token rows into a layer's cache (Section 3 "Concat", Section 5 storage):
+ * k, v are FP16 [b, s, h1] views whose consecutive rows are row_stride elements apart
+ * (so they may be column slices of a [b*s, 3*h1] QKV buffer).  Rows land at cache rows
+ * pos0 .. pos0+s-1 of sequences batch_offset .. batch_offset+b-1; with FG_Q4G64 every
+ * 64-element group of a row is quantized exactly as fg_quantize_groupwise does. */
+int fg_kv_append(const fg_model_cfg* cfg, const void* k_f16, const void* v_f16, int64_t row_stride,
+                 int32_t b, int32_t s, const fg_kv_cache* kv, int32_t batch_offset, int32_t pos0,
+                 void* stream);
+
+/* Decode-phase attention (Section 3): for each of b sequences and nh heads,
+ * out = softmax(q . K^T / sqrt(dh)) . V over cache rows 0 .. rows-1 of sequence
+ * batch_offset+i, K and V read in their stored format and dequantized in registers.
+ * q is an FP16 [b, h1] view with row stride q_row_stride elements; out FP16 [b, h1]. */
+int fg_decode_attention(const fg_model_cfg* cfg, const void* q_f16, int64_t q_row_stride, int32_t b,
+                        int32_t rows, const fg_kv_cache* kv, int32_t batch_offset, void* out_f16,
+                        void* stream);
+
+/* Prefill-phase attention (Section 3): causal softmax(q . k^T / sqrt(dh)) . v per sequence and
+ * head over the fresh FP16 q, k, v held in qkv [b*s, 3*h1] (columns q | k | v); out [b*s, h1]. */
+int fg_prefill_attention(const fg_model_cfg* cfg, const void* qkv_f16, int32_t b, int32_t s,
+                         void* out_f16, void* stream);
+
+/* x0 = E[id] + P[pos] (FP16).  ids int32 [rows]; position of row r is pos0 + (r % s_len). */
+int fg_embed(const fg_model_cfg* cfg, const void* embed_f16, const void* pos_f16, const int32_t* ids,
+             int64_t rows, int32_t s_len, int32_t pos0, void* out_f16, void* stream);
+
+/* Final LayerNorm, logits against the tied FP16 embedding [vocab, h1], greedy argmax with the
+ * lowest index winning ties.  x FP16 [rows, h1] with row stride x_row_stride elements.
+ * out_ids int32, written with stride out_stride elements; logits_f32 [rows, vocab] is scratch
+ * the caller may inspect.  ws >= fg_lm_head_workspace_bytes. */
+int fg_lm_head_greedy(const fg_model_cfg* cfg, const void* x_f16, int64_t x_row_stride, int64_t rows,
+                      const void* lnf_g, const void* lnf_b, const void* embed_f16, int32_t* out_ids,
+                      int64_t out_stride, float* logits_f32, void* ws, size_t ws_bytes, void* stream);
+size_t fg_lm_head_workspace_bytes(const fg_model_cfg* cfg, int64_t rows);
+
+/* ---- Section 3: one transformer layer --------------------------------------------------
+ * Prefill: x_in [b, s, h1] FP16 -> x_out [b, s, h1].  Attention is causal over the fresh FP16
+ * K/V; then the s K/V rows are stored at cache rows 0..s-1 of sequences batch_offset.. .
+ * ws >= fg_layer_workspace_bytes(cfg, wts, b*s).  x_out may alias x_in. */
+int fg_prefill_layer(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in, int32_t b,
+                     int32_t s, const fg_kv_cache* kv, int32_t batch_offset, void* x_out, void* ws,
+                     size_t ws_bytes, void* stream);
+
+/* Decode: x_in [b, h1] FP16 is the current token; t rows are already cached (0 <= t < cap).
+ * Appends the new K/V row at row t in the storage format, attends to rows 0..t read back from
+ * the cache, then output projection, residual, MLP, residual.  x_out [b, h1] may alias x_in.
+ * ws >= fg_layer_workspace_bytes(cfg, wts, b). */
+int fg_decode_layer(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in, int32_t b,
+                    int32_t t, const fg_kv_cache* kv, int32_t batch_offset, void* x_out, void* ws,
+                    size_t ws_bytes, void* stream);
+size_t fg_layer_workspace_bytes(const fg_model_cfg* cfg, const fg_layer_weights* wts, int64_t rows);
+
+/* ---- Sections 3-4: generation of a block -----------------------------------------------
+ * A model of l layers, prompts of s tokens, n generated tokens, a block of
+ * num_gpu_batches x gpu_batch_size sequences (bls).  Token step 1 prefills the prompts and
+ * emits token 1; steps 2..n decode.  Loop nest of the block schedule (Algorithm 1): token
+ * step -> layer -> GPU batch, so a layer's weights are streamed once per block and step; in
+ * decode steps all bls rows go through a layer's projections in one pass.
+ * layers: host array of l structs (device pointers inside).  kv: host array of l caches with
+ * batch == bls and cap >= s+n-1.  prompt int32 [bls, s] device; out_ids int32 [bls, n] device.
+ * ws >= fg_workspace_bytes(...).  stats (host) may be NULL. */
+int fg_generate(const fg_model_cfg* cfg, int32_t l, const fg_layer_weights* layers, const void* embed_f16,
+                const void* pos_f16, const void* lnf_g, const void* lnf_b, const int32_t* prompt,
+                int32_t s, int32_t n, int32_t num_gpu_batches, int32_t gpu_batch_size,
+                const fg_kv_cache* kv, int32_t* out_ids, void* ws, size_t ws_bytes, void* stream,
+                fg_stats* stats);
+size_t fg_workspace_bytes(const fg_model_cfg* cfg, const fg_layer_weights* layer0, int32_t gpu_batch_size,
+                          int32_t num_gpu_batches, int32_t s);
+
+/* ---- Per-kernel timing (HIP events on the caller's stream) -----------------------------
+ * Between fg_profile_begin and fg_profile_end every kernel launch of the library is bracketed
+ * by two events.  fg_profile_end synchronises and accumulates, per kernel class, the summed
+ * GPU time and the number of launches; fg_profile_read returns them.  Global, not thread-safe. */
+typedef enum {
+  FG_K_QUANTIZE = 0, FG_K_DEQUANTIZE, FG_K_LAYERNORM, FG_K_GEMM_SMALL_M, FG_K_GEMM_SMALL_M_FINISH,
+  FG_K_GEMM_LARGE_M, FG_K_KV_APPEND, FG_K_ATTN_DECODE, FG_K_ATTN_PREFILL, FG_K_EMBED, FG_K_ARGMAX,
+  FG_K_COUNT
+} fg_kernel_class;
+int fg_profile_begin(void);
+int fg_profile_end(void);
+int fg_profile_read(int kernel_class, double* total_ms, int64_t* launches);
+const char* fg_kernel_class_name(int kernel_class);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FG_H */

@@ -1,0 +1,398 @@
+// Decode-phase attention over the stored KV cache (Section 3, decode: softmax(tQ.K^T/sqrt(h)).V),
+// with the cache read in its storage format of Section 5 and dequantized in registers.
+//
+// One workgroup of four waves per (sequence, head).  The rows of that head's K and V are one
+// contiguous byte stream in the cache, read 16 bytes per lane (1 KiB per wave load).  Waves take
+// 4 KiB chunks of the stream round-robin, keep a running (max, sum, output) triple each, and the
+// four triples are merged through LDS at the end (log-sum-exp merge).
+//
+// 4-bit path, per chunk of 128 quantization groups (64 rows at head size 128, 128 rows at 64):
+//   scores  : q.k_hat = sum_g scale_g * (q_g . c_g) + min_g * sum(q_g).  The code dot products run on
+//             the matrix cores: the K codes, expanded to FP16 in registers, are the B operand of
+//             v_mfma_f32_16x16x32_f16 (lane = row, 8 consecutive codes per lane); the A operand
+//             holds the query, masked so that output row 0/1 of each lane group separates the two
+//             groups a lane pair covers.  Sixteen MFMAs leave, in lane L, the two group sums of
+//             groups 2L and 2L+1 of the chunk, which is also the lane that loaded their {min,scale}.
+//   softmax : one or two scores per lane, wavefront shuffles for the running max.
+//   output  : sum_j p_j v_hat_j = sum_j (p_j scale_j)(c_j - 8) + sum_j p_j (min_j + 8 scale_j); the
+//             first term is accumulated per lane over its 32 head dimensions with FP16->FP32 mixed
+//             FMAs, the second is one scalar per group.
+#include "fg_common.h"
+
+namespace fg {
+
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+struct AttnArgs {
+  const half_t* q;
+  int64_t q_stride;
+  const uint8_t* k_codes;
+  const uint8_t* v_codes;
+  const float2* k_meta;
+  const float2* v_meta;
+  half_t* out;       // [b, nh*dh]
+  int nh, cap, rows, batch_offset;
+  float scale;       // 1/sqrt(dh)
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Merge the four per-wave triples and write the head's output.  o_w already includes the
+// per-group constant term.
+template <int DH>
+__device__ __forceinline__ void merge_and_store(float* sm_m, float* sm_l, float* sm_o, half_t* out) {
+  __syncthreads();
+  const int t = threadIdx.x;
+  if (t < DH) {
+    float M = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
+    float num = 0.f, den = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float f = sm_m[w] == -INFINITY ? 0.f : fast_exp2((sm_m[w] - M) * kLog2e);
+      num += f * sm_o[w * DH + t];
+      den += f * sm_l[w];
+    }
+    out[t] = (half_t)(num / den);
+  }
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
+  constexpr int GPR = DH / 64;       // quantization groups per row of this head
+  constexpr int NS = 2 / GPR;        // scores per lane per chunk (lane owns groups 2L, 2L+1)
+  __shared__ __attribute__((aligned(16))) half_t sm_q[DH];
+  __shared__ float sm_m[4], sm_l[4];
+  __shared__ float sm_o[4 * DH];
+
+  const int head = blockIdx.x, seq = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, q4 = lane >> 4, h = q4 >> 1, half = q4 & 1;
+
+  const int64_t hrow = ((int64_t)(a.batch_offset + seq) * a.nh + head) * a.cap;   // first cache row
+  const uint8_t* kc = a.k_codes + hrow * (DH / 2);
+  const uint8_t* vc = a.v_codes + hrow * (DH / 2);
+  const float2* km = a.k_meta + hrow * GPR;
+  const float2* vm = a.v_meta + hrow * GPR;
+  const int G = a.rows * GPR;                  // groups in the stream
+  const int n_chunks = (G + 127) >> 7;
+
+  if (tid < DH / 8)
+    *reinterpret_cast<u4_t*>(sm_q + tid * 8) =
+        *reinterpret_cast<const u4_t*>(a.q + (int64_t)seq * a.q_stride + head * DH + tid * 8);
+  __syncthreads();
+
+  // per-group query sums: Qs = sum q_d, Os = sum off_d q_d with off = 1024 (even d) / 64 (odd d),
+  // the biases the register unpacking leaves on the codes.
+  float Qs[2], Os[2];
+  {
+    const float qa_ = (float)sm_q[lane];
+    const float qb_ = DH == 128 ? (float)sm_q[(lane + 64) % DH] : qa_;
+    const float off = (lane & 1) ? 64.f : 1024.f;
+    Qs[0] = wave_sum(qa_);
+    Os[0] = wave_sum(qa_ * off);
+    Qs[1] = wave_sum(qb_);
+    Os[1] = wave_sum(qb_ * off);
+  }
+
+  // A operands: qop[i][u] is non-zero only in lanes whose output row (lane&15) equals 4*i + h,
+  // so that load i's sixteen rows land in lane group i of the accumulator.
+  h8_t qop[4][4];
+  {
+    const int m = lane & 15;
+    const bool valid_h = (m & 3) == h;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int d0 = (DH == 128 ? 64 * h : 0) + 32 * half + 8 * u;
+      const u4_t raw = *reinterpret_cast<const u4_t*>(sm_q + d0);
+      const u4_t pm = permute8_like_codes(raw);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool valid = valid_h && ((m >> 2) == i);
+        const u4_t z = {0u, 0u, 0u, 0u};
+        qop[i][u] = __builtin_bit_cast(h8_t, valid ? pm : z);
+      }
+    }
+  }
+
+  float m_run = -INFINITY, l_run = 0.f;
+  float mterm[2] = {0.f, 0.f};   // sum_j p_j (min_j + 8 scale_j) for the groups this lane owns
+  float o[32];
+#pragma unroll
+  for (int e = 0; e < 32; ++e) o[e] = 0.f;
+
+  for (int chunk = wave; chunk < n_chunks; chunk += 4) {
+    const int gbase = chunk << 7;
+    // ---- loads (all addresses clamped into the stream; masked later)
+    u4_t kq[4], vq[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int g = gbase + 32 * i + 2 * r + h;
+      g = g < G ? g : G - 1;
+      kq[i] = *reinterpret_cast<const u4_t*>(kc + (int64_t)g * 32 + half * 16);
+      vq[i] = *reinterpret_cast<const u4_t*>(vc + (int64_t)g * 32 + half * 16);
+    }
+    const int g0 = gbase + 2 * lane, g1 = g0 + 1;
+    const float2 km0 = km[g0 < G ? g0 : G - 1], km1 = km[g1 < G ? g1 : G - 1];
+    const float2 vm0 = vm[g0 < G ? g0 : G - 1], vm1 = vm[g1 < G ? g1 : G - 1];
+
+    // ---- scores on the matrix cores
+    f4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        uint32_t pk[4];
+        unpack8_biased(kq[i][u], pk);
+        const u4_t bw = {pk[0], pk[1], pk[2], pk[3]};
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qop[i][u], __builtin_bit_cast(h8_t, bw), acc, 0, 0, 0);
+      }
+    }
+    const float s0 = km0.y * (acc[0] - Os[0]) + km0.x * Qs[0];
+    const float s1 = km1.y * (acc[1] - Os[1]) + km1.x * Qs[1];
+    float sc[NS];
+    if (DH == 128) {
+      sc[0] = g0 < G ? (s0 + s1) * a.scale : -INFINITY;
+    } else {
+      sc[0] = g0 < G ? s0 * a.scale : -INFINITY;
+      sc[NS - 1] = g1 < G ? s1 * a.scale : -INFINITY;
+    }
+    // ---- online softmax (chunk 0 of every wave has at least one valid row)
+    float cmax = sc[0];
+    if (NS == 2) cmax = fmaxf(cmax, sc[NS - 1]);
+    cmax = wave_max(cmax);
+    const float m_new = fmaxf(m_run, cmax);
+    if (m_new > m_run) {   // wave-uniform
+      const float alpha = fast_exp2((m_run - m_new) * kLog2e);
+      l_run *= alpha;
+      mterm[0] *= alpha;
+      mterm[1] *= alpha;
+#pragma unroll
+      for (int e = 0; e < 32; ++e) o[e] *= alpha;
+      m_run = m_new;
+    }
+    float p[2];
+    p[0] = fast_exp2((sc[0] - m_run) * kLog2e);
+    p[1] = NS == 2 ? fast_exp2((sc[NS - 1] - m_run) * kLog2e) : p[0];
+    l_run += NS == 2 ? p[0] + p[1] : p[0];
+    // weights of the V codes of the two groups this lane owns, and their constant terms
+    const float wv0 = p[0] * vm0.y, wv1 = p[1] * vm1.y;
+    mterm[0] += p[0] * (vm0.x + 8.f * vm0.y);
+    mterm[1] += p[1] * (vm1.x + 8.f * vm1.y);
+
+    // ---- output accumulation: lane (r, q4) handles group 32 i + 2 r + h of each load, half `half`
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int src = 16 * i + r;
+      const float w0 = __shfl(wv0, src, 64), w1 = __shfl(wv1, src, 64);
+      const float w = h ? w1 : w0;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        uint32_t pk[4];
+        unpack8_biased(vq[i][u], pk);
+        const h2_t k1032 = {(half_t)1032.0f, (half_t)1032.0f};
+        const h2_t k72 = {(half_t)72.0f, (half_t)72.0f};
+        const h2_t c04 = __builtin_bit_cast(h2_t, pk[0]) - k1032;   // codes - 8, exact
+        const h2_t c15 = __builtin_bit_cast(h2_t, pk[1]) - k72;
+        const h2_t c26 = __builtin_bit_cast(h2_t, pk[2]) - k1032;
+        const h2_t c37 = __builtin_bit_cast(h2_t, pk[3]) - k72;
+        o[8 * u + 0] += w * (float)c04.x;
+        o[8 * u + 4] += w * (float)c04.y;
+        o[8 * u + 1] += w * (float)c15.x;
+        o[8 * u + 5] += w * (float)c15.y;
+        o[8 * u + 2] += w * (float)c26.x;
+        o[8 * u + 6] += w * (float)c26.y;
+        o[8 * u + 3] += w * (float)c37.x;
+        o[8 * u + 7] += w * (float)c37.y;
+      }
+    }
+  }
+
+  // ---- reduce inside the wave: lanes with the same head-dimension range add up
+#pragma unroll
+  for (int e = 0; e < 32; ++e) {
+    float v = o[e];
+    v += __shfl_xor(v, 1, 64);
+    v += __shfl_xor(v, 2, 64);
+    v += __shfl_xor(v, 4, 64);
+    v += __shfl_xor(v, 8, 64);
+    if (DH == 64) v += __shfl_xor(v, 32, 64);
+    o[e] = v;
+  }
+  const float lw = wave_sum(l_run);
+  const float mt0 = wave_sum(mterm[0]), mt1 = wave_sum(mterm[1]);
+  if (lane == 0) {
+    sm_m[wave] = m_run;
+    sm_l[wave] = lw;
+  }
+  if (r == 0 && (DH == 128 || h == 0)) {
+    // this lane's range: head dims [dbase, dbase + 32), all in one quantization group
+    const int dbase = DH == 128 ? 32 * q4 : 32 * half;
+    const float c = DH == 128 ? (h ? mt1 : mt0) : (mt0 + mt1);
+#pragma unroll
+    for (int e = 0; e < 32; ++e) sm_o[wave * DH + dbase + e] = o[e] + c;
+  }
+  merge_and_store<DH>(sm_m, sm_l, sm_o, a.out + (int64_t)seq * a.nh * DH + head * DH);
+}
+
+// FP16 cache: the same streaming structure without the unpacking.  K rows are the B operand
+// directly (lane = row, 8 consecutive head dimensions per lane).
+template <int DH>
+__global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
+  constexpr int NU = DH / 32;        // 32-wide head-dimension blocks
+  __shared__ __attribute__((aligned(16))) half_t sm_q[DH];
+  __shared__ float sm_m[4], sm_l[4];
+  __shared__ float sm_o[4 * DH];
+
+  const int head = blockIdx.x, seq = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, q4 = lane >> 4;
+  const int64_t hrow = ((int64_t)(a.batch_offset + seq) * a.nh + head) * a.cap;
+  const half_t* kp = reinterpret_cast<const half_t*>(a.k_codes) + hrow * DH;
+  const half_t* vp = reinterpret_cast<const half_t*>(a.v_codes) + hrow * DH;
+  const int n_chunks = (a.rows + 63) >> 6;
+
+  if (tid < DH / 8)
+    *reinterpret_cast<u4_t*>(sm_q + tid * 8) =
+        *reinterpret_cast<const u4_t*>(a.q + (int64_t)seq * a.q_stride + head * DH + tid * 8);
+  __syncthreads();
+
+  h8_t qop[4][NU];
+  {
+    const int m = lane & 15;
+#pragma unroll
+    for (int u = 0; u < NU; ++u) {
+      const u4_t raw = *reinterpret_cast<const u4_t*>(sm_q + 32 * u + 8 * q4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const u4_t z = {0u, 0u, 0u, 0u};
+        qop[i][u] = __builtin_bit_cast(h8_t, (m == 4 * i) ? raw : z);
+      }
+    }
+  }
+
+  float m_run = -INFINITY, l_run = 0.f;
+  float o[8 * NU];
+#pragma unroll
+  for (int e = 0; e < 8 * NU; ++e) o[e] = 0.f;
+
+  for (int chunk = wave; chunk < n_chunks; chunk += 4) {
+    const int rbase = chunk << 6;
+    f4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int row = rbase + 16 * i + r;
+      row = row < a.rows ? row : a.rows - 1;
+#pragma unroll
+      for (int u = 0; u < NU; ++u) {
+        const h8_t kv = *reinterpret_cast<const h8_t*>(kp + (int64_t)row * DH + 32 * u + 8 * q4);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qop[i][u], kv, acc, 0, 0, 0);
+      }
+    }
+    const float sc = (rbase + lane) < a.rows ? acc[0] * a.scale : -INFINITY;
+    const float cmax = wave_max(sc);
+    const float m_new = fmaxf(m_run, cmax);
+    if (m_new > m_run) {
+      const float alpha = fast_exp2((m_run - m_new) * kLog2e);
+      l_run *= alpha;
+#pragma unroll
+      for (int e = 0; e < 8 * NU; ++e) o[e] *= alpha;
+      m_run = m_new;
+    }
+    const float p = fast_exp2((sc - m_run) * kLog2e);
+    l_run += p;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int row = rbase + 16 * i + r;
+      row = row < a.rows ? row : a.rows - 1;
+      const float w = __shfl(p, 16 * i + r, 64);
+#pragma unroll
+      for (int u = 0; u < NU; ++u) {
+        const h8_t vv = *reinterpret_cast<const h8_t*>(vp + (int64_t)row * DH + 32 * u + 8 * q4);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[8 * u + e] += w * (float)vv[e];
+      }
+    }
+  }
+
+#pragma unroll
+  for (int e = 0; e < 8 * NU; ++e) {
+    float v = o[e];
+    v += __shfl_xor(v, 1, 64);
+    v += __shfl_xor(v, 2, 64);
+    v += __shfl_xor(v, 4, 64);
+    v += __shfl_xor(v, 8, 64);
+    o[e] = v;
+  }
+  const float lw = wave_sum(l_run);
+  if (lane == 0) {
+    sm_m[wave] = m_run;
+    sm_l[wave] = lw;
+  }
+  if (r == 0) {
+#pragma unroll
+    for (int u = 0; u < NU; ++u)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sm_o[wave * DH + 32 * u + 8 * q4 + e] = o[8 * u + e];
+  }
+  merge_and_store<DH>(sm_m, sm_l, sm_o, a.out + (int64_t)seq * a.nh * DH + head * DH);
+}
+
+}  // namespace
+
+int decode_attention_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_stride, int32_t b,
+                            int32_t rows, const fg_kv_cache& kv, int32_t batch_offset, half_t* out,
+                            hipStream_t stream) {
+  if (b == 0) return FG_OK;
+  const int dh = cfg.h1 / cfg.nh;
+  AttnArgs a;
+  a.q = q;
+  a.q_stride = q_stride;
+  a.k_codes = reinterpret_cast<const uint8_t*>(kv.k_codes);
+  a.v_codes = reinterpret_cast<const uint8_t*>(kv.v_codes);
+  a.k_meta = reinterpret_cast<const float2*>(kv.k_meta);
+  a.v_meta = reinterpret_cast<const float2*>(kv.v_meta);
+  a.out = out;
+  a.nh = cfg.nh;
+  a.cap = kv.cap;
+  a.rows = rows;
+  a.batch_offset = batch_offset;
+  a.scale = 1.0f / sqrtf((float)dh);
+  const dim3 grid(cfg.nh, b);
+  ProfScope prof(FG_K_ATTN_DECODE, stream);
+  if (kv.dtype == FG_Q4G64) {
+    if (dh == 128)
+      hipLaunchKernelGGL(attn_decode_q4_kernel<128>, grid, dim3(256), 0, stream, a);
+    else
+      hipLaunchKernelGGL(attn_decode_q4_kernel<64>, grid, dim3(256), 0, stream, a);
+  } else {
+    if (dh == 128)
+      hipLaunchKernelGGL(attn_decode_f16_kernel<128>, grid, dim3(256), 0, stream, a);
+    else
+      hipLaunchKernelGGL(attn_decode_f16_kernel<64>, grid, dim3(256), 0, stream, a);
+  }
+  FG_LAUNCH_CHECK();
+  return FG_OK;
+}
+
+}  // namespace fg
+
+using namespace fg;
+
+extern "C" int fg_decode_attention(const fg_model_cfg* cfg, const void* q_f16, int64_t q_row_stride, int32_t b,
+                                   int32_t rows, const fg_kv_cache* kv, int32_t batch_offset, void* out_f16,
+                                   void* stream) {
+  if (!cfg || !kv) return FG_ERR_NULL;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  rc = check_kv(cfg, kv);
+  if (rc) return rc;
+  if (b < 0 || rows < 1 || rows > kv->cap || batch_offset < 0 || (int64_t)batch_offset + b > kv->batch)
+    return FG_ERR_SHAPE;
+  if (q_row_stride < cfg->h1 || q_row_stride % 8 != 0) return FG_ERR_SHAPE;
+  if (b == 0) return FG_OK;
+  if (!q_f16 || !out_f16) return FG_ERR_NULL;
+  return decode_attention_launch(*cfg, reinterpret_cast<const half_t*>(q_f16), q_row_stride, b, rows, *kv,
+                                 batch_offset, reinterpret_cast<half_t*>(out_f16), as_stream(stream));
+}

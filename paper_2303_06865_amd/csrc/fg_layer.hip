@@ -1,0 +1,567 @@
+// Host side of the library: argument validation, the linear dispatcher, one transformer layer in
+// its prefill and decode forms (Section 3), and the block-schedule driver (Section 4.2,
+// Algorithm 1) that generates n tokens for a block of GPU batches.
+#include <math.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "fg_common.h"
+
+namespace fg {
+
+// ---------------------------------------------------------------- errors, profile
+static thread_local std::string g_dev_err;
+
+void set_device_error(hipError_t e, const char* what) {
+  g_dev_err = std::string(hipGetErrorString(e)) + " in " + what;
+}
+
+struct ProfRec {
+  int k;
+  hipEvent_t e0, e1;
+};
+static bool g_prof_on = false;
+static std::vector<ProfRec> g_prof_open;
+static double g_prof_ms[FG_K_COUNT];
+static int64_t g_prof_n[FG_K_COUNT];
+
+bool profile_enabled() { return g_prof_on; }
+
+void profile_mark(int kclass, hipStream_t stream, bool begin) {
+  if (begin) {
+    ProfRec r;
+    r.k = kclass;
+    if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return;
+    (void)hipEventRecord(r.e0, stream);
+    g_prof_open.push_back(r);
+  } else {
+    // scopes never nest across kernel classes: the most recent open record of this class
+    for (size_t i = g_prof_open.size(); i-- > 0;) {
+      if (g_prof_open[i].k == kclass) {
+        (void)hipEventRecord(g_prof_open[i].e1, stream);
+        break;
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------- validation
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_cfg(const fg_model_cfg* c) {
+  if (c->h1 <= 0 || c->nh <= 0 || c->h2 <= 0 || c->vocab <= 0 || c->max_pos <= 0) return FG_ERR_SHAPE;
+  if (c->h1 % c->nh != 0) return FG_ERR_SHAPE;
+  const int dh = c->h1 / c->nh;
+  if (dh != 64 && dh != 128) return FG_ERR_UNSUPPORTED;
+  if (c->h1 % kGroup != 0 || c->h2 % kGroup != 0) return FG_ERR_SHAPE;
+  if (!(c->ln_eps > 0.f)) return FG_ERR_SHAPE;
+  return FG_OK;
+}
+
+int check_mat(const fg_mat* w) {
+  if (w->dtype != FG_F16 && w->dtype != FG_Q4G64) return FG_ERR_UNSUPPORTED;
+  if (w->rows <= 0 || w->cols <= 0 || w->cols % kGroup != 0 || w->rows % 8 != 0) return FG_ERR_SHAPE;
+  if (w->rows > 0x7fffffff || w->cols > 0x7fffffff) return FG_ERR_SHAPE;
+  if (!w->data) return FG_ERR_NULL;
+  if (w->dtype == FG_Q4G64 && !w->meta) return FG_ERR_NULL;
+  if (!aligned16(w->data) || (w->meta && !aligned16(w->meta))) return FG_ERR_SHAPE;
+  return FG_OK;
+}
+
+int check_kv(const fg_model_cfg* cfg, const fg_kv_cache* kv) {
+  (void)cfg;
+  if (kv->dtype != FG_F16 && kv->dtype != FG_Q4G64) return FG_ERR_UNSUPPORTED;
+  if (kv->batch <= 0 || kv->cap <= 0) return FG_ERR_SHAPE;
+  if (!kv->k_codes || !kv->v_codes) return FG_ERR_NULL;
+  if (kv->dtype == FG_Q4G64 && (!kv->k_meta || !kv->v_meta)) return FG_ERR_NULL;
+  if (!aligned16(kv->k_codes) || !aligned16(kv->v_codes)) return FG_ERR_SHAPE;
+  if (kv->dtype == FG_Q4G64 && (!aligned16(kv->k_meta) || !aligned16(kv->v_meta))) return FG_ERR_SHAPE;
+  return FG_OK;
+}
+
+static int check_layer(const fg_model_cfg* cfg, const fg_layer_weights* w) {
+  int rc;
+  if ((rc = check_mat(&w->wqkv)) || (rc = check_mat(&w->wo)) || (rc = check_mat(&w->w1)) ||
+      (rc = check_mat(&w->w2)))
+    return rc;
+  const int64_t h1 = cfg->h1, h2 = cfg->h2;
+  if (w->wqkv.rows != 3 * h1 || w->wqkv.cols != h1 || w->wo.rows != h1 || w->wo.cols != h1 ||
+      w->w1.rows != h2 || w->w1.cols != h1 || w->w2.rows != h1 || w->w2.cols != h2)
+    return FG_ERR_SHAPE;
+  if (!w->ln1_g || !w->ln1_b || !w->ln2_g || !w->ln2_b) return FG_ERR_NULL;
+  return FG_OK;
+}
+
+// ---------------------------------------------------------------- linear dispatch
+static const int64_t kSmallMLimit = 512;   // rows up to which the weight-streaming kernel is used
+
+size_t linear_workspace_bytes(int dtype, int64_t n, int64_t k, int64_t m) {
+  if (m <= kSmallMLimit) return gemm_small_m_workspace(dtype, n, k, m);
+  return 0;
+}
+
+int linear_launch(const LinearArgs& a, void* ws, size_t ws_bytes, hipStream_t stream) {
+  if (a.m <= kSmallMLimit) return gemm_small_m_launch(a, ws, ws_bytes, stream);
+  return gemm_large_m_launch(a, stream);
+}
+
+static LinearArgs make_linear(const fg_mat& w, const void* bias, const half_t* x, int64_t ldx, int64_t m,
+                              const half_t* residual, int64_t ldr, int relu, half_t* out, int64_t ldo) {
+  LinearArgs a;
+  a.w_data = w.data;
+  a.w_meta = w.meta;
+  a.dtype = w.dtype;
+  a.n = w.rows;
+  a.k = w.cols;
+  a.x = x;
+  a.ldx = ldx;
+  a.m = m;
+  a.bias = reinterpret_cast<const half_t*>(bias);
+  a.residual = residual;
+  a.ldr = ldr;
+  a.relu = relu;
+  a.out_f16 = out;
+  a.out_f32 = nullptr;
+  a.ldo = ldo;
+  return a;
+}
+
+// ---------------------------------------------------------------- one layer
+struct LayerWs {
+  half_t *y, *qkv, *o, *x1, *act;
+  void* gemm;
+  size_t gemm_bytes;
+  size_t total;
+};
+
+static size_t layer_gemm_ws(const fg_model_cfg& c, const fg_layer_weights& w, int64_t rows) {
+  size_t g = linear_workspace_bytes(w.wqkv.dtype, 3 * (int64_t)c.h1, c.h1, rows);
+  size_t t = linear_workspace_bytes(w.wo.dtype, c.h1, c.h1, rows);
+  g = t > g ? t : g;
+  t = linear_workspace_bytes(w.w1.dtype, c.h2, c.h1, rows);
+  g = t > g ? t : g;
+  t = linear_workspace_bytes(w.w2.dtype, c.h1, c.h2, rows);
+  return t > g ? t : g;
+}
+
+static LayerWs carve_layer_ws(const fg_model_cfg& c, const fg_layer_weights& w, int64_t rows, void* base) {
+  LayerWs L;
+  unsigned char* p = reinterpret_cast<unsigned char*>(base);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    unsigned char* r = p ? p + off : nullptr;
+    off += align_up(bytes, 256);
+    return r;
+  };
+  L.y = reinterpret_cast<half_t*>(take((size_t)rows * c.h1 * 2));
+  L.qkv = reinterpret_cast<half_t*>(take((size_t)rows * 3 * c.h1 * 2));
+  L.o = reinterpret_cast<half_t*>(take((size_t)rows * c.h1 * 2));
+  L.x1 = reinterpret_cast<half_t*>(take((size_t)rows * c.h1 * 2));
+  L.act = reinterpret_cast<half_t*>(take((size_t)rows * c.h2 * 2));
+  L.gemm_bytes = layer_gemm_ws(c, w, rows);
+  L.gemm = take(L.gemm_bytes);
+  L.total = off;
+  return L;
+}
+
+// Section 3 with OPT's pre-LayerNorm placement.  prefill: s > 0 rows per sequence, causal attention
+// over the fresh K/V, rows stored at 0..s-1.  decode: one row per sequence, K/V appended at row t,
+// attention over rows 0..t read back from the cache.
+static int run_layer(const fg_model_cfg& c, const fg_layer_weights& w, const half_t* x_in, int32_t b, int32_t s,
+                     bool prefill, int32_t t, const fg_kv_cache& kv, int32_t batch_offset, half_t* x_out,
+                     void* ws, hipStream_t st) {
+  const int64_t rows = (int64_t)b * (prefill ? s : 1);
+  const int64_t h1 = c.h1, h2 = c.h2;
+  LayerWs L = carve_layer_ws(c, w, rows, ws);
+  int rc;
+  if ((rc = layernorm_launch(x_in, h1, reinterpret_cast<const half_t*>(w.ln1_g),
+                             reinterpret_cast<const half_t*>(w.ln1_b), rows, h1, c.ln_eps, L.y, h1, st)))
+    return rc;
+  if ((rc = linear_launch(make_linear(w.wqkv, w.bqkv, L.y, h1, rows, nullptr, 0, 0, L.qkv, 3 * h1), L.gemm,
+                          L.gemm_bytes, st)))
+    return rc;
+  if (prefill) {
+    if ((rc = prefill_attention_launch(c, L.qkv, b, s, L.o, st))) return rc;
+    if ((rc = kv_append_launch(c, L.qkv + h1, L.qkv + 2 * h1, 3 * h1, b, s, kv, batch_offset, 0, st))) return rc;
+  } else {
+    if ((rc = kv_append_launch(c, L.qkv + h1, L.qkv + 2 * h1, 3 * h1, b, 1, kv, batch_offset, t, st))) return rc;
+    if ((rc = decode_attention_launch(c, L.qkv, 3 * h1, b, t + 1, kv, batch_offset, L.o, st))) return rc;
+  }
+  if ((rc = linear_launch(make_linear(w.wo, w.bo, L.o, h1, rows, x_in, h1, 0, L.x1, h1), L.gemm, L.gemm_bytes,
+                          st)))
+    return rc;
+  if ((rc = layernorm_launch(L.x1, h1, reinterpret_cast<const half_t*>(w.ln2_g),
+                             reinterpret_cast<const half_t*>(w.ln2_b), rows, h1, c.ln_eps, L.y, h1, st)))
+    return rc;
+  if ((rc = linear_launch(make_linear(w.w1, w.b1, L.y, h1, rows, nullptr, 0, 1, L.act, h2), L.gemm,
+                          L.gemm_bytes, st)))
+    return rc;
+  return linear_launch(make_linear(w.w2, w.b2, L.act, h2, rows, L.x1, h1, 0, x_out, h1), L.gemm, L.gemm_bytes,
+                       st);
+}
+
+// ---------------------------------------------------------------- LM head
+struct HeadWs {
+  half_t* y;
+  void* gemm;
+  size_t gemm_bytes;
+  size_t total;
+};
+static HeadWs carve_head_ws(const fg_model_cfg& c, int64_t rows, void* base) {
+  HeadWs H;
+  unsigned char* p = reinterpret_cast<unsigned char*>(base);
+  const size_t ybytes = align_up((size_t)rows * c.h1 * 2, 256);
+  H.y = reinterpret_cast<half_t*>(p);
+  H.gemm_bytes = linear_workspace_bytes(FG_F16, c.vocab, c.h1, rows);
+  H.gemm = p ? p + ybytes : nullptr;
+  H.total = ybytes + align_up(H.gemm_bytes, 256);
+  return H;
+}
+
+static int run_lm_head(const fg_model_cfg& c, const half_t* x, int64_t ldx, int64_t rows, const half_t* g,
+                       const half_t* bta, const half_t* emb, int32_t* out_ids, int64_t out_stride, float* logits,
+                       void* ws, hipStream_t st) {
+  HeadWs H = carve_head_ws(c, rows, ws);
+  int rc;
+  if ((rc = layernorm_launch(x, ldx, g, bta, rows, c.h1, c.ln_eps, H.y, c.h1, st))) return rc;
+  LinearArgs a;
+  a.w_data = emb;
+  a.w_meta = nullptr;
+  a.dtype = FG_F16;
+  a.n = c.vocab;
+  a.k = c.h1;
+  a.x = H.y;
+  a.ldx = c.h1;
+  a.m = rows;
+  a.bias = nullptr;
+  a.residual = nullptr;
+  a.ldr = 0;
+  a.relu = 0;
+  a.out_f16 = nullptr;
+  a.out_f32 = logits;
+  a.ldo = c.vocab;
+  if ((rc = linear_launch(a, H.gemm, H.gemm_bytes, st))) return rc;
+  return argmax_launch(logits, rows, c.vocab, out_ids, out_stride, st);
+}
+
+}  // namespace fg
+
+using namespace fg;
+
+// ================================================================ C ABI
+extern "C" const char* fg_error_string(int status) {
+  switch (status) {
+    case FG_OK: return "ok";
+    case FG_ERR_NULL: return "a required pointer is NULL";
+    case FG_ERR_SHAPE: return "bad shape, size or alignment";
+    case FG_ERR_UNSUPPORTED: return "unsupported format (only 4-bit codes, groups of 64, head size 64 or 128)";
+    case FG_ERR_WORKSPACE: return "workspace missing or too small";
+    case FG_ERR_DEVICE: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+extern "C" const char* fg_last_device_error(void) { return g_dev_err.c_str(); }
+
+extern "C" int fg_version(void) { return 100; }
+
+extern "C" const char* fg_kernel_class_name(int k) {
+  static const char* names[FG_K_COUNT] = {"quantize",      "dequantize",          "layernorm",    "gemm_small_m",
+                                          "gemm_small_m_finish", "gemm_large_m",  "kv_append",    "attn_decode",
+                                          "attn_prefill",  "embed",               "argmax"};
+  return (k >= 0 && k < FG_K_COUNT) ? names[k] : "?";
+}
+
+extern "C" int fg_profile_begin(void) {
+  for (auto& r : g_prof_open) {
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+  }
+  g_prof_open.clear();
+  memset(g_prof_ms, 0, sizeof(g_prof_ms));
+  memset(g_prof_n, 0, sizeof(g_prof_n));
+  g_prof_on = true;
+  return FG_OK;
+}
+
+extern "C" int fg_profile_end(void) {
+  g_prof_on = false;
+  int rc = FG_OK;
+  for (auto& r : g_prof_open) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.e1) == hipSuccess && hipEventElapsedTime(&ms, r.e0, r.e1) == hipSuccess) {
+      g_prof_ms[r.k] += ms;
+      g_prof_n[r.k] += 1;
+    } else {
+      rc = FG_ERR_DEVICE;
+    }
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+  }
+  g_prof_open.clear();
+  return rc;
+}
+
+extern "C" int fg_profile_read(int k, double* total_ms, int64_t* launches) {
+  if (k < 0 || k >= FG_K_COUNT) return FG_ERR_SHAPE;
+  if (total_ms) *total_ms = g_prof_ms[k];
+  if (launches) *launches = g_prof_n[k];
+  return FG_OK;
+}
+
+extern "C" size_t fg_linear_workspace_bytes(const fg_mat* w, int64_t m) {
+  if (!w || m <= 0) return 0;
+  return linear_workspace_bytes(w->dtype, w->rows, w->cols, m);
+}
+
+extern "C" int fg_linear(const fg_mat* w, const void* bias_f16, const void* x_f16, int64_t m,
+                         const void* residual_f16, int relu, void* out_f16, void* ws, size_t ws_bytes,
+                         void* stream) {
+  if (!w) return FG_ERR_NULL;
+  int rc = check_mat(w);
+  if (rc) return rc;
+  if (m < 0 || m > 0x7fffffff) return FG_ERR_SHAPE;
+  if (m == 0) return FG_OK;
+  if (!x_f16 || !out_f16) return FG_ERR_NULL;
+  if (!aligned16(x_f16) || !aligned16(out_f16)) return FG_ERR_SHAPE;
+  const size_t need = linear_workspace_bytes(w->dtype, w->rows, w->cols, m);
+  if (need && (!ws || ws_bytes < need)) return FG_ERR_WORKSPACE;
+  return linear_launch(make_linear(*w, bias_f16, reinterpret_cast<const half_t*>(x_f16), w->cols, m,
+                                   reinterpret_cast<const half_t*>(residual_f16), w->rows, relu,
+                                   reinterpret_cast<half_t*>(out_f16), w->rows),
+                       ws, ws_bytes, as_stream(stream));
+}
+
+extern "C" size_t fg_lm_head_workspace_bytes(const fg_model_cfg* cfg, int64_t rows) {
+  if (!cfg || rows <= 0 || check_cfg(cfg)) return 0;
+  return carve_head_ws(*cfg, rows, nullptr).total;
+}
+
+extern "C" int fg_lm_head_greedy(const fg_model_cfg* cfg, const void* x_f16, int64_t x_row_stride, int64_t rows,
+                                 const void* lnf_g, const void* lnf_b, const void* embed_f16, int32_t* out_ids,
+                                 int64_t out_stride, float* logits_f32, void* ws, size_t ws_bytes,
+                                 void* stream) {
+  if (!cfg) return FG_ERR_NULL;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if (rows < 0 || rows > 0x7fffffff || x_row_stride < cfg->h1 || x_row_stride % 8 != 0 || out_stride < 1)
+    return FG_ERR_SHAPE;
+  if (cfg->vocab % 8 != 0) return FG_ERR_SHAPE;
+  if (rows == 0) return FG_OK;
+  if (!x_f16 || !lnf_g || !lnf_b || !embed_f16 || !out_ids || !logits_f32) return FG_ERR_NULL;
+  if (!ws || ws_bytes < carve_head_ws(*cfg, rows, nullptr).total) return FG_ERR_WORKSPACE;
+  return run_lm_head(*cfg, reinterpret_cast<const half_t*>(x_f16), x_row_stride, rows,
+                     reinterpret_cast<const half_t*>(lnf_g), reinterpret_cast<const half_t*>(lnf_b),
+                     reinterpret_cast<const half_t*>(embed_f16), out_ids, out_stride, logits_f32, ws,
+                     as_stream(stream));
+}
+
+extern "C" size_t fg_layer_workspace_bytes(const fg_model_cfg* cfg, const fg_layer_weights* wts, int64_t rows) {
+  if (!cfg || !wts || rows <= 0 || check_cfg(cfg)) return 0;
+  return carve_layer_ws(*cfg, *wts, rows, nullptr).total;
+}
+
+static int check_layer_call(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in,
+                            const fg_kv_cache* kv, void* x_out) {
+  if (!cfg || !wts || !kv) return FG_ERR_NULL;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if ((rc = check_layer(cfg, wts))) return rc;
+  if ((rc = check_kv(cfg, kv))) return rc;
+  (void)x_in;
+  (void)x_out;
+  return FG_OK;
+}
+
+extern "C" int fg_prefill_layer(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in, int32_t b,
+                                int32_t s, const fg_kv_cache* kv, int32_t batch_offset, void* x_out, void* ws,
+                                size_t ws_bytes, void* stream) {
+  int rc = check_layer_call(cfg, wts, x_in, kv, x_out);
+  if (rc) return rc;
+  if (b < 0 || s < 0 || batch_offset < 0 || b > 65535) return FG_ERR_SHAPE;
+  if ((int64_t)batch_offset + b > kv->batch || s > kv->cap) return FG_ERR_SHAPE;
+  if ((int64_t)b * s > 0x7fffffff) return FG_ERR_SHAPE;
+  if (b == 0 || s == 0) return FG_OK;
+  if (!x_in || !x_out) return FG_ERR_NULL;
+  if (!aligned16(x_in) || !aligned16(x_out)) return FG_ERR_SHAPE;
+  const size_t need = carve_layer_ws(*cfg, *wts, (int64_t)b * s, nullptr).total;
+  if (!ws || ws_bytes < need) return FG_ERR_WORKSPACE;
+  if (!aligned16(ws)) return FG_ERR_SHAPE;
+  return run_layer(*cfg, *wts, reinterpret_cast<const half_t*>(x_in), b, s, true, 0, *kv, batch_offset,
+                   reinterpret_cast<half_t*>(x_out), ws, as_stream(stream));
+}
+
+extern "C" int fg_decode_layer(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in, int32_t b,
+                               int32_t t, const fg_kv_cache* kv, int32_t batch_offset, void* x_out, void* ws,
+                               size_t ws_bytes, void* stream) {
+  int rc = check_layer_call(cfg, wts, x_in, kv, x_out);
+  if (rc) return rc;
+  if (b < 0 || t < 0 || batch_offset < 0 || b > 65535) return FG_ERR_SHAPE;
+  if ((int64_t)batch_offset + b > kv->batch || t >= kv->cap) return FG_ERR_SHAPE;
+  if (b == 0) return FG_OK;
+  if (!x_in || !x_out) return FG_ERR_NULL;
+  if (!aligned16(x_in) || !aligned16(x_out)) return FG_ERR_SHAPE;
+  const size_t need = carve_layer_ws(*cfg, *wts, b, nullptr).total;
+  if (!ws || ws_bytes < need) return FG_ERR_WORKSPACE;
+  if (!aligned16(ws)) return FG_ERR_SHAPE;
+  return run_layer(*cfg, *wts, reinterpret_cast<const half_t*>(x_in), b, 1, false, t, *kv, batch_offset,
+                   reinterpret_cast<half_t*>(x_out), ws, as_stream(stream));
+}
+
+// ---------------------------------------------------------------- block generation
+namespace {
+struct GenWs {
+  half_t* x_all;    // [bls*s, h1] prefill activations of the whole block
+  half_t* x_dec;    // [bls, h1]
+  float* logits;    // [bls, vocab]
+  void* layer;      // per-layer scratch (max of prefill GPU batch and decode block)
+  size_t layer_bytes;
+  void* head;
+  size_t head_bytes;
+  size_t total;
+};
+GenWs carve_gen_ws(const fg_model_cfg& c, const fg_layer_weights& w0, int32_t gbs, int32_t ngb, int32_t s,
+                   void* base) {
+  GenWs G;
+  unsigned char* p = reinterpret_cast<unsigned char*>(base);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    unsigned char* r = p ? p + off : nullptr;
+    off += align_up(bytes, 256);
+    return r;
+  };
+  const int64_t bls = (int64_t)gbs * ngb;
+  G.x_all = reinterpret_cast<half_t*>(take((size_t)bls * s * c.h1 * 2));
+  G.x_dec = reinterpret_cast<half_t*>(take((size_t)bls * c.h1 * 2));
+  G.logits = reinterpret_cast<float*>(take((size_t)bls * c.vocab * 4));
+  const size_t lp = carve_layer_ws(c, w0, (int64_t)gbs * s, nullptr).total;
+  const size_t ld = carve_layer_ws(c, w0, bls, nullptr).total;
+  G.layer_bytes = lp > ld ? lp : ld;
+  G.layer = take(G.layer_bytes);
+  G.head_bytes = carve_head_ws(c, bls, nullptr).total;
+  G.head = take(G.head_bytes);
+  G.total = off;
+  return G;
+}
+}  // namespace
+
+extern "C" size_t fg_workspace_bytes(const fg_model_cfg* cfg, const fg_layer_weights* layer0, int32_t gpu_batch_size,
+                                     int32_t num_gpu_batches, int32_t s) {
+  if (!cfg || !layer0 || gpu_batch_size <= 0 || num_gpu_batches <= 0 || s <= 0 || check_cfg(cfg)) return 0;
+  return carve_gen_ws(*cfg, *layer0, gpu_batch_size, num_gpu_batches, s, nullptr).total;
+}
+
+extern "C" int fg_generate(const fg_model_cfg* cfg, int32_t l, const fg_layer_weights* layers,
+                           const void* embed_f16, const void* pos_f16, const void* lnf_g, const void* lnf_b,
+                           const int32_t* prompt, int32_t s, int32_t n, int32_t num_gpu_batches,
+                           int32_t gpu_batch_size, const fg_kv_cache* kv, int32_t* out_ids, void* ws,
+                           size_t ws_bytes, void* stream, fg_stats* stats) {
+  if (!cfg || !layers || !kv) return FG_ERR_NULL;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if (l <= 0 || s <= 0 || n <= 0 || num_gpu_batches <= 0 || gpu_batch_size <= 0) return FG_ERR_SHAPE;
+  const int64_t bls64 = (int64_t)num_gpu_batches * gpu_batch_size;
+  if (bls64 > 65535 || (int64_t)gpu_batch_size * s > 0x7fffffff) return FG_ERR_SHAPE;
+  if ((int64_t)s + n - 1 > cfg->max_pos || cfg->vocab % 8 != 0) return FG_ERR_SHAPE;
+  const int32_t bls = (int32_t)bls64;
+  for (int j = 0; j < l; ++j) {
+    if ((rc = check_layer(cfg, &layers[j]))) return rc;
+    if ((rc = check_kv(cfg, &kv[j]))) return rc;
+    if (kv[j].batch < bls || kv[j].cap < s + n - 1) return FG_ERR_SHAPE;
+    // one scratch size serves all layers: they must share the storage format of layer 0
+    if (layers[j].wqkv.dtype != layers[0].wqkv.dtype || layers[j].wo.dtype != layers[0].wo.dtype ||
+        layers[j].w1.dtype != layers[0].w1.dtype || layers[j].w2.dtype != layers[0].w2.dtype)
+      return FG_ERR_UNSUPPORTED;
+  }
+  if (!embed_f16 || !pos_f16 || !lnf_g || !lnf_b || !prompt || !out_ids) return FG_ERR_NULL;
+  const GenWs need = carve_gen_ws(*cfg, layers[0], gpu_batch_size, num_gpu_batches, s, nullptr);
+  if (!ws || ws_bytes < need.total) return FG_ERR_WORKSPACE;
+  if (!aligned16(ws)) return FG_ERR_SHAPE;
+  const GenWs G = carve_gen_ws(*cfg, layers[0], gpu_batch_size, num_gpu_batches, s, ws);
+  hipStream_t st = as_stream(stream);
+  const half_t* emb = reinterpret_cast<const half_t*>(embed_f16);
+  const half_t* pos = reinterpret_cast<const half_t*>(pos_f16);
+  const half_t* fg_ = reinterpret_cast<const half_t*>(lnf_g);
+  const half_t* fb_ = reinterpret_cast<const half_t*>(lnf_b);
+  const int64_t h1 = cfg->h1;
+
+  std::vector<hipEvent_t> ev;
+  auto mark = [&]() -> int {
+    if (!stats) return FG_OK;
+    hipEvent_t e;
+    FG_HIP(hipEventCreate(&e));
+    FG_HIP(hipEventRecord(e, st));
+    ev.push_back(e);
+    return FG_OK;
+  };
+  auto cleanup = [&]() {
+    for (auto e : ev) (void)hipEventDestroy(e);
+  };
+#define FG_TRY(expr)       \
+  do {                     \
+    int _rc = (expr);      \
+    if (_rc) {             \
+      cleanup();           \
+      return _rc;          \
+    }                      \
+  } while (0)
+
+  // ---- token step 1: prefill.  Layer outermost, GPU batch innermost (zig-zag block schedule):
+  // all GPU batches pass through layer j before layer j+1 is touched.
+  FG_TRY(mark());
+  FG_TRY(embed_launch(emb, pos, prompt, 1, (int64_t)bls * s, s, 0, cfg->h1, cfg->vocab, G.x_all, st));
+  for (int j = 0; j < l; ++j) {
+    for (int k = 0; k < num_gpu_batches; ++k) {
+      half_t* xk = G.x_all + (int64_t)k * gpu_batch_size * s * h1;
+      FG_TRY(run_layer(*cfg, layers[j], xk, gpu_batch_size, s, true, 0, kv[j], k * gpu_batch_size, xk, G.layer,
+                       st));
+    }
+  }
+  FG_TRY(run_lm_head(*cfg, G.x_all + (int64_t)(s - 1) * h1, (int64_t)s * h1, bls, fg_, fb_, emb, out_ids, n,
+                     G.logits, G.head, st));
+  FG_TRY(mark());
+  // ---- token steps 2..n: decode.  Every layer takes all bls rows in one pass, so its weights are
+  // streamed from HBM once per step for the whole block.
+  for (int i = 1; i < n; ++i) {
+    const int t = s + i - 1;   // rows already cached = absolute position of the token fed back
+    FG_TRY(embed_launch(emb, pos, out_ids + (i - 1), n, bls, 1, t, cfg->h1, cfg->vocab, G.x_dec, st));
+    for (int j = 0; j < l; ++j)
+      FG_TRY(run_layer(*cfg, layers[j], G.x_dec, bls, 1, false, t, kv[j], 0, G.x_dec, G.layer, st));
+    FG_TRY(run_lm_head(*cfg, G.x_dec, h1, bls, fg_, fb_, emb, out_ids + i, n, G.logits, G.head, st));
+    FG_TRY(mark());
+  }
+#undef FG_TRY
+
+  if (stats) {
+    if (hipEventSynchronize(ev.back()) != hipSuccess) {
+      cleanup();
+      return FG_ERR_DEVICE;
+    }
+    float ms = 0.f;
+    (void)hipEventElapsedTime(&ms, ev[0], ev[1]);
+    stats->prefill_s = ms * 1e-3;
+    double dec = 0.0;
+    for (int i = 1; i < n; ++i) {
+      (void)hipEventElapsedTime(&ms, ev[i], ev[i + 1]);
+      dec += ms * 1e-3;
+      if (stats->decode_step_s) stats->decode_step_s[i - 1] = ms * 1e-3;
+    }
+    stats->decode_s = dec;
+    stats->tokens = (int64_t)bls * n;
+    auto mat_bytes = [](const fg_mat& m) -> int64_t {
+      const int64_t e = m.rows * m.cols;
+      return m.dtype == FG_Q4G64 ? e / 2 + e / kGroup * 8 : e * 2;
+    };
+    int64_t wb = 0;
+    for (int j = 0; j < l; ++j)
+      wb += mat_bytes(layers[j].wqkv) + mat_bytes(layers[j].wo) + mat_bytes(layers[j].w1) + mat_bytes(layers[j].w2);
+    stats->weight_bytes_per_step = wb;
+    const int64_t rows_last = (int64_t)s + n - 1;
+    const int64_t el = 2 * (int64_t)bls * l * h1 * (n > 1 ? rows_last : 0);
+    stats->kv_bytes_last_step = kv[0].dtype == FG_Q4G64 ? el / 2 + el / kGroup * 8 : el * 2;
+    cleanup();
+  }
+  return FG_OK;
+}

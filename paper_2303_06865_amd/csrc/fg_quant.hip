@@ -1,0 +1,235 @@
+// Group-wise 4-bit asymmetric quantization (Section 5 of the paper): quantizer, inverse map,
+// and the KV-cache append that stores new token rows in the compressed layout.
+//
+// This file is compiled with -ffp-contract=off: codes and {min, scale} must be bit-exact
+// functions of the input (binary32, one rounding per operation, IEEE division).
+#include "fg_common.h"
+
+namespace fg {
+
+// Eight lanes cooperate on one group of 64 FP16 values (16 bytes per lane), so a wavefront
+// covers eight groups per pass: 1 KiB of coalesced input, 256 B of codes, 64 B of meta.
+__device__ __forceinline__ void quantize_group_8lanes(const h8_t v, int sub, uint32_t& packed,
+                                                      float& mn_out, float& scale_out) {
+  float x[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) x[i] = (float)v[i];
+  float mn = x[0], mx = x[0];
+#pragma unroll
+  for (int i = 1; i < 8; ++i) {
+    mn = fminf(mn, x[i]);
+    mx = fmaxf(mx, x[i]);
+  }
+#pragma unroll
+  for (int o = 1; o < 8; o <<= 1) {
+    mn = fminf(mn, __shfl_xor(mn, o, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  }
+  const float range = mx - mn;
+  const float scale = range / 15.0f;  // IEEE-rounded division (see build flags)
+  uint32_t p = 0;
+  if (scale > 0.0f) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float t = (x[i] - mn) / scale;
+      float r = rintf(t);  // ties to even
+      r = fminf(fmaxf(r, 0.0f), 15.0f);
+      p |= ((uint32_t)(int)r) << (4 * i);
+    }
+  }
+  packed = p;
+  mn_out = mn;
+  scale_out = scale;
+  (void)sub;
+}
+
+// Plain layout: x [rows, cols] contiguous -> codes [rows, cols/2], meta [rows, cols/64].
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const half_t* __restrict__ x,
+                                                            int64_t n_groups,
+                                                            uint32_t* __restrict__ codes,
+                                                            float2* __restrict__ meta) {
+  const int sub = threadIdx.x & 7;
+  int64_t g = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 3;
+  const int64_t stride = ((int64_t)gridDim.x * blockDim.x) >> 3;
+  for (; g < n_groups; g += stride) {  // uniform per 8-lane team, so shuffles stay converged
+    const h8_t v = *reinterpret_cast<const h8_t*>(x + g * kGroup + sub * 8);
+    uint32_t p;
+    float mn, sc;
+    quantize_group_8lanes(v, sub, p, mn, sc);
+    codes[g * 8 + sub] = p;
+    if (sub == 0) meta[g] = make_float2(mn, sc);
+  }
+}
+
+__global__ __launch_bounds__(256) void dequantize_rows_kernel(const uint32_t* __restrict__ codes,
+                                                              const float2* __restrict__ meta,
+                                                              int64_t n_words,
+                                                              float* __restrict__ out) {
+  int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; w < n_words; w += stride) {
+    const uint32_t p = codes[w];
+    const float2 m = meta[w >> 3];
+    float4 lo, hi;
+    float* o = reinterpret_cast<float*>(&lo);
+    float* o2 = reinterpret_cast<float*>(&hi);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[i] = __fadd_rn(m.x, __fmul_rn((float)((p >> (4 * i)) & 15u), m.y));
+      o2[i] = __fadd_rn(m.x, __fmul_rn((float)((p >> (4 * i + 16)) & 15u), m.y));
+    }
+    reinterpret_cast<float4*>(out)[w * 2] = lo;
+    reinterpret_cast<float4*>(out)[w * 2 + 1] = hi;
+  }
+}
+
+// Cache layout: token rows x [b*s, h1] (row stride `ld` elements) -> cache [batch, nh, cap, dh].
+// z = 0 stores K, z = 1 stores V.
+struct KvAppendArgs {
+  const half_t* src[2];
+  void* codes[2];
+  void* meta[2];
+  int64_t ld;
+  int32_t b, s, nh, dh, cap, batch_offset, pos0;
+};
+
+__global__ __launch_bounds__(256) void kv_append_q4_kernel(KvAppendArgs a) {
+  const int which = blockIdx.y;
+  const half_t* __restrict__ x = a.src[which];
+  uint32_t* __restrict__ codes = reinterpret_cast<uint32_t*>(a.codes[which]);
+  float2* __restrict__ meta = reinterpret_cast<float2*>(a.meta[which]);
+  const int gph = a.dh / kGroup;              // groups per head
+  const int gpr = a.nh * gph;                 // groups per token row
+  const int64_t n_groups = (int64_t)a.b * a.s * gpr;
+  const int sub = threadIdx.x & 7;
+  int64_t g = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 3;
+  const int64_t stride = ((int64_t)gridDim.x * blockDim.x) >> 3;
+  for (; g < n_groups; g += stride) {
+    const int64_t row = g / gpr;
+    const int gi = (int)(g - row * gpr);
+    const int head = gi / gph, gh = gi - head * gph;
+    const int64_t bi = row / a.s;
+    const int pos = a.pos0 + (int)(row - bi * a.s);
+    const h8_t v = *reinterpret_cast<const h8_t*>(x + row * a.ld + (int64_t)gi * kGroup + sub * 8);
+    uint32_t p;
+    float mn, sc;
+    quantize_group_8lanes(v, sub, p, mn, sc);
+    const int64_t crow = (((int64_t)(a.batch_offset + bi) * a.nh + head) * a.cap + pos);
+    codes[(crow * gph + gh) * 8 + sub] = p;
+    if (sub == 0) meta[crow * gph + gh] = make_float2(mn, sc);
+  }
+}
+
+__global__ __launch_bounds__(256) void kv_append_f16_kernel(KvAppendArgs a) {
+  const int which = blockIdx.y;
+  const half_t* __restrict__ x = a.src[which];
+  half_t* __restrict__ dst = reinterpret_cast<half_t*>(a.codes[which]);
+  const int cpr = a.nh * a.dh / 8;            // 16-byte chunks per token row
+  const int cph = a.dh / 8;
+  const int64_t n_chunks = (int64_t)a.b * a.s * cpr;
+  int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; c < n_chunks; c += stride) {
+    const int64_t row = c / cpr;
+    const int ci = (int)(c - row * cpr);
+    const int head = ci / cph, ch = ci - head * cph;
+    const int64_t bi = row / a.s;
+    const int pos = a.pos0 + (int)(row - bi * a.s);
+    const u4_t v = *reinterpret_cast<const u4_t*>(x + row * a.ld + (int64_t)ci * 8);
+    const int64_t crow = (((int64_t)(a.batch_offset + bi) * a.nh + head) * a.cap + pos);
+    *reinterpret_cast<u4_t*>(dst + crow * a.dh + ch * 8) = v;
+  }
+}
+
+static int grid_for(int64_t work_items, int per_block) {
+  int64_t blocks = ceil_div(work_items, per_block);
+  const int64_t cap = 256 * 64;  // enough to fill the chip many times over; loops cover the rest
+  if (blocks > cap) blocks = cap;
+  if (blocks < 1) blocks = 1;
+  return (int)blocks;
+}
+
+int kv_append_launch(const fg_model_cfg& cfg, const half_t* k, const half_t* v, int64_t row_stride,
+                     int32_t b, int32_t s, const fg_kv_cache& kv, int32_t batch_offset, int32_t pos0,
+                     hipStream_t stream) {
+  if (b == 0 || s == 0) return FG_OK;
+  KvAppendArgs a;
+  a.src[0] = k;
+  a.src[1] = v;
+  a.codes[0] = kv.k_codes;
+  a.codes[1] = kv.v_codes;
+  a.meta[0] = kv.k_meta;
+  a.meta[1] = kv.v_meta;
+  a.ld = row_stride;
+  a.b = b;
+  a.s = s;
+  a.nh = cfg.nh;
+  a.dh = cfg.h1 / cfg.nh;
+  a.cap = kv.cap;
+  a.batch_offset = batch_offset;
+  a.pos0 = pos0;
+  ProfScope prof(FG_K_KV_APPEND, stream);
+  if (kv.dtype == FG_Q4G64) {
+    const int64_t groups = (int64_t)b * s * cfg.h1 / kGroup;
+    dim3 grid(grid_for(groups, 32), 2);
+    hipLaunchKernelGGL(kv_append_q4_kernel, grid, dim3(256), 0, stream, a);
+  } else {
+    const int64_t chunks = (int64_t)b * s * cfg.h1 / 8;
+    dim3 grid(grid_for(chunks, 256), 2);
+    hipLaunchKernelGGL(kv_append_f16_kernel, grid, dim3(256), 0, stream, a);
+  }
+  FG_LAUNCH_CHECK();
+  return FG_OK;
+}
+
+}  // namespace fg
+
+using namespace fg;
+
+extern "C" int fg_quantize_groupwise(const void* x_f16, int64_t rows, int64_t cols, int group, int bits,
+                                     void* codes_out, void* meta_out, void* stream) {
+  if (group != kGroup || bits != 4) return FG_ERR_UNSUPPORTED;
+  if (rows < 0 || cols <= 0 || cols % kGroup != 0) return FG_ERR_SHAPE;
+  if (rows == 0) return FG_OK;
+  if (!x_f16 || !codes_out || !meta_out) return FG_ERR_NULL;
+  const int64_t groups = rows * (cols / kGroup);
+  hipStream_t st = as_stream(stream);
+  ProfScope prof(FG_K_QUANTIZE, st);
+  hipLaunchKernelGGL(quantize_rows_kernel, dim3(grid_for(groups, 32)), dim3(256), 0, st,
+                     reinterpret_cast<const half_t*>(x_f16), groups,
+                     reinterpret_cast<uint32_t*>(codes_out), reinterpret_cast<float2*>(meta_out));
+  FG_LAUNCH_CHECK();
+  return FG_OK;
+}
+
+extern "C" int fg_dequantize_groupwise(const void* codes, const void* meta, int64_t rows, int64_t cols,
+                                       void* out_f32, void* stream) {
+  if (rows < 0 || cols <= 0 || cols % kGroup != 0) return FG_ERR_SHAPE;
+  if (rows == 0) return FG_OK;
+  if (!codes || !meta || !out_f32) return FG_ERR_NULL;
+  const int64_t words = rows * cols / 8;
+  hipStream_t st = as_stream(stream);
+  ProfScope prof(FG_K_DEQUANTIZE, st);
+  hipLaunchKernelGGL(dequantize_rows_kernel, dim3(grid_for(words, 256)), dim3(256), 0, st,
+                     reinterpret_cast<const uint32_t*>(codes), reinterpret_cast<const float2*>(meta), words,
+                     reinterpret_cast<float*>(out_f32));
+  FG_LAUNCH_CHECK();
+  return FG_OK;
+}
+
+extern "C" int fg_kv_append(const fg_model_cfg* cfg, const void* k_f16, const void* v_f16,
+                            int64_t row_stride, int32_t b, int32_t s, const fg_kv_cache* kv,
+                            int32_t batch_offset, int32_t pos0, void* stream) {
+  if (!cfg || !kv) return FG_ERR_NULL;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  rc = check_kv(cfg, kv);
+  if (rc) return rc;
+  if (b < 0 || s < 0 || batch_offset < 0 || pos0 < 0) return FG_ERR_SHAPE;
+  if ((int64_t)batch_offset + b > kv->batch || (int64_t)pos0 + s > kv->cap) return FG_ERR_SHAPE;
+  if (row_stride < cfg->h1 || row_stride % 8 != 0) return FG_ERR_SHAPE;
+  if (b == 0 || s == 0) return FG_OK;
+  if (!k_f16 || !v_f16) return FG_ERR_NULL;
+  return kv_append_launch(*cfg, reinterpret_cast<const half_t*>(k_f16), reinterpret_cast<const half_t*>(v_f16),
+                          row_stride, b, s, *kv, batch_offset, pos0, as_stream(stream));
+}

@@ -1,0 +1,117 @@
+"""The C-ABI library loads, exports every symbol include/fg.h declares, and turns bad arguments
+into error codes on the host before anything touches a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2303_06865_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "fg.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fg_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = _declared()
+    assert "fg_quantize_groupwise" in names and "fg_prefill_layer" in names
+    assert "fg_decode_layer" in names and "fg_generate" in names
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), n
+        assert n in B.EXPORTS, "binding lacks " + n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_struct_sizes_match_the_header_layout():
+    assert C.sizeof(B.fg_mat) == 40
+    assert C.sizeof(B.fg_model_cfg) == 24
+    assert C.sizeof(B.fg_layer_weights) == 4 * 40 + 8 * 8
+    assert C.sizeof(B.fg_kv_cache) == 48
+    assert C.sizeof(B.fg_stats) == 48
+
+
+def test_error_strings_and_version():
+    L = B.lib()
+    assert L.fg_version() >= 100
+    assert L.fg_error_string(0) == b"ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert len(L.fg_error_string(code)) > 3
+    assert [L.fg_kernel_class_name(i).decode() for i in range(len(B.KERNEL_CLASSES))] == B.KERNEL_CLASSES
+
+
+def test_quantize_argument_errors_need_no_gpu():
+    L = B.lib()
+    p = C.c_void_p(16)   # never dereferenced: every call below fails validation first
+    assert L.fg_quantize_groupwise(p, 4, 128, 32, 4, p, p, None) == B.FG_ERR_UNSUPPORTED
+    assert L.fg_quantize_groupwise(p, 4, 128, 64, 3, p, p, None) == B.FG_ERR_UNSUPPORTED
+    assert L.fg_quantize_groupwise(p, 4, 96, 64, 4, p, p, None) == B.FG_ERR_SHAPE
+    assert L.fg_quantize_groupwise(p, -1, 128, 64, 4, p, p, None) == B.FG_ERR_SHAPE
+    assert L.fg_quantize_groupwise(None, 4, 128, 64, 4, p, p, None) == B.FG_ERR_NULL
+    assert L.fg_quantize_groupwise(p, 0, 128, 64, 4, p, p, None) == B.FG_OK      # empty input: no-op
+    assert L.fg_dequantize_groupwise(p, p, 2, 100, p, None) == B.FG_ERR_SHAPE
+    assert L.fg_layernorm(p, p, p, 2, 12, 1e-5, p, None) == B.FG_ERR_SHAPE
+
+
+def _cfg(**kw):
+    d = dict(h1=768, nh=12, h2=3072, vocab=50272, max_pos=2048, ln_eps=1e-5)
+    d.update(kw)
+    return B.fg_model_cfg(d["h1"], d["nh"], d["h2"], d["vocab"], d["max_pos"], d["ln_eps"])
+
+
+def test_layer_argument_errors_need_no_gpu():
+    L = B.lib()
+    cfg = _cfg()
+    a = 4096  # a fake, 16-byte aligned, never dereferenced address
+    mat = lambda r, c, dt=B.FG_Q4G64: B.fg_mat(a, a, dt, 0, r, c)
+    w = B.fg_layer_weights(mat(2304, 768), mat(768, 768), mat(3072, 768), mat(768, 3072), None, None, None, None,
+                           a, a, a, a)
+    kv = B.fg_kv_cache(a, a, a, a, B.FG_Q4G64, 4, 40, 0)
+    ws = C.c_void_p(a)
+    call = lambda cfg_, w_, kv_, b=4, t=32, ws_=ws, nws=1 << 40: L.fg_decode_layer(
+        C.byref(cfg_), C.byref(w_), a, b, t, C.byref(kv_), 0, a, ws_, nws, None)
+    assert call(_cfg(nh=5), w, kv) == B.FG_ERR_SHAPE            # h1 % nh != 0
+    assert call(_cfg(h1=768, nh=3), w, kv) == B.FG_ERR_UNSUPPORTED   # head size 256
+    assert call(cfg, w, kv, t=40) == B.FG_ERR_SHAPE             # t >= cap
+    assert call(cfg, w, kv, b=5) == B.FG_ERR_SHAPE              # more sequences than the cache holds
+    assert call(cfg, w, kv, nws=8) == B.FG_ERR_WORKSPACE
+    assert call(cfg, w, kv, ws_=None) == B.FG_ERR_WORKSPACE
+    bad = B.fg_layer_weights(mat(2304, 768), mat(768, 704), mat(3072, 768), mat(768, 3072), None, None, None, None,
+                             a, a, a, a)
+    assert call(cfg, bad, kv) == B.FG_ERR_SHAPE
+    bad = B.fg_layer_weights(mat(2304, 768, 7), mat(768, 768), mat(3072, 768), mat(768, 3072), None, None, None,
+                             None, a, a, a, a)
+    assert call(cfg, bad, kv) == B.FG_ERR_UNSUPPORTED
+    nometa = B.fg_kv_cache(a, None, a, a, B.FG_Q4G64, 4, 40, 0)
+    assert call(cfg, w, nometa) == B.FG_ERR_NULL
+    assert L.fg_decode_layer(None, C.byref(w), a, 4, 0, C.byref(kv), 0, a, ws, 1 << 40, None) == B.FG_ERR_NULL
+    assert L.fg_prefill_layer(C.byref(cfg), C.byref(w), a, 4, 41, C.byref(kv), 0, a, ws, 1 << 40, None) == B.FG_ERR_SHAPE
+    # generate: block must fit the caches, positions must exist
+    larr = (B.fg_layer_weights * 1)(w)
+    karr = (B.fg_kv_cache * 1)(kv)
+    gen = lambda s, n, ngb, gbs, c=cfg: L.fg_generate(C.byref(c), 1, larr, a, a, a, a, a, s, n, ngb, gbs, karr, a, ws,
+                                                      1 << 40, None, None)
+    assert gen(32, 10, 1, 4) == B.FG_ERR_SHAPE       # needs cap >= 41
+    assert gen(32, 9, 2, 4) == B.FG_ERR_SHAPE        # 8 sequences, cache holds 4
+    assert gen(32, 9, 1, 4, _cfg(max_pos=39)) == B.FG_ERR_SHAPE
+    assert gen(0, 9, 1, 4) == B.FG_ERR_SHAPE
+
+
+def test_workspace_queries_are_pure_host_functions():
+    L = B.lib()
+    cfg = _cfg()
+    a = 4096
+    mat = lambda r, c: B.fg_mat(a, a, B.FG_Q4G64, 0, r, c)
+    w = B.fg_layer_weights(mat(2304, 768), mat(768, 768), mat(3072, 768), mat(768, 3072), None, None, None, None,
+                           a, a, a, a)
+    d = L.fg_layer_workspace_bytes(C.byref(cfg), C.byref(w), 4)
+    p = L.fg_layer_workspace_bytes(C.byref(cfg), C.byref(w), 4 * 32)
+    assert 0 < d and d <= p
+    g = L.fg_workspace_bytes(C.byref(cfg), C.byref(w), 4, 1, 32)
+    assert g >= p + 4 * 32 * 768 * 2 + 4 * 50272 * 4
+    assert L.fg_workspace_bytes(C.byref(cfg), C.byref(w), 0, 1, 32) == 0

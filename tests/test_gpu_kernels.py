@@ -1,0 +1,282 @@
+"""Kernel-level parity: each HIP kernel behind the C ABI against the CPU oracle on the same seeded
+inputs.  Integer results (codes, {min,scale} bits, stored FP16 rows) must match bit for bit; FP16
+activations within relative L2 2e-3 and max abs 1e-2."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import fg_oracle as O
+from paper_2303_06865_amd import binding as B
+from paper_2303_06865_amd import synth
+from tests.util import assert_close, dev, host, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand16(shape, std, seed):
+    return (np.random.default_rng(seed).standard_normal(shape) * std).astype(np.float16)
+
+
+# ------------------------------------------------------------------ quantizer
+@pytest.mark.parametrize("rows,cols,std", [(1, 64, 1.0), (37, 576, 0.02), (513, 12288, 0.02), (7, 64 * 5, 30.0),
+                                           (144, 768, 1.0), (3, 49152, 0.02)])
+def test_quantize_bit_exact(rows, cols, std):
+    x = _rand16((rows, cols), std, rows * 7 + cols)
+    codes_ref, meta_ref = O.quantize_groupwise(x)
+    codes, meta = B.fg_quantize_groupwise(dev(x))
+    torch.cuda.synchronize()
+    assert np.array_equal(host(codes), codes_ref)
+    assert np.array_equal(host(meta).view(np.uint32), meta_ref.view(np.uint32))
+
+
+def test_quantize_edge_groups_bit_exact():
+    x = np.zeros((6, 128), np.float16)
+    x[0, :64] = 0.37                                   # constant group
+    x[0, 64:] = np.tile(np.arange(16), 4)              # integers 0..15: scale 1
+    x[1, 1] = 15.0
+    x[1, 2:6] = [0.5, 1.5, 2.5, 3.5]                   # exact ties -> even
+    x[2] = _rand16(128, 1e-4, 1)                       # tiny values (FP16 subnormals present)
+    x[3] = _rand16(128, 2000.0, 2)                     # large values
+    x[4, :64] = -5.0
+    x[4, 64:] = np.linspace(-3, 4.5, 64).astype(np.float16)
+    x[5] = np.float16(65504.0) * np.sign(_rand16(128, 1.0, 3)).astype(np.float16)   # +-max finite
+    codes_ref, meta_ref = O.quantize_groupwise(x)
+    codes, meta = B.fg_quantize_groupwise(dev(x))
+    torch.cuda.synchronize()
+    assert np.array_equal(host(codes), codes_ref)
+    assert np.array_equal(host(meta).view(np.uint32), meta_ref.view(np.uint32))
+    assert list(O.unpack_codes(host(codes))[1, 2:6]) == [0, 2, 2, 4]
+
+
+def test_quantize_empty_input_is_a_noop():
+    x = torch.empty((0, 128), dtype=torch.float16, device="cuda")
+    codes, meta = B.fg_quantize_groupwise(x)
+    assert codes.shape == (0, 64) and meta.shape == (0, 2, 2)
+
+
+def test_dequantize_bit_exact():
+    x = _rand16((65, 640), 0.5, 5)
+    codes_ref, meta_ref = O.quantize_groupwise(x)
+    out = B.fg_dequantize_groupwise(dev(codes_ref), dev(meta_ref))
+    torch.cuda.synchronize()
+    ref = O.dequantize_groupwise(codes_ref, meta_ref)
+    assert np.array_equal(host(out).view(np.uint32), ref.view(np.uint32))
+
+
+# ------------------------------------------------------------------ LayerNorm
+@pytest.mark.parametrize("rows,cols", [(1, 768), (5, 12288), (33, 4096), (2, 7168)])
+def test_layernorm(rows, cols):
+    x = (_rand16((rows, cols), 3.0, rows + cols).astype(np.float32) + 0.7).astype(np.float16)
+    g = (1 + _rand16(cols, 0.1, 1).astype(np.float32)).astype(np.float16)
+    b = _rand16(cols, 0.1, 2)
+    ref = O.round_f16(O.layernorm(x, g, b, 1e-5))
+    out = B.fg_layernorm(dev(x), dev(g), dev(b), 1e-5)
+    torch.cuda.synchronize()
+    assert_close(host(out), ref, "layernorm", rel=5e-4, mabs=4e-3)
+
+
+# ------------------------------------------------------------------ fused dequant + GEMM
+def _linear_case(m, n, k, quant, bias, relu, residual, seed, std_w=0.02, std_x=1.0):
+    w16 = _rand16((n, k), std_w, seed)
+    x16 = _rand16((m, k), std_x, seed + 1)
+    b16 = _rand16(n, 0.5, seed + 2) if bias else None
+    r16 = _rand16((m, n), 1.0, seed + 3) if residual else None
+    om = O.Mat.from_f16(w16, quant)
+    y = O.linear(x16.astype(np.float64), om, b16)
+    if relu:
+        y = np.maximum(y, 0.0)
+    if residual:
+        y = y + r16.astype(np.float64)
+    ref = O.round_f16(y)
+    wm = B.Mat.from_f16(dev(w16), quant)
+    if quant:   # the device-made weights are the oracle's bits
+        assert np.array_equal(host(wm.data), om.codes) and np.array_equal(host(wm.meta), om.meta)
+    out = B.fg_linear(wm, dev(b16), dev(x16), dev(r16), relu)
+    torch.cuda.synchronize()
+    return host(out), ref
+
+
+SMALL_M_CASES = [
+    # m, n, k, bias, relu, residual
+    (1, 256, 128, False, False, False),
+    (4, 768, 768, True, False, True),
+    (4, 3072, 768, True, True, False),
+    (4, 768, 3072, False, False, True),
+    (17, 2304, 768, True, False, False),
+    (36, 1000, 832, True, False, True),      # ragged N, K = 64 mod 128
+    (48, 264, 192, False, True, False),
+    (100, 520, 1024, True, False, False),
+    (144, 1024, 12288, True, False, True),   # OPT-175B hidden size, one column slab
+    (150, 768, 768, False, False, False),
+    (200, 512, 256, True, True, True),       # two row blocks
+    (300, 776, 448, True, False, True),
+]
+
+
+@pytest.mark.parametrize("quant", [True, False])
+@pytest.mark.parametrize("m,n,k,bias,relu,residual", SMALL_M_CASES)
+def test_linear_small_m(m, n, k, bias, relu, residual, quant):
+    got, ref = _linear_case(m, n, k, quant, bias, relu, residual, seed=m + n + k)
+    assert_close(got, ref, "linear m=%d n=%d k=%d q=%s" % (m, n, k, quant))
+
+
+@pytest.mark.parametrize("quant", [True, False])
+@pytest.mark.parametrize("m,n,k,bias,relu,residual", [
+    (600, 768, 768, True, False, True),
+    (1100, 520, 448, True, True, False),      # ragged M, N; K = 7 groups
+    (2048, 3072, 768, False, False, False),
+    (513, 256, 3072, True, False, True),
+])
+def test_linear_large_m(m, n, k, bias, relu, residual, quant):
+    got, ref = _linear_case(m, n, k, quant, bias, relu, residual, seed=m + n + k)
+    assert_close(got, ref, "linear m=%d n=%d k=%d q=%s" % (m, n, k, quant))
+
+
+def test_linear_identity_and_onehot():
+    """Special cases that fix the orientation of W ([out, in]) and the K order inside a group."""
+    eye = np.eye(128, dtype=np.float16)
+    x = _rand16((5, 128), 1.0, 3)
+    out = B.fg_linear(B.Mat.from_f16(dev(eye), False), None, dev(x))
+    assert np.array_equal(host(out), x)
+    w = _rand16((64, 256), 0.5, 4)
+    wq = B.Mat.from_f16(dev(w), True)
+    what = O.Mat.from_f16(w, True).dense()
+    for kk in (0, 1, 5, 63, 64, 130, 255):
+        e = np.zeros((1, 256), np.float16)
+        e[0, kk] = 1.0
+        col = host(B.fg_linear(wq, None, dev(e)))[0]
+        assert_close(col, O.round_f16(what[:, kk]), "one-hot k=%d" % kk, rel=1e-3, mabs=2e-3)
+
+
+# ------------------------------------------------------------------ KV append
+@pytest.mark.parametrize("quant", [True, False])
+@pytest.mark.parametrize("nh,dh", [(3, 128), (12, 64)])
+def test_kv_append_bit_exact(nh, dh, quant):
+    h1 = nh * dh
+    cfg = B.Cfg(h1, nh, 4 * h1, 1000, 64)
+    b, s, cap, boff, pos0 = 3, 5, 16, 1, 4
+    qkv = _rand16((b * s, 3 * h1), 1.0, nh + dh)
+    okv = O.KVCache.empty(5, nh, cap, dh, quant)
+    okv.store(boff, pos0, qkv[:, h1:2 * h1].reshape(b, s, h1), qkv[:, 2 * h1:].reshape(b, s, h1))
+    kv = B.KVCache(cfg, 5, cap, quant)
+    dq = dev(qkv)
+    B.fg_kv_append(cfg, dq[:, h1:], dq[:, 2 * h1:], 3 * h1, b, s, kv, boff, pos0)
+    torch.cuda.synchronize()
+    if quant:
+        assert np.array_equal(host(kv.k_codes), okv.k_codes) and np.array_equal(host(kv.v_codes), okv.v_codes)
+        assert np.array_equal(host(kv.k_meta).view(np.uint32), okv.k_meta.view(np.uint32))
+        assert np.array_equal(host(kv.v_meta).view(np.uint32), okv.v_meta.view(np.uint32))
+    else:
+        assert np.array_equal(host(kv.k_codes), okv.k_f16) and np.array_equal(host(kv.v_codes), okv.v_f16)
+
+
+# ------------------------------------------------------------------ decode attention
+def _decode_attn_case(nh, dh, quant, rows, b=3, batch=4, boff=1, seed=0, kstd=1.0):
+    h1 = nh * dh
+    cfg = B.Cfg(h1, nh, 4 * h1, 1000, 4096)
+    cap = rows + 3
+    k16 = _rand16((batch, rows, h1), kstd, seed)
+    v16 = _rand16((batch, rows, h1), 1.0, seed + 1)
+    q16 = _rand16((b, 3 * h1), 1.0, seed + 2)
+    okv = O.KVCache.empty(batch, nh, cap, dh, quant)
+    okv.store(0, 0, k16, v16)
+    ref = np.empty((b, nh, dh))
+    for i in range(b):
+        for h in range(nh):
+            kh, vh = okv.load(boff + i, h, rows)
+            ref[i, h] = O.attn_decode(q16[i, h * dh:(h + 1) * dh].astype(np.float64), kh, vh)
+    ref = O.round_f16(ref.reshape(b, h1))
+    kv = B.KVCache(cfg, batch, cap, quant)
+    if quant:   # upload the oracle's cache bytes: this test isolates the attention kernel
+        kv.k_codes.copy_(dev(okv.k_codes)); kv.v_codes.copy_(dev(okv.v_codes))
+        kv.k_meta.copy_(dev(okv.k_meta)); kv.v_meta.copy_(dev(okv.v_meta))
+    else:
+        kv.k_codes.copy_(dev(okv.k_f16)); kv.v_codes.copy_(dev(okv.v_f16))
+    out = B.fg_decode_attention(cfg, dev(q16), 3 * h1, b, rows, kv, boff)
+    torch.cuda.synchronize()
+    return host(out), ref
+
+
+@pytest.mark.parametrize("quant", [True, False])
+@pytest.mark.parametrize("nh,dh", [(2, 128), (3, 64)])
+@pytest.mark.parametrize("rows", [1, 2, 5, 63, 64, 65, 127, 128, 129, 255, 257, 600, 1100])
+def test_decode_attention(rows, nh, dh, quant):
+    got, ref = _decode_attn_case(nh, dh, quant, rows, seed=rows)
+    assert_close(got, ref, "decode attention rows=%d dh=%d q=%s" % (rows, dh, quant))
+
+
+@pytest.mark.parametrize("quant", [True, False])
+def test_decode_attention_peaked_softmax(quant):
+    """Large key norm: a near one-hot softmax, where a wrong max/rescale shows immediately."""
+    got, ref = _decode_attn_case(2, 128, quant, 300, seed=77, kstd=4.0)
+    assert_close(got, ref, "peaked softmax")
+
+
+# ------------------------------------------------------------------ prefill attention
+@pytest.mark.parametrize("nh,dh", [(2, 128), (3, 64)])
+@pytest.mark.parametrize("b,s", [(1, 1), (2, 7), (1, 64), (2, 65), (1, 100), (1, 200), (3, 32)])
+def test_prefill_attention(b, s, nh, dh):
+    h1 = nh * dh
+    cfg = B.Cfg(h1, nh, 4 * h1, 1000, 4096)
+    qkv = _rand16((b * s, 3 * h1), 1.0, b * 100 + s)
+    x = qkv.astype(np.float64).reshape(b, s, 3, nh, dh)
+    ref = np.empty((b, s, nh, dh))
+    for i in range(b):
+        for h in range(nh):
+            ref[i, :, h] = O.attn_prefill(x[i, :, 0, h], x[i, :, 1, h], x[i, :, 2, h])
+    ref = O.round_f16(ref.reshape(b * s, h1))
+    out = B.fg_prefill_attention(cfg, dev(qkv), b, s)
+    torch.cuda.synchronize()
+    assert_close(host(out), ref, "prefill attention b=%d s=%d dh=%d" % (b, s, dh))
+
+
+# ------------------------------------------------------------------ embedding and LM head
+def test_embed_bit_exact():
+    sh = synth.Shape(h1=256, nh=2, h2=512, vocab=1000, max_pos=64)
+    cfg = B.Cfg(sh.h1, sh.nh, sh.h2, sh.vocab, sh.max_pos)
+    m = synth.model_tensors(sh, 3, std=0.5)
+    ids = synth.prompt_ids(3, 7, sh.vocab, 3)
+    ref = O.embed(ids, np.broadcast_to(np.arange(7), (3, 7)), m["embed"], m["pos"]).reshape(21, sh.h1)
+    out = B.fg_embed(cfg, dev(m["embed"]), dev(m["pos"]), dev(ids.reshape(-1)), 7, 0)
+    assert np.array_equal(host(out), ref)
+    ref = O.embed(ids[:, 0], np.full(3, 11), m["embed"], m["pos"])
+    out = B.fg_embed(cfg, dev(m["embed"]), dev(m["pos"]), dev(np.ascontiguousarray(ids[:, 0])), 1, 11)
+    assert np.array_equal(host(out), ref)
+
+
+@pytest.mark.parametrize("rows,vocab,h1", [(4, 50272, 768), (37, 1000, 256), (144, 5000, 1024)])
+def test_lm_head_greedy(rows, vocab, h1):
+    sh = synth.Shape(h1=h1, nh=h1 // 64, h2=4 * h1, vocab=vocab, max_pos=64)
+    ocfg = O.ModelCfg(sh.h1, sh.nh, sh.h2, sh.vocab, sh.max_pos)
+    cfg = B.Cfg(sh.h1, sh.nh, sh.h2, sh.vocab, sh.max_pos)
+    m = synth.model_tensors(sh, 5, std=0.02)
+    x = _rand16((rows, h1), 2.0, 9)
+    g = (1 + _rand16(h1, 0.1, 1).astype(np.float32)).astype(np.float16)
+    bb = _rand16(h1, 0.1, 2)
+    ref = O.lm_head_logits(ocfg, x, g, bb, m["embed"])
+    ids, logits = B.fg_lm_head_greedy(cfg, dev(x), dev(g), dev(bb), dev(m["embed"]))
+    torch.cuda.synchronize()
+    lg = host(logits)
+    assert_close(lg, ref, "logits", rel=2e-3, mabs=1e-2)
+    # the GPU's ids are the lowest-index argmax of the GPU's own binary32 logits ...
+    assert np.array_equal(host(ids), np.argmax(lg, axis=-1).astype(np.int32))
+    # ... and equal the oracle's wherever the oracle's top-2 margin exceeds the logit error
+    srt = np.sort(ref, axis=-1)
+    margin = srt[:, -1] - srt[:, -2]
+    err = np.abs(lg - ref).max()
+    safe = margin > 2 * err
+    assert safe.sum() >= rows * 0.9
+    assert np.array_equal(host(ids)[safe], O.greedy(ref)[safe])
+
+
+def test_argmax_lowest_index_on_exact_ties():
+    """All-zero hidden state and beta = 0 give all-zero logits: token 0 must win every row."""
+    sh = synth.Shape(h1=128, nh=2, h2=512, vocab=520, max_pos=8)
+    cfg = B.Cfg(sh.h1, sh.nh, sh.h2, sh.vocab, sh.max_pos)
+    m = synth.model_tensors(sh, 1)
+    x = np.zeros((3, 128), np.float16)
+    ids, logits = B.fg_lm_head_greedy(cfg, dev(x), dev(np.ones(128, np.float16)), dev(np.zeros(128, np.float16)),
+                                      dev(m["embed"]))
+    assert np.all(host(logits) == 0) and np.all(host(ids) == 0)

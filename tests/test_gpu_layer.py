@@ -1,0 +1,98 @@
+"""Layer-level parity (Section 3): fg_prefill_layer and fg_decode_layer against the oracle, on the
+OPT-125m-shaped configuration (batch 4, prompt 32, 8 decode steps, seed 0) and on other shapes that
+span head sizes, biases, FP16 storage and ragged sizes."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fg_oracle as O
+from paper_2303_06865_amd import binding as B
+from paper_2303_06865_amd import synth
+from tests.util import assert_close, cache_rows_dense, cfg_pair, dev, host, oracle_cache_dense, oracle_layer
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_layer_sequence(sh, quant_w, quant_kv, b, s, steps, seed, biases, random_ln, x_std=0.05, batch=None,
+                        boff=0):
+    """Prefill then `steps` decode steps on both sides, each side feeding on its own cache, the
+    decode inputs being fresh seeded activations (the same on both sides)."""
+    ocfg, cfg = cfg_pair(sh)
+    t = synth.layer_tensors(sh, seed, 0, std=0.02, biases=biases, random_ln=random_ln)
+    ow = oracle_layer(t, quant_w)
+    w = B.LayerWeights.from_numpy(t, quant_w)
+    batch = batch or b
+    cap = s + steps
+    okv = O.KVCache.empty(batch, sh.nh, cap, sh.dh, quant_kv)
+    kv = B.KVCache(cfg, batch, cap, quant_kv)
+    x = synth.activations_f16((b, s, sh.h1), x_std, seed)
+    ref = O.prefill_layer(ocfg, ow, x, okv, batch_offset=boff)
+    got = B.fg_prefill_layer(cfg, w, dev(x), kv, batch_offset=boff)
+    torch.cuda.synchronize()
+    assert_close(host(got), ref, "prefill output")
+    kr, vr = oracle_cache_dense(okv, s)
+    kg, vg = cache_rows_dense(kv, s)
+    assert_close(kg[boff:boff + b], kr[boff:boff + b], "prefill K cache", mabs=2e-2)
+    assert_close(vg[boff:boff + b], vr[boff:boff + b], "prefill V cache", mabs=2e-2)
+    for i in range(steps):
+        xt = synth.activations_f16((b, sh.h1), x_std, seed + 100 + i)
+        ref = O.decode_layer(ocfg, ow, xt, s + i, okv, batch_offset=boff)
+        got = B.fg_decode_layer(cfg, w, dev(xt), s + i, kv, batch_offset=boff)
+        torch.cuda.synchronize()
+        assert_close(host(got), ref, "decode step %d output" % i)
+    kr, vr = oracle_cache_dense(okv, cap)
+    kg, vg = cache_rows_dense(kv, cap)
+    # a stored value may sit one quantization step away when the FP16 input differed by an ulp
+    assert_close(kg[boff:boff + b], kr[boff:boff + b], "final K cache", rel=5e-3, mabs=5e-2)
+    assert_close(vg[boff:boff + b], vr[boff:boff + b], "final V cache", rel=5e-3, mabs=5e-2)
+    if boff or batch > b:   # rows of other sequences stay untouched
+        untouched = [i for i in range(batch) if not (boff <= i < boff + b)]
+        assert np.all(kg[untouched] == 0) and np.all(vg[untouched] == 0)
+
+
+def test_opt125m_layer_q4_batch4_prompt32_8steps():
+    """The small parity configuration: hidden 768, 12 heads x 64, FFN 3072, weights ~N(0,0.02),
+    LN gamma=1/beta=0, 4-bit weights and cache, batch 4, prompt 32, 8 decode steps, seed 0."""
+    _run_layer_sequence(synth.OPT_125M_LAYER, True, True, b=4, s=32, steps=8, seed=0, biases=False,
+                        random_ln=False, x_std=0.03)
+
+
+@pytest.mark.parametrize("quant_w,quant_kv", [(False, False), (True, False), (False, True)])
+def test_opt125m_layer_storage_variants(quant_w, quant_kv):
+    _run_layer_sequence(synth.OPT_125M_LAYER, quant_w, quant_kv, b=4, s=32, steps=3, seed=1, biases=True,
+                        random_ln=True)
+
+
+@pytest.mark.parametrize("quant", [True, False])
+def test_layer_head128_ragged_sizes_and_offset(quant):
+    sh = synth.Shape(h1=512, nh=4, h2=1536, vocab=1000, max_pos=256)
+    _run_layer_sequence(sh, quant, quant, b=3, s=70, steps=3, seed=2, biases=True, random_ln=True, x_std=0.5,
+                        batch=5, boff=2)
+
+
+def test_layer_large_m_prefill_path():
+    """b*s = 660 rows takes the large-M GEMM kernel in prefill; decode then uses the small-M one."""
+    sh = synth.Shape(h1=256, nh=2, h2=1024, vocab=1000, max_pos=512)
+    _run_layer_sequence(sh, True, True, b=5, s=132, steps=2, seed=3, biases=True, random_ln=True, x_std=0.5)
+
+
+def test_layer_6_7b_shape_slice():
+    """Real width of OPT-6.7B (hidden 4096, 32 heads x 128, FFN 16384), two sequences."""
+    sh = synth.Shape(h1=4096, nh=32, h2=16384, vocab=1000, max_pos=64)
+    _run_layer_sequence(sh, True, True, b=2, s=20, steps=2, seed=4, biases=False, random_ln=False, x_std=0.5)
+
+
+def test_prefill_then_decode_consistency_on_gpu_fp16():
+    """FP16 path: prefill(s) + decode(1) reproduces the last row of prefill(s+1) (Section 3)."""
+    sh = synth.Shape(h1=256, nh=4, h2=512, vocab=1000, max_pos=64)
+    ocfg, cfg = cfg_pair(sh)
+    t = synth.layer_tensors(sh, 5, 0, biases=True, random_ln=True)
+    w = B.LayerWeights.from_numpy(t, False)
+    x = synth.activations_f16((2, 9, sh.h1), 0.5, 5)
+    kva = B.KVCache(cfg, 2, 12, False)
+    full = host(B.fg_prefill_layer(cfg, w, dev(x), kva))
+    kvb = B.KVCache(cfg, 2, 12, False)
+    B.fg_prefill_layer(cfg, w, dev(np.ascontiguousarray(x[:, :8])), kvb)
+    last = host(B.fg_decode_layer(cfg, w, dev(np.ascontiguousarray(x[:, 8])), 8, kvb))
+    assert np.array_equal(host(kva.k_codes[:, :, :9]), host(kvb.k_codes[:, :, :9]))
+    assert_close(last, full[:, 8], "prefill vs decode", rel=1e-3, mabs=5e-3)
