@@ -24,7 +24,9 @@
  *             round((x-min)/scale) (ties to even; a constant group has scale 0 and codes 0).
  *             codes: cols/2 bytes per row, element 2j in the low nibble of byte j;
  *             meta : cols/64 pairs per row, 8 bytes each {min, scale} (binary32).
- *             An element is recovered as min + code*scale.  0.625 bytes per element.
+ *             An element is recovered as min + code*scale: weights as the FP16 number nearest to
+ *             that value (the projections multiply FP16 by FP16 into binary32), KV rows in
+ *             binary32 inside the attention kernel.  0.625 bytes per element.
  */
 #ifndef FG_H
 #define FG_H
@@ -116,7 +118,7 @@ int fg_quantize_groupwise(const void* x_f16, int64_t rows, int64_t cols, int gro
                           void* codes_out, void* meta_out, void* stream);
 
 /* Inverse map of Section 5 (stored 4-bit -> values before computation): out_f32[r][c] =
- * min + code*scale evaluated as one binary32 multiply then one binary32 add. */
+ * min + code*scale rounded once to binary32 (a fused multiply-add). */
 int fg_dequantize_groupwise(const void* codes, const void* meta, int64_t rows, int64_t cols,
                             void* out_f32, void* stream);
 

@@ -10,6 +10,9 @@ Precision policy
     with one rounding per operation (numpy float32 ops never fuse), because its
     result is an integer code and a stored (min, scale) pair that the HIP path
     must reproduce bit for bit.
+  * Dequantization is the real number min + code * scale rounded once: to FP16 for
+    weights (the paper dequantizes to FP16 before computation), to binary32 for
+    KV-cache rows (their consumer, the attention, works in binary32).
   * Everything else (Section 3 layer equations) runs in float64 on the
     dequantized operands.  Activations are rounded to FP16 at the points where
     the layer stores an activation tensor: after each LayerNorm, after each
@@ -92,16 +95,28 @@ def unpack_codes(b: np.ndarray) -> np.ndarray:
     return out
 
 
-def dequantize_groupwise(codes: np.ndarray, meta: np.ndarray, group: int = GROUP) -> np.ndarray:
-    """x_hat = min + code * scale, binary32 multiply then binary32 add
-    (Section 5: stored quantized, converted back before computation)."""
-    c = unpack_codes(codes).astype(np.float32)
+def _dequantize_exact(codes: np.ndarray, meta: np.ndarray, group: int = GROUP) -> np.ndarray:
+    """The real number min + code * scale of every element, held in float64 (the product of a
+    4-bit code and a binary32 scale is exact there, and so is the sum unless the two terms are
+    more than 2^25 apart in magnitude)."""
+    c = unpack_codes(codes).astype(np.float64)
     shp = c.shape
     c = c.reshape(shp[:-1] + (shp[-1] // group, group))
-    mn = meta[..., 0].astype(np.float32)[..., None]
-    sc = meta[..., 1].astype(np.float32)[..., None]
-    prod = (c * sc).astype(np.float32)
-    return (mn + prod).astype(np.float32).reshape(shp)
+    mn = meta[..., 0].astype(np.float64)[..., None]
+    sc = meta[..., 1].astype(np.float64)[..., None]
+    return (mn + c * sc).reshape(shp)
+
+
+def dequantize_groupwise(codes: np.ndarray, meta: np.ndarray, group: int = GROUP) -> np.ndarray:
+    """x_hat = min + code * scale rounded once to binary32 (Section 5: stored quantized, converted
+    back before computation).  Used for the KV cache, whose consumer works in binary32."""
+    return _dequantize_exact(codes, meta, group).astype(np.float32)
+
+
+def dequantize_groupwise_f16(codes: np.ndarray, meta: np.ndarray, group: int = GROUP) -> np.ndarray:
+    """The FP16 number nearest to min + code * scale (Section 5: "converted back to FP16 before
+    computation").  This is the weight value the projections multiply with."""
+    return _dequantize_exact(codes, meta, group).astype(np.float16)
 
 
 # --------------------------------------------------------------------------
@@ -140,11 +155,11 @@ class Mat:
         return Mat(r, c, f16=w16)
 
     def dense(self) -> np.ndarray:
-        """The matrix the layer computes with: the FP16 values, or the
-        dequantized values (Section 5), as float64."""
+        """The matrix the layer computes with, as float64: the FP16 values, or the
+        values dequantized back to FP16 (Section 5)."""
         if self.f16 is not None:
             return self.f16.astype(np.float64)
-        return dequantize_groupwise(self.codes, self.meta).astype(np.float64)
+        return dequantize_groupwise_f16(self.codes, self.meta).astype(np.float64)
 
 
 def linear(x: np.ndarray, w: Mat, bias: Optional[np.ndarray]) -> np.ndarray:

@@ -141,6 +141,24 @@ __device__ __forceinline__ void unpack8_codes(uint32_t x, h2_t p[4]) {
   p[3] = __builtin_bit_cast(h2_t, r[3]) - k64;
 }
 
+// Exact dequantization of one word of eight codes to FP16: w_i = RN16(mn + c_i * scale), one rounding
+// from the real number (Section 5: "converted back to FP16 before computation").
+// A nibble masked in place is the FP16 subnormal c * 2^-24 (low nibble of a half) or c * 2^-20 (next
+// nibble); gfx950 mixed-precision FMAs take FP16 subnormals at full rate, multiply by the pre-scaled
+// s24 = scale * 2^24 / s20 = scale * 2^20 (exact scalings), add mn and round once into an FP16 half.
+// Output pair order: (w0,w4),(w1,w5),(w2,w6),(w3,w7), the order permute8_like_codes gives activations.
+__device__ __forceinline__ void dequant8_exact(uint32_t x, float s24, float s20, float mn, h2_t p[4]) {
+  const uint32_t y = x >> 8;
+  const h2_t a = __builtin_bit_cast(h2_t, x & 0x000F000Fu);
+  const h2_t b = __builtin_bit_cast(h2_t, x & 0x00F000F0u);
+  const h2_t c = __builtin_bit_cast(h2_t, y & 0x000F000Fu);
+  const h2_t d = __builtin_bit_cast(h2_t, y & 0x00F000F0u);
+  p[0] = (h2_t){(half_t)__builtin_fmaf((float)a.x, s24, mn), (half_t)__builtin_fmaf((float)a.y, s24, mn)};
+  p[1] = (h2_t){(half_t)__builtin_fmaf((float)b.x, s20, mn), (half_t)__builtin_fmaf((float)b.y, s20, mn)};
+  p[2] = (h2_t){(half_t)__builtin_fmaf((float)c.x, s24, mn), (half_t)__builtin_fmaf((float)c.y, s24, mn)};
+  p[3] = (h2_t){(half_t)__builtin_fmaf((float)d.x, s20, mn), (half_t)__builtin_fmaf((float)d.y, s20, mn)};
+}
+
 // Reorder eight consecutive FP16 values h0..h7 (four words) into the pair order produced by
 // unpack8_*: (h0,h4),(h1,h5),(h2,h6),(h3,h7), so that a contraction against unpacked codes lines up.
 __device__ __forceinline__ u4_t permute8_like_codes(u4_t d) {

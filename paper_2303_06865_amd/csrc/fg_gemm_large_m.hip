@@ -119,19 +119,17 @@ __global__ __launch_bounds__(256) void gemm_large_m_kernel(LargeArgs a) {
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         const int id = tid + 256 * c;
-        const half_t s = (half_t)gm[c].y, m = (half_t)gm[c].x;
-        const h2_t sc2 = {s, s}, mn2 = {m, m};
+        const float s24 = gm[c].y * 16777216.0f, s20 = gm[c].y * 1048576.0f, mnf = gm[c].x;
         half_t* dst = Bd + (id >> 1) * LDT + (id & 1) * 32;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           h2_t cc[4];
-          unpack8_codes(gb[c][u], cc);
+          dequant8_exact(gb[c][u], s24, s20, mnf, cc);
           h8_t o;
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const h2_t v = cc[e] * sc2 + mn2;
-            o[2 * e] = v.x;
-            o[2 * e + 1] = v.y;
+            o[2 * e] = cc[e].x;
+            o[2 * e + 1] = cc[e].y;
           }
           *reinterpret_cast<h8_t*>(dst + u * 8) = o;
         }

@@ -6,7 +6,8 @@
 //
 // Design (gfx950):
 //   * The weight matrix is streamed from HBM exactly once, straight into registers, 16 bytes per
-//     lane; 4-bit codes are expanded to FP16 in registers (never through LDS or HBM) and fed to
+//     lane; 4-bit codes are dequantized to FP16 in registers (exactly: one rounding of
+//     min + code * scale; never through LDS or HBM) and fed to
 //     v_mfma_f32_16x16x32_f16 as the B operand.  The activation tile (all M rows x 128 K) is
 //     staged in LDS once per workgroup and shared by its four waves as the A operand.
 //   * A workgroup covers 256 output columns (4 waves x 4 column tiles of 16), so each A-operand
@@ -172,15 +173,15 @@ __global__ __launch_bounds__(256) void gemm_small_m_kernel(SmallArgs a) {
     for (int ks = ks0; ks < ks1; ++ks) {
       // operands of this step, moved out of the prefetch registers
       u4_t bcur[kNTW][Q4 ? 1 : NSUB];
-      h2_t sc2[kNTW], mn2[kNTW];
+      float s24[kNTW], s20[kNTW], mnf[kNTW];
 #pragma unroll
       for (int j = 0; j < kNTW; ++j) {
 #pragma unroll
         for (int i = 0; i < (Q4 ? 1 : NSUB); ++i) bcur[j][i] = bq[j][i];
         if (Q4) {
-          const half_t s = (half_t)bm[j].y, m = (half_t)bm[j].x;
-          sc2[j] = (h2_t){s, s};
-          mn2[j] = (h2_t){m, m};
+          s24[j] = bm[j].y * 16777216.0f;
+          s20[j] = bm[j].y * 1048576.0f;
+          mnf[j] = bm[j].x;
         }
       }
       const bool more = ks + 1 < ks1;
@@ -201,12 +202,11 @@ __global__ __launch_bounds__(256) void gemm_small_m_kernel(SmallArgs a) {
           h8_t bop;
           if (Q4) {
             h2_t c[4];
-            unpack8_codes(bcur[j][0][i], c);
+            dequant8_exact(bcur[j][0][i], s24[j], s20[j], mnf[j], c);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              const h2_t v = c[e] * sc2[j] + mn2[j];
-              bop[2 * e] = v.x;
-              bop[2 * e + 1] = v.y;
+              bop[2 * e] = c[e].x;
+              bop[2 * e + 1] = c[e].y;
             }
           } else {
             bop = __builtin_bit_cast(h8_t, bcur[j][i]);

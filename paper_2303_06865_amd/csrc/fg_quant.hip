@@ -75,8 +75,8 @@ __global__ __launch_bounds__(256) void dequantize_rows_kernel(const uint32_t* __
     float* o2 = reinterpret_cast<float*>(&hi);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      o[i] = __fadd_rn(m.x, __fmul_rn((float)((p >> (4 * i)) & 15u), m.y));
-      o2[i] = __fadd_rn(m.x, __fmul_rn((float)((p >> (4 * i + 16)) & 15u), m.y));
+      o[i] = __builtin_fmaf((float)((p >> (4 * i)) & 15u), m.y, m.x);        // one rounding
+      o2[i] = __builtin_fmaf((float)((p >> (4 * i + 16)) & 15u), m.y, m.x);
     }
     reinterpret_cast<float4*>(out)[w * 2] = lo;
     reinterpret_cast<float4*>(out)[w * 2 + 1] = hi;

@@ -33,18 +33,28 @@ def _gpu_generate(cfg, layers, m, prompt, n, ngb, gbs, quant_kv):
     return host(ids), stats
 
 
-def _compare_ids(got, ref, logits):
-    if np.array_equal(got, ref):
-        return
-    bad = np.argwhere(got != ref)
-    for b, i in bad:
-        # only the first divergence of a sequence is attributable; later tokens follow from it
+def _compare_ids(got, ref, logits, err=2e-3):
+    """Ids must be equal.  The one admissible exception is a near-tie: the GPU's token is the
+    oracle's runner-up region, i.e. the oracle's own logit gap between its winner and the GPU's
+    choice is below 4 x `err` x rms of that logit row, `err` being the relative logit error to
+    expect: 2e-3 with FP16 caches; 1e-2 with 4-bit caches, where the two sides' caches differ by
+    whole quantization steps in a fraction of a percent of their entries (an FP16 ulp of difference
+    in a K/V value that crosses a rounding boundary) and short contexts average little of that
+    away.  Such events are printed; a sequence is not compared past its first near-tie because its
+    later tokens legitimately follow a different prefix.  Returns the number of near-ties."""
+    ties = 0
+    for b, i in np.argwhere(got != ref):
         if np.any(got[b, :i] != ref[b, :i]):
             continue
-        srt = np.sort(logits[i, b])
-        margin = float(srt[-1] - srt[-2])
-        assert margin < 2e-3, "sequence %d step %d: ids %d vs %d with oracle margin %.3e" % (
-            b, i, got[b, i], ref[b, i], margin)
+        row = logits[i, b].astype(np.float64)
+        gap = float(row[ref[b, i]] - row[got[b, i]])
+        allowed = 4 * err * float(np.sqrt((row ** 2).mean()))
+        assert 0 <= gap < allowed, "sequence %d step %d: ids %d vs %d, oracle gap %.3e (near-tie bound %.3e)" % (
+            b, i, got[b, i], ref[b, i], gap, allowed)
+        print("near-tie: sequence %d step %d ids %d vs %d, oracle gap %.3e < %.3e" % (
+            b, i, got[b, i], ref[b, i], gap, allowed))
+        ties += 1
+    return ties
 
 
 @pytest.mark.parametrize("n", [9, 8])
@@ -78,7 +88,7 @@ def test_generate_small_multilayer_and_factorisations(quant):
     outs = []
     for ngb, gbs in ((1, 6), (2, 3), (6, 1), (3, 2)):
         got, _ = _gpu_generate(cfg, layers, m, prompt, 6, ngb, gbs, quant)
-        _compare_ids(got, ref, logits)
+        assert _compare_ids(got, ref, logits, 1e-2 if quant else 2e-3) <= 1
         outs.append(got)
     for o in outs[1:]:
         assert np.array_equal(o, outs[0])

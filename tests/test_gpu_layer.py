@@ -8,15 +8,18 @@ import torch
 from oracle import fg_oracle as O
 from paper_2303_06865_amd import binding as B
 from paper_2303_06865_amd import synth
-from tests.util import assert_close, cache_rows_dense, cfg_pair, dev, host, oracle_cache_dense, oracle_layer
+from tests.util import assert_cache_close, assert_close, cache_rows_dense, cfg_pair, dev, host, oracle_layer, upload_cache
 
 pytestmark = pytest.mark.gpu
 
 
 def _run_layer_sequence(sh, quant_w, quant_kv, b, s, steps, seed, biases, random_ln, x_std=0.05, batch=None,
                         boff=0):
-    """Prefill then `steps` decode steps on both sides, each side feeding on its own cache, the
-    decode inputs being fresh seeded activations (the same on both sides)."""
+    """Prefill then `steps` decode steps on both sides, the decode inputs being fresh seeded
+    activations (the same on both sides).  Before every decode step the device cache is overwritten
+    with the oracle's bytes, so each step is compared on identical inputs: the two caches otherwise
+    drift apart by whole quantization steps wherever an FP16 ulp of difference in a K/V value
+    crosses a rounding boundary, which says nothing about the kernels."""
     ocfg, cfg = cfg_pair(sh)
     t = synth.layer_tensors(sh, seed, 0, std=0.02, biases=biases, random_ln=random_ln)
     ow = oracle_layer(t, quant_w)
@@ -30,22 +33,18 @@ def _run_layer_sequence(sh, quant_w, quant_kv, b, s, steps, seed, biases, random
     got = B.fg_prefill_layer(cfg, w, dev(x), kv, batch_offset=boff)
     torch.cuda.synchronize()
     assert_close(host(got), ref, "prefill output")
-    kr, vr = oracle_cache_dense(okv, s)
-    kg, vg = cache_rows_dense(kv, s)
-    assert_close(kg[boff:boff + b], kr[boff:boff + b], "prefill K cache", mabs=2e-2)
-    assert_close(vg[boff:boff + b], vr[boff:boff + b], "prefill V cache", mabs=2e-2)
+    assert_cache_close(kv, okv, slice(boff, boff + b), s, "prefill")
     for i in range(steps):
         xt = synth.activations_f16((b, sh.h1), x_std, seed + 100 + i)
+        upload_cache(kv, okv)
         ref = O.decode_layer(ocfg, ow, xt, s + i, okv, batch_offset=boff)
         got = B.fg_decode_layer(cfg, w, dev(xt), s + i, kv, batch_offset=boff)
         torch.cuda.synchronize()
         assert_close(host(got), ref, "decode step %d output" % i)
-    kr, vr = oracle_cache_dense(okv, cap)
-    kg, vg = cache_rows_dense(kv, cap)
-    # a stored value may sit one quantization step away when the FP16 input differed by an ulp
-    assert_close(kg[boff:boff + b], kr[boff:boff + b], "final K cache", rel=5e-3, mabs=5e-2)
-    assert_close(vg[boff:boff + b], vr[boff:boff + b], "final V cache", rel=5e-3, mabs=5e-2)
+        assert_cache_close(kv, okv, slice(boff, boff + b), s + i + 1, "decode step %d" % i)
+    assert_cache_close(kv, okv, slice(boff, boff + b), cap, "final")
     if boff or batch > b:   # rows of other sequences stay untouched
+        kg, vg = cache_rows_dense(kv, cap)
         untouched = [i for i in range(batch) if not (boff <= i < boff + b)]
         assert np.all(kg[untouched] == 0) and np.all(vg[untouched] == 0)
 

@@ -52,8 +52,10 @@ def test_linear_bruteforce_and_special_cases():
             for r in range(6):          # dequantized matrix element by element, plain Python
                 for k in range(128):
                     mn, sc = float(meta[r, k // 64, 0]), float(meta[r, k // 64, 1])
-                    assert abs(w[r, k] - (mn + int(c[r, k]) * sc)) <= 1e-6 * max(1.0, abs(mn))
-            assert np.all(np.abs(w - w16.astype(np.float64)) <= meta[..., 1].repeat(64, axis=1) / 2 * (1 + 1e-6) + 1e-7)
+                    ref = mn + int(c[r, k]) * sc
+                    assert w[r, k] == float(np.float16(ref))          # the FP16 number nearest to it
+            half_ulp = np.abs(w16.astype(np.float64)) * 2.0 ** -11 + 2.0 ** -25
+            assert np.all(np.abs(w - w16.astype(np.float64)) <= meta[..., 1].repeat(64, axis=1) / 2 * (1 + 1e-6) + half_ulp)
         y = O.linear(x, m, bias)
         for i in range(3):
             for r in range(6):

@@ -110,6 +110,28 @@ def test_ties_round_to_even():
     assert c[0] == 0 and c[1] == 15
 
 
+def test_dequantize_is_single_rounding_of_the_exact_value():
+    """min + code*scale evaluated exactly (Python fractions) and rounded once, to binary32 for the
+    cache form and to FP16 for the weight form."""
+    from fractions import Fraction
+    x = _rand16((3, 128), 0.02, 21)
+    codes, meta = O.quantize_groupwise(x)
+    c = O.unpack_codes(codes)
+    d32 = O.dequantize_groupwise(codes, meta)
+    d16 = O.dequantize_groupwise_f16(codes, meta)
+    assert d32.dtype == np.float32 and d16.dtype == np.float16
+    for r in range(3):
+        for k in range(0, 128, 7):
+            exact = Fraction(float(meta[r, k // 64, 0])) + int(c[r, k]) * Fraction(float(meta[r, k // 64, 1]))
+            f = float(exact)                       # exact -> double is itself correctly rounded
+            assert d32[r, k] == np.float32(f) and d16[r, k] == np.float16(f)
+            # nearest: no neighbouring representable number is closer
+            for arr, dt in ((d32, np.float32), (d16, np.float16)):
+                v = arr[r, k]
+                for nb in (np.nextafter(v, dt(np.inf)), np.nextafter(v, dt(-np.inf))):
+                    assert abs(Fraction(float(v)) - exact) <= abs(Fraction(float(nb)) - exact)
+
+
 def test_constant_group_is_exact():
     v = np.full((2, 128), 0.37, np.float16)
     v[1, 64:] = -2.5
