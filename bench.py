@@ -1,0 +1,257 @@
+#!/usr/bin/env python3
+"""Benchmark of the generation hot path on one MI355X.
+
+A "step" is one pass of the whole hot path: fg_generate over one block of synthetic prompts
+(prefill of all GPU batches, then n-1 decode steps), inputs already resident in HBM.  The default
+workload is the one the headline metric is quoted on: OPT-175B shape, 4-bit group-wise weights and
+KV cache, block 4 x 36 sequences, prompt 512, 32 generated tokens (Section 6 workload of the paper).
+
+Prints ONE JSON line with generated tokens/s (paper's definition: bls*n / (prefill + decode time)),
+the per-kernel-class rooflines measured live with HIP events on the launch stream, the decode-phase
+HBM fraction, and the CPU oracle timed on a bounded slice of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12          # bytes/s, MI355X HBM3E
+MFMA_F16_PEAK = 2.5e15     # flop/s, dense FP16 MFMA
+
+WORKLOADS = {
+    # name: (shape name, quantized weights, quantized kv, num_gpu_batches, gpu_batch_size, s, n)
+    "opt175b_q4": ("OPT_175B", True, True, 4, 36, 512, 32),
+    "opt30b_q4": ("OPT_30B", True, True, 8, 32, 512, 32),
+    "opt6.7b_f16": ("OPT_6_7B", False, False, 4, 32, 512, 32),
+    "opt125m_layer_q4": ("OPT_125M_LAYER", True, True, 1, 4, 32, 9),
+}
+
+
+def bpe(q):
+    return 0.625 if q else 2.0
+
+
+def build_model(sh, wq, seed, torch, B):
+    """Random-init weights ~N(0, 0.02) generated and quantized on the device, one layer at a time."""
+    g = torch.Generator(device="cuda")
+    layers = []
+    ones = torch.ones(sh.h1, dtype=torch.float16, device="cuda")
+    zeros = torch.zeros(sh.h1, dtype=torch.float16, device="cuda")
+
+    def mat(rows, cols, j, tid):
+        g.manual_seed(seed * 1000003 + j * 16 + tid)
+        w = torch.empty((rows, cols), dtype=torch.float16, device="cuda")
+        w.normal_(0.0, 0.02, generator=g)
+        m = B.Mat.from_f16(w, wq)
+        return m
+
+    for j in range(sh.l):
+        layers.append(B.LayerWeights(mat(3 * sh.h1, sh.h1, j, 0), mat(sh.h1, sh.h1, j, 1), mat(sh.h2, sh.h1, j, 2),
+                                     mat(sh.h1, sh.h2, j, 3), ones, zeros, ones, zeros))
+    g.manual_seed(seed * 1000003 + 999983)
+    emb = torch.empty((sh.vocab, sh.h1), dtype=torch.float16, device="cuda").normal_(0.0, 0.02, generator=g)
+    pos = torch.empty((sh.max_pos, sh.h1), dtype=torch.float16, device="cuda").normal_(0.0, 0.02, generator=g)
+    return layers, emb, pos, ones, zeros
+
+
+def cpu_baseline(sh, wq, kvq, s, n, budget_s=25.0):
+    """The oracle as it stands, on the host cores, on a bounded slice of the workload: a decode step
+    of ONE layer for 4 sequences at the real widths, with each projection cut to a 512-row slab of
+    its weight matrix; scaled to the full matrices and to l layers.  Reported, not a target."""
+    import numpy as np
+    from oracle import fg_oracle as O
+    from paper_2303_06865_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    b, slab = 4, 512
+    rows = s + n // 2
+    h1, h2, nh, dh = sh.h1, sh.h2, sh.nh, sh.dh
+    rng = np.random.default_rng(0)
+    f16 = lambda shape, std: (rng.standard_normal(shape, dtype=np.float32) * np.float32(std)).astype(np.float16)
+    slabs = {"wqkv": (3 * h1, h1), "wo": (h1, h1), "w1": (h2, h1), "w2": (h1, h2)}
+    mats = {k: O.Mat.from_f16(f16((min(slab, r), c), 0.02), wq) for k, (r, c) in slabs.items()}
+    kv = O.KVCache.empty(b, nh, rows + 1, dh, kvq)
+    kv.store(0, 0, f16((b, rows, h1), 1.0), f16((b, rows, h1), 1.0))
+    x = f16((b, h1), 1.0)
+    a = f16((b, h2), 1.0)
+    ones, zeros = np.ones(h1, np.float16), np.zeros(h1, np.float16)
+    t_total = 0.0
+    t0 = time.perf_counter()
+    y = O.round_f16(O.layernorm(x.astype(np.float64), ones, zeros, 1e-5))
+    t_ln = time.perf_counter() - t0
+    t_lin = 0.0
+    for k, (r, c) in slabs.items():
+        xin = a if k == "w2" else y
+        t0 = time.perf_counter()
+        O.round_f16(O.linear(xin, mats[k], None))
+        t_lin += (time.perf_counter() - t0) * (r / min(slab, r))
+    t0 = time.perf_counter()
+    kv.store(0, rows, f16((b, 1, h1), 1.0), f16((b, 1, h1), 1.0))
+    q = x.astype(np.float64).reshape(b, nh, dh)
+    heads = 0
+    for bi in range(b):
+        for h in range(nh):
+            kh, vh = kv.load(bi, h, rows + 1)
+            O.attn_decode(q[bi, h], kh, vh)
+            heads += 1
+        if time.perf_counter() - t0 > budget_s / 2:
+            break
+    t_att = (time.perf_counter() - t0) * (b * nh / max(heads, 1))
+    t_layer = 2 * t_ln + t_lin + t_att
+    t_total = t_layer * sh.l
+    return {"value": b / t_total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "extrapolated: oracle decode step of one layer, 4 sequences, %d cached rows, real widths "
+                      "(h1=%d, h2=%d, %d heads), each projection timed on a 512-row slab of its matrix and scaled "
+                      "to the full matrix, then x%d layers" % (rows + 1, h1, h2, nh, sh.l)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="opt175b_q4", choices=sorted(WORKLOADS))
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; marks the line)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2303_06865_amd import binding as B
+    from paper_2303_06865_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    B.lib()   # fails loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+
+    shape_name, wq, kvq, ngb, gbs, s, n = WORKLOADS[args.workload]
+    sh = getattr(synth, shape_name)
+    if args.layers:
+        sh = synth.Shape(sh.h1, sh.nh, sh.h2, sh.vocab, sh.max_pos, args.layers, sh.ln_eps)
+    bls = ngb * gbs
+    cfg = B.Cfg(sh.h1, sh.nh, sh.h2, sh.vocab, sh.max_pos, sh.ln_eps)
+
+    t_setup = time.time()
+    layers, emb, pos, lnf_g, lnf_b = build_model(sh, wq, args.seed, torch, B)
+    cap = s + n
+    kv = [B.KVCache(cfg, bls, cap, kvq, zero=False) for _ in range(sh.l)]
+    ws = torch.empty(B.fg_workspace_bytes(cfg, layers[0], gbs, ngb, s), dtype=torch.uint8, device="cuda")
+    out_ids = torch.zeros((bls, n), dtype=torch.int32, device="cuda")
+    prompt = torch.from_numpy(synth.prompt_ids(bls, s, sh.vocab, args.seed)).cuda()
+    torch.cuda.synchronize()
+    resident = sum(w.nbytes() for w in layers) + sum(k.nbytes() for k in kv) + emb.numel() * 2 + pos.numel() * 2
+    t_setup = time.time() - t_setup
+
+    def step(want_stats):
+        return B.fg_generate(cfg, layers, emb, pos, lnf_g, lnf_b, prompt, n, ngb, gbs, kv, ws=ws, out_ids=out_ids,
+                             want_stats=want_stats)
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps, per-kernel-class HIP events recorded on the launch stream
+    B.fg_profile_begin()
+    stats = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        stats.append(step(True)[1])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = B.fg_profile_end()
+
+    K = args.steps
+    tokens = bls * n * K
+    value = tokens / elapsed
+    prefill_s = sum(st["prefill_s"] for st in stats) / K
+    decode_s = sum(st["decode_s"] for st in stats) / K
+    step_s = [sum(st["decode_step_s"][i] for st in stats) / K for i in range(n - 1)]
+
+    # ---- algorithmic bytes / flops of each kernel class per generate (Section 4.3 terms, re-priced)
+    P = 4 * sh.h1 * sh.h1 + 2 * sh.h1 * sh.h2
+    w_bytes = sh.l * P * bpe(wq)
+    head_bytes = sh.vocab * sh.h1 * 2.0
+    kv_bytes = [2.0 * bls * sh.l * sh.h1 * (s + i) * bpe(kvq) for i in range(1, n)]
+    alg = {
+        "gemm_large_m": ("mfma", 2.0 * bls * s * P * sh.l),
+        "attn_prefill": ("mfma", 4.0 * bls * s * s * sh.h1 * sh.l / 2.0),
+        "attn_decode": ("hbm", float(sum(kv_bytes))),
+        "gemm_small_m": ("hbm", (n - 1) * (w_bytes + head_bytes) + head_bytes),
+        "kv_append": ("hbm", (2.0 * bls * s * sh.h1 * (2.0 + bpe(kvq)) + (n - 1) * 2.0 * bls * sh.h1 * (2 + bpe(kvq))) * sh.l),
+    }
+    small_flops = 2.0 * bls * ((n - 1) * (sh.l * P + sh.vocab * sh.h1) + sh.vocab * sh.h1)
+    rl = {}
+    for name, (bound, work) in alg.items():
+        if name not in prof:
+            continue
+        ms = prof[name]["ms"] / K
+        peak = HBM_PEAK if bound == "hbm" else MFMA_F16_PEAK
+        ach = work / (ms * 1e-3)
+        rl[name] = {"bound": bound, "achieved": ach / 1e9 if bound == "hbm" else ach / 1e12,
+                    "peak": peak / 1e9 if bound == "hbm" else peak / 1e12,
+                    "unit": "GB/s" if bound == "hbm" else "TFLOP/s", "frac": ach / peak, "traffic": None,
+                    "ms_per_step": ms, "launches_per_step": prof[name]["launches"] / K,
+                    "avg_launch_us": 1e3 * prof[name]["ms"] / prof[name]["launches"]}
+    if "gemm_small_m" in rl:   # the decode projections also have an MFMA bound at large blocks
+        ms = prof["gemm_small_m"]["ms"] / K
+        rl["gemm_small_m"]["mfma_frac"] = small_flops / (ms * 1e-3) / MFMA_F16_PEAK
+    dominant = max(rl, key=lambda k: rl[k]["ms_per_step"]) if rl else None
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        try:
+            tr = json.load(open(traffic_file)).get(args.workload, {})
+            for k, v in tr.items():
+                if k in rl:
+                    rl[k]["traffic"] = v
+        except Exception:
+            pass
+
+    decode = {}
+    if n > 1:
+        pick = sorted(set([0, (n - 1) // 2, n - 2]))
+        decode = {
+            "tokens_per_s": bls * (n - 1) / decode_s,
+            "ms_per_token_step": 1e3 * decode_s / (n - 1),
+            "hbm_frac_avg": (w_bytes + sum(kv_bytes) / (n - 1)) / (decode_s / (n - 1)) / HBM_PEAK,
+            "hbm_frac_at_step": {str(i + 1): (w_bytes + kv_bytes[i]) / step_s[i] / HBM_PEAK for i in pick},
+            "bytes_per_step_avg": w_bytes + sum(kv_bytes) / (n - 1),
+        }
+
+    line = {
+        "metric": "generated tokens/s + % peak HBM BW, 4-bit OPT-175B-shape decode, 1 GPU",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": 1e3 * elapsed / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": args.workload + ("" if not args.layers else "_%dlayers" % args.layers),
+                   "shape": {"l": sh.l, "h1": sh.h1, "nh": sh.nh, "h2": sh.h2, "vocab": sh.vocab},
+                   "weights": "q4g64" if wq else "f16", "kv_cache": "q4g64" if kvq else "f16",
+                   "block": "%dx%d" % (ngb, gbs), "prompt_len": s, "gen_len": n,
+                   "resident_gb": resident / 1e9, "setup_s": t_setup},
+        "prefill_s": prefill_s, "decode_s": decode_s, "decode": decode,
+        "roofline": (dict(rl[dominant], kernel=dominant) if dominant else None),
+        "roofline_kernels": rl,
+        "paper_context": "FlexGen reports 1.12 token/s for OPT-175B (4-bit) on one 16 GB T4 with CPU offloading",
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(sh, wq, kvq, s, n)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
