@@ -145,18 +145,27 @@ __device__ __forceinline__ void unpack8_codes(uint32_t x, h2_t p[4]) {
 // from the real number (Section 5: "converted back to FP16 before computation").
 // A nibble masked in place is the FP16 subnormal c * 2^-24 (low nibble of a half) or c * 2^-20 (next
 // nibble); gfx950 mixed-precision FMAs take FP16 subnormals at full rate, multiply by the pre-scaled
-// s24 = scale * 2^24 / s20 = scale * 2^20 (exact scalings), add mn and round once into an FP16 half.
-// Output pair order: (w0,w4),(w1,w5),(w2,w6),(w3,w7), the order permute8_like_codes gives activations.
-__device__ __forceinline__ void dequant8_exact(uint32_t x, float s24, float s20, float mn, h2_t p[4]) {
+// s24 = scale * 2^24 / s20 = scale * 2^20 (exact scalings), add mn and round once into an FP16 half
+// of the destination (v_fma_mixlo_f16 / v_fma_mixhi_f16).  Thirteen VALU instructions per eight
+// weights.  Output in natural order: p[0] = (w0,w1), p[1] = (w2,w3), p[2] = (w4,w5), p[3] = (w6,w7).
+__device__ __forceinline__ void dequant8_exact(uint32_t x, float s24, float s20, float mn, uint32_t p[4]) {
   const uint32_t y = x >> 8;
-  const h2_t a = __builtin_bit_cast(h2_t, x & 0x000F000Fu);
-  const h2_t b = __builtin_bit_cast(h2_t, x & 0x00F000F0u);
-  const h2_t c = __builtin_bit_cast(h2_t, y & 0x000F000Fu);
-  const h2_t d = __builtin_bit_cast(h2_t, y & 0x00F000F0u);
-  p[0] = (h2_t){(half_t)__builtin_fmaf((float)a.x, s24, mn), (half_t)__builtin_fmaf((float)a.y, s24, mn)};
-  p[1] = (h2_t){(half_t)__builtin_fmaf((float)b.x, s20, mn), (half_t)__builtin_fmaf((float)b.y, s20, mn)};
-  p[2] = (h2_t){(half_t)__builtin_fmaf((float)c.x, s24, mn), (half_t)__builtin_fmaf((float)c.y, s24, mn)};
-  p[3] = (h2_t){(half_t)__builtin_fmaf((float)d.x, s20, mn), (half_t)__builtin_fmaf((float)d.y, s20, mn)};
+  const uint32_t a = x & 0x000F000Fu;   // halves: c0 * 2^-24 , c4 * 2^-24
+  const uint32_t b = x & 0x00F000F0u;   //         c1 * 2^-20 , c5 * 2^-20
+  const uint32_t c = y & 0x000F000Fu;   //         c2 * 2^-24 , c6 * 2^-24
+  const uint32_t d = y & 0x00F000F0u;   //         c3 * 2^-20 , c7 * 2^-20
+  const h2_t ha = __builtin_bit_cast(h2_t, a), hb = __builtin_bit_cast(h2_t, b);
+  const h2_t hc = __builtin_bit_cast(h2_t, c), hd = __builtin_bit_cast(h2_t, d);
+  const h2_t q0 = {(half_t)__builtin_fmaf((float)ha.x, s24, mn), (half_t)__builtin_fmaf((float)hb.x, s20, mn)};
+  const h2_t q1 = {(half_t)__builtin_fmaf((float)hc.x, s24, mn), (half_t)__builtin_fmaf((float)hd.x, s20, mn)};
+  const h2_t q2 = {(half_t)__builtin_fmaf((float)ha.y, s24, mn), (half_t)__builtin_fmaf((float)hb.y, s20, mn)};
+  const h2_t q3 = {(half_t)__builtin_fmaf((float)hc.y, s24, mn), (half_t)__builtin_fmaf((float)hd.y, s20, mn)};
+  const uint32_t r0 = __builtin_bit_cast(uint32_t, q0), r1 = __builtin_bit_cast(uint32_t, q1);
+  const uint32_t r2 = __builtin_bit_cast(uint32_t, q2), r3 = __builtin_bit_cast(uint32_t, q3);
+  p[0] = r0;
+  p[1] = r1;
+  p[2] = r2;
+  p[3] = r3;
 }
 
 // Reorder eight consecutive FP16 values h0..h7 (four words) into the pair order produced by

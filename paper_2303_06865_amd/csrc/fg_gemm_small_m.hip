@@ -157,7 +157,7 @@ __global__ __launch_bounds__(256) void gemm_small_m_kernel(SmallArgs a) {
       for (int c = 0; c < ACH; ++c) {
         const int id = tid + 256 * c;
         const int row = id / CPR, kc = id % CPR;
-        const u4_t v = Q4 ? permute8_like_codes(aq[c]) : aq[c];
+        const u4_t v = aq[c];
         if (id < NCH) *reinterpret_cast<u4_t*>(As + buf * kStage + row * kLdA + kc * 8) = v;
       }
     };
@@ -201,13 +201,10 @@ __global__ __launch_bounds__(256) void gemm_small_m_kernel(SmallArgs a) {
         for (int j = 0; j < kNTW; ++j) {
           h8_t bop;
           if (Q4) {
-            h2_t c[4];
+            uint32_t c[4];
             dequant8_exact(bcur[j][0][i], s24[j], s20[j], mnf[j], c);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              bop[2 * e] = c[e].x;
-              bop[2 * e + 1] = c[e].y;
-            }
+            const u4_t cw = {c[0], c[1], c[2], c[3]};
+            bop = __builtin_bit_cast(h8_t, cw);
           } else {
             bop = __builtin_bit_cast(h8_t, bcur[j][i]);
           }
