@@ -27,6 +27,12 @@
  *             An element is recovered as min + code*scale: weights as the FP16 number nearest to
  *             that value (the projections multiply FP16 by FP16 into binary32), KV rows in
  *             binary32 inside the attention kernel.  0.625 bytes per element.
+ *   FG_Q4G64_TILED  the same codes and pairs as FG_Q4G64, reordered for streaming (weights only;
+ *             made by fg_pack_weights, rows % 32 == 0): for every tile of 32 rows (output columns)
+ *             x 64 columns (one group per row) the 1 KiB of codes is stored contiguously, 16 bytes
+ *             per (row r, half h of the group) at offset 16*(32*h + r); tiles of one row block
+ *             follow each other along the input dimension, row blocks follow each other; meta has
+ *             32 pairs per tile in the same tile order.  Same size as FG_Q4G64.
  */
 #ifndef FG_H
 #define FG_H
@@ -47,12 +53,13 @@ typedef enum {
   FG_ERR_DEVICE = -5       /* a HIP runtime call failed (see fg_last_device_error) */
 } fg_status;
 
-typedef enum { FG_F16 = 0, FG_Q4G64 = 1 } fg_dtype;
+typedef enum { FG_F16 = 0, FG_Q4G64 = 1, FG_Q4G64_TILED = 2 } fg_dtype;
 
 /* A weight matrix [rows = output features, cols = input features], row-major.
  * FG_F16:   data = FP16 values, meta = NULL.
  * FG_Q4G64: data = packed codes (rows*cols/2 bytes), meta = rows*cols/64 {min,scale} pairs;
- *           groups run along cols (the contraction dimension); cols % 64 == 0. */
+ *           groups run along cols (the contraction dimension); cols % 64 == 0.
+ * FG_Q4G64_TILED: the same bytes in the streaming order described above. */
 typedef struct {
   const void* data;
   const void* meta;
@@ -116,6 +123,10 @@ int fg_version(void);
  * binary32 arithmetic, IEEE division, no fused multiply-add. */
 int fg_quantize_groupwise(const void* x_f16, int64_t rows, int64_t cols, int group, int bits,
                           void* codes_out, void* meta_out, void* stream);
+
+/* Reorder a canonical FG_Q4G64 matrix into FG_Q4G64_TILED (same byte counts: rows*cols/2 and
+ * rows*cols/64*8).  src->rows % 32 == 0.  Done once per weight matrix, e.g. at load time. */
+int fg_pack_weights(const fg_mat* src, void* data_out, void* meta_out, void* stream);
 
 /* Inverse map of Section 5 (stored 4-bit -> values before computation): out_f32[r][c] =
  * min + code*scale rounded once to binary32 (a fused multiply-add). */

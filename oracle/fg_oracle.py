@@ -119,6 +119,21 @@ def dequantize_groupwise_f16(codes: np.ndarray, meta: np.ndarray, group: int = G
     return _dequantize_exact(codes, meta, group).astype(np.float16)
 
 
+def tile_weights(codes: np.ndarray, meta: np.ndarray):
+    """The streaming order of a quantized weight matrix (a pure permutation of the canonical bytes):
+    tiles of 32 rows x 64 columns, row blocks outermost, then the tiles of a row block along the
+    columns; inside a tile the 16-byte piece of (row r, half h of the 64-column group) sits at
+    byte 16*(32*h + r); meta: 32 pairs per tile, in the same tile order."""
+    n, kh = codes.shape
+    k = kh * 2
+    assert n % 32 == 0 and k % GROUP == 0
+    ks = k // GROUP
+    c = codes.reshape(n // 32, 32, ks, 2, 16)          # [row block, r, k tile, h, 16 bytes]
+    c = c.transpose(0, 2, 3, 1, 4)                     # [row block, k tile, h, r, 16]
+    m = meta.reshape(n // 32, 32, ks, 2).transpose(0, 2, 1, 3)   # [row block, k tile, r, {min,scale}]
+    return np.ascontiguousarray(c).reshape(n, kh), np.ascontiguousarray(m).reshape(n, ks, 2)
+
+
 # --------------------------------------------------------------------------
 # Section 3 building blocks (float64)
 # --------------------------------------------------------------------------

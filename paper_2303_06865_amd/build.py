@@ -17,6 +17,7 @@ SOURCES = [
     "fg_norm.hip",
     "fg_gemm_small_m.hip",
     "fg_gemm_large_m.hip",
+    "fg_gemm_stream.hip",
     "fg_attn_decode.hip",
     "fg_attn_prefill.hip",
     "fg_layer.hip",

@@ -80,6 +80,11 @@ int linear_launch(const LinearArgs& a, void* ws, size_t ws_bytes, hipStream_t st
 size_t gemm_small_m_workspace(int dtype, int64_t n, int64_t k, int64_t m);
 int gemm_small_m_launch(const LinearArgs& a, void* ws, size_t ws_bytes, hipStream_t stream);
 int gemm_large_m_launch(const LinearArgs& a, hipStream_t stream);
+// tiled 4-bit weights: weight-streaming kernel for few rows, and the repacking kernel
+size_t gemm_stream_workspace(int64_t n, int64_t k, int64_t m);
+int gemm_stream_launch(const LinearArgs& a, void* ws, size_t ws_bytes, hipStream_t stream);
+int pack_weights_launch(const void* codes, const void* meta, int64_t n, int64_t k, void* codes_out, void* meta_out,
+                        hipStream_t stream);
 
 int layernorm_launch(const half_t* x, int64_t ldx, const half_t* g, const half_t* b, int64_t rows,
                      int64_t cols, float eps, half_t* out, int64_t ldo, hipStream_t stream);

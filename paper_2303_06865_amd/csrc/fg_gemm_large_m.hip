@@ -14,8 +14,6 @@
 // under them too.  Tiles are walked in an order that keeps the 32
 // workgroups resident on one XCD inside an 8x4 patch of tiles, so its L2 sees 12 panel streams
 // instead of 64.
-#include <stdlib.h>
-
 #include "fg_common.h"
 
 namespace fg {
@@ -56,8 +54,11 @@ __device__ __forceinline__ void async_copy16(const void* g, half_t* lds_base) {
   __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)lds_base, 16, 0, 0);
 }
 
-template <bool Q4, int DBG = 0>
+// WF: weight format, 0 = FP16, 1 = 4-bit canonical (row-major codes), 2 = 4-bit tiled
+template <int WF>
 __global__ __launch_bounds__(256) void gemm_large_m_kernel(LargeArgs a) {
+  constexpr bool Q4 = WF != 0;
+  constexpr bool TILED = WF == 2;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   half_t* As = reinterpret_cast<half_t*>(smem_raw);   // [2][BM][KS]
   half_t* Bs = As + 2 * STAGE;                        // [2][BN][KS]
@@ -112,19 +113,36 @@ __global__ __launch_bounds__(256) void gemm_large_m_kernel(LargeArgs a) {
       bf_src[c] = reinterpret_cast<const half_t*>(a.w) + (int64_t)col * a.K + swz(prow, lane & 7) * 8;
     }
   }
-  // Q4 weights: 512 pieces of 32 codes per step, 2 per thread: id -> (row = id/2, half = id%2)
+  // Q4 weights: 512 pieces of 32 codes per step, 2 per thread.  Piece id -> (tile row, half of the
+  // 64-element K step): canonical layout (id/2, id%2); tiled layout: 32-column tile id/64, and
+  // inside it the wavefront order of the tile (column id%32, half (id/32)%2), 1 KiB contiguous.
   u4_t gb[2];
   float2 gm[2];
   const uint8_t* bq_src[2];
   const float2* bm_src[2];
+  int bq_row[2], bq_hb[2];
+  constexpr int kBqStep = TILED ? 1024 : KS / 2;   // bytes between K steps
+  constexpr int kBmStep = TILED ? 32 : 1;          // pairs between K steps
   if (Q4) {
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       const int id = tid + 256 * c;
-      int col = n0 + (id >> 1);
-      col = col < a.N ? col : a.N - 1;
-      bq_src[c] = a.w + (int64_t)col * (a.K >> 1) + (id & 1) * 16;
-      bm_src[c] = a.meta + (int64_t)col * (a.K >> 6);
+      if (TILED) {
+        bq_row[c] = (id >> 6) * 32 + (id & 31);
+        bq_hb[c] = (id >> 5) & 1;
+        const int n32 = a.N >> 5;
+        int nt = (n0 >> 5) + (id >> 6);
+        nt = nt < n32 ? nt : n32 - 1;
+        bq_src[c] = a.w + (int64_t)nt * (a.K >> 6) * 1024 + (id & 63) * 16;
+        bm_src[c] = a.meta + (int64_t)nt * (a.K >> 6) * 32 + (id & 31);
+      } else {
+        bq_row[c] = id >> 1;
+        bq_hb[c] = id & 1;
+        int col = n0 + (id >> 1);
+        col = col < a.N ? col : a.N - 1;
+        bq_src[c] = a.w + (int64_t)col * (a.K >> 1) + (id & 1) * 16;
+        bm_src[c] = a.meta + (int64_t)col * (a.K >> 6);
+      }
     }
   }
 
@@ -141,8 +159,8 @@ __global__ __launch_bounds__(256) void gemm_large_m_kernel(LargeArgs a) {
     if (Q4) {
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
-        gb[c] = *reinterpret_cast<const u4_t*>(bq_src[c] + ks * (KS / 2));
-        gm[c] = bm_src[c][ks];
+        gb[c] = *reinterpret_cast<const u4_t*>(bq_src[c] + (int64_t)ks * kBqStep);
+        gm[c] = bm_src[c][(int64_t)ks * kBmStep];
       }
     }
   };
@@ -153,8 +171,7 @@ __global__ __launch_bounds__(256) void gemm_large_m_kernel(LargeArgs a) {
   auto dq_sub = [&](int buf, int piece, int sub) {
     if (!Q4) return;
     const int c = piece >> 2, u = piece & 3;
-    const int id = tid + 256 * c;
-    const int row = id >> 1, hb = id & 1;
+    const int row = bq_row[c], hb = bq_hb[c];
     if (sub == 0) {
       const uint32_t x = gb[c][u], y = x >> 8;
       dq_m[0] = x & 0x000F000Fu;
@@ -207,10 +224,10 @@ __global__ __launch_bounds__(256) void gemm_large_m_kernel(LargeArgs a) {
   int buf = 0;
   for (int ks = 0; ks < nk; ++ks) {
     // The last iteration re-fetches its own tile into the idle stage: no branch in the loop body.
-    const int kn = (DBG & 1) ? 0 : (ks + 1 < nk ? ks + 1 : ks);
-    if (!(DBG & 2)) load_bq(kn);
+    const int kn = ks + 1 < nk ? ks + 1 : ks;
+    load_bq(kn);
     __builtin_amdgcn_sched_barrier(0);   // register loads first: they can then be awaited with the copies in flight
-    if (!(DBG & 2)) issue_async(kn, buf ^ 1);
+    issue_async(kn, buf ^ 1);
     const half_t* At = As + buf * STAGE;
     const half_t* Bt = Bs + buf * STAGE;
     h8_t aop[2][4], bop[2][4];
@@ -224,7 +241,7 @@ __global__ __launch_bounds__(256) void gemm_large_m_kernel(LargeArgs a) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       const int cur = kk & 1, nxt = cur ^ 1;
-      if (kk < 3 && !((DBG & 4) && ks > 0)) {   // operands of the next K slice are fetched under this slice's MFMAs
+      if (kk < 3) {   // operands of the next K slice are fetched under this slice's MFMAs
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           aop[nxt][i] = *reinterpret_cast<const h8_t*>(At + a_off[kk + 1] + i * 32 * KS);
@@ -302,31 +319,21 @@ int gemm_large_m_launch(const LinearArgs& la, hipStream_t stream) {
   const int64_t tiles = (int64_t)a.tm * a.tn;
   const unsigned grid = (unsigned)(ceil_div(tiles, 8) * 8);
   const size_t smem = (size_t)4 * STAGE * sizeof(half_t);   // 128 KiB
-  const bool q4 = la.dtype == FG_Q4G64;
-  static bool attr_done[2] = {false, false};
-  if (!attr_done[q4]) {
-    if (q4)
-      FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_large_m_kernel<true>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    else
-      FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_large_m_kernel<false>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    attr_done[q4] = true;
+  const int wf = la.dtype == FG_F16 ? 0 : (la.dtype == FG_Q4G64 ? 1 : 2);
+  static bool attr_done[3] = {false, false, false};
+  const void* fn = wf == 0 ? (const void*)&gemm_large_m_kernel<0>
+                           : (wf == 1 ? (const void*)&gemm_large_m_kernel<1> : (const void*)&gemm_large_m_kernel<2>);
+  if (!attr_done[wf]) {
+    FG_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    attr_done[wf] = true;
   }
   ProfScope prof(FG_K_GEMM_LARGE_M, stream);
-  static const int dbg = getenv("FG_DBG_LARGE") ? atoi(getenv("FG_DBG_LARGE")) : 0;
-  if (q4 && dbg) {
-    const void* f = dbg == 1 ? (const void*)&gemm_large_m_kernel<true, 1> : dbg == 2 ? (const void*)&gemm_large_m_kernel<true, 2>
-                  : dbg == 4 ? (const void*)&gemm_large_m_kernel<true, 4> : (const void*)&gemm_large_m_kernel<true, 6>;
-    FG_HIP(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    if (dbg == 1) hipLaunchKernelGGL((gemm_large_m_kernel<true, 1>), dim3(grid), dim3(256), smem, stream, a);
-    else if (dbg == 2) hipLaunchKernelGGL((gemm_large_m_kernel<true, 2>), dim3(grid), dim3(256), smem, stream, a);
-    else if (dbg == 4) hipLaunchKernelGGL((gemm_large_m_kernel<true, 4>), dim3(grid), dim3(256), smem, stream, a);
-    else hipLaunchKernelGGL((gemm_large_m_kernel<true, 6>), dim3(grid), dim3(256), smem, stream, a);
-  } else if (q4)
-    hipLaunchKernelGGL(gemm_large_m_kernel<true>, dim3(grid), dim3(256), smem, stream, a);
+  if (wf == 0)
+    hipLaunchKernelGGL(gemm_large_m_kernel<0>, dim3(grid), dim3(256), smem, stream, a);
+  else if (wf == 1)
+    hipLaunchKernelGGL(gemm_large_m_kernel<1>, dim3(grid), dim3(256), smem, stream, a);
   else
-    hipLaunchKernelGGL(gemm_large_m_kernel<false>, dim3(grid), dim3(256), smem, stream, a);
+    hipLaunchKernelGGL(gemm_large_m_kernel<2>, dim3(grid), dim3(256), smem, stream, a);
   FG_LAUNCH_CHECK();
   return FG_OK;
 }

@@ -61,11 +61,12 @@ int check_cfg(const fg_model_cfg* c) {
 }
 
 int check_mat(const fg_mat* w) {
-  if (w->dtype != FG_F16 && w->dtype != FG_Q4G64) return FG_ERR_UNSUPPORTED;
+  if (w->dtype != FG_F16 && w->dtype != FG_Q4G64 && w->dtype != FG_Q4G64_TILED) return FG_ERR_UNSUPPORTED;
   if (w->rows <= 0 || w->cols <= 0 || w->cols % kGroup != 0 || w->rows % 8 != 0) return FG_ERR_SHAPE;
+  if (w->dtype == FG_Q4G64_TILED && w->rows % 32 != 0) return FG_ERR_SHAPE;
   if (w->rows > 0x7fffffff || w->cols > 0x7fffffff) return FG_ERR_SHAPE;
   if (!w->data) return FG_ERR_NULL;
-  if (w->dtype == FG_Q4G64 && !w->meta) return FG_ERR_NULL;
+  if (w->dtype != FG_F16 && !w->meta) return FG_ERR_NULL;
   if (!aligned16(w->data) || (w->meta && !aligned16(w->meta))) return FG_ERR_SHAPE;
   return FG_OK;
 }
@@ -98,13 +99,14 @@ static int check_layer(const fg_model_cfg* cfg, const fg_layer_weights* w) {
 static const int64_t kSmallMLimit = 512;   // rows up to which the weight-streaming kernel is used
 
 size_t linear_workspace_bytes(int dtype, int64_t n, int64_t k, int64_t m) {
-  if (m <= kSmallMLimit) return gemm_small_m_workspace(dtype, n, k, m);
-  return 0;
+  if (m > kSmallMLimit) return 0;
+  return dtype == FG_Q4G64_TILED ? gemm_stream_workspace(n, k, m) : gemm_small_m_workspace(dtype, n, k, m);
 }
 
 int linear_launch(const LinearArgs& a, void* ws, size_t ws_bytes, hipStream_t stream) {
-  if (a.m <= kSmallMLimit) return gemm_small_m_launch(a, ws, ws_bytes, stream);
-  return gemm_large_m_launch(a, stream);
+  if (a.m > kSmallMLimit) return gemm_large_m_launch(a, stream);
+  if (a.dtype == FG_Q4G64_TILED) return gemm_stream_launch(a, ws, ws_bytes, stream);
+  return gemm_small_m_launch(a, ws, ws_bytes, stream);
 }
 
 static LinearArgs make_linear(const fg_mat& w, const void* bias, const half_t* x, int64_t ldx, int64_t m,
@@ -309,6 +311,17 @@ extern "C" int fg_profile_read(int k, double* total_ms, int64_t* launches) {
   if (total_ms) *total_ms = g_prof_ms[k];
   if (launches) *launches = g_prof_n[k];
   return FG_OK;
+}
+
+extern "C" int fg_pack_weights(const fg_mat* src, void* data_out, void* meta_out, void* stream) {
+  if (!src) return FG_ERR_NULL;
+  int rc = check_mat(src);
+  if (rc) return rc;
+  if (src->dtype != FG_Q4G64) return FG_ERR_UNSUPPORTED;
+  if (src->rows % 32 != 0) return FG_ERR_SHAPE;
+  if (!data_out || !meta_out) return FG_ERR_NULL;
+  if (!aligned16(data_out) || !aligned16(meta_out)) return FG_ERR_SHAPE;
+  return pack_weights_launch(src->data, src->meta, src->rows, src->cols, data_out, meta_out, as_stream(stream));
 }
 
 extern "C" size_t fg_linear_workspace_bytes(const fg_mat* w, int64_t m) {
@@ -552,7 +565,7 @@ extern "C" int fg_generate(const fg_model_cfg* cfg, int32_t l, const fg_layer_we
     stats->tokens = (int64_t)bls * n;
     auto mat_bytes = [](const fg_mat& m) -> int64_t {
       const int64_t e = m.rows * m.cols;
-      return m.dtype == FG_Q4G64 ? e / 2 + e / kGroup * 8 : e * 2;
+      return m.dtype != FG_F16 ? e / 2 + e / kGroup * 8 : e * 2;
     };
     int64_t wb = 0;
     for (int j = 0; j < l; ++j)

@@ -78,7 +78,7 @@ def test_layernorm(rows, cols):
 
 
 # ------------------------------------------------------------------ fused dequant + GEMM
-def _linear_case(m, n, k, quant, bias, relu, residual, seed, std_w=0.02, std_x=1.0):
+def _linear_case(m, n, k, quant, bias, relu, residual, seed, std_w=0.02, std_x=1.0, tiled=False):
     w16 = _rand16((n, k), std_w, seed)
     x16 = _rand16((m, k), std_x, seed + 1)
     b16 = _rand16(n, 0.5, seed + 2) if bias else None
@@ -93,6 +93,10 @@ def _linear_case(m, n, k, quant, bias, relu, residual, seed, std_w=0.02, std_x=1
     wm = B.Mat.from_f16(dev(w16), quant)
     if quant:   # the device-made weights are the oracle's bits
         assert np.array_equal(host(wm.data), om.codes) and np.array_equal(host(wm.meta), om.meta)
+    if tiled:
+        wm = wm.tiled()
+        tc, tmeta = O.tile_weights(om.codes, om.meta)
+        assert np.array_equal(host(wm.data), tc) and np.array_equal(host(wm.meta), tmeta)
     out = B.fg_linear(wm, dev(b16), dev(x16), dev(r16), relu)
     torch.cuda.synchronize()
     return host(out), ref
@@ -132,6 +136,29 @@ def test_linear_small_m(m, n, k, bias, relu, residual, quant):
 def test_linear_large_m(m, n, k, bias, relu, residual, quant):
     got, ref = _linear_case(m, n, k, quant, bias, relu, residual, seed=m + n + k)
     assert_close(got, ref, "linear m=%d n=%d k=%d q=%s" % (m, n, k, quant))
+
+
+TILED_CASES = [
+    (1, 256, 128, False, False, False),
+    (4, 768, 768, True, False, True),
+    (4, 3072, 768, True, True, False),
+    (17, 2304, 768, True, False, False),
+    (36, 992, 832, True, False, True),       # ragged column block (992 = 31 tiles of 32)
+    (48, 288, 192, False, True, False),
+    (100, 544, 1024, True, False, False),
+    (144, 1024, 12288, True, False, True),
+    (150, 768, 768, False, False, False),
+    (200, 512, 256, True, True, True),       # two row blocks
+    (300, 800, 448, True, False, True),
+    (600, 768, 768, True, False, True),      # large-M kernel reading tiled weights
+    (1100, 544, 448, True, True, False),
+]
+
+
+@pytest.mark.parametrize("m,n,k,bias,relu,residual", TILED_CASES)
+def test_linear_tiled_weights(m, n, k, bias, relu, residual):
+    got, ref = _linear_case(m, n, k, True, bias, relu, residual, seed=m + n + k, tiled=True)
+    assert_close(got, ref, "tiled linear m=%d n=%d k=%d" % (m, n, k))
 
 
 def test_linear_identity_and_onehot():

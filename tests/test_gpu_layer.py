@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 
 def _run_layer_sequence(sh, quant_w, quant_kv, b, s, steps, seed, biases, random_ln, x_std=0.05, batch=None,
-                        boff=0):
+                        boff=0, tiled=False):
     """Prefill then `steps` decode steps on both sides, the decode inputs being fresh seeded
     activations (the same on both sides).  Before every decode step the device cache is overwritten
     with the oracle's bytes, so each step is compared on identical inputs: the two caches otherwise
@@ -23,7 +23,7 @@ def _run_layer_sequence(sh, quant_w, quant_kv, b, s, steps, seed, biases, random
     ocfg, cfg = cfg_pair(sh)
     t = synth.layer_tensors(sh, seed, 0, std=0.02, biases=biases, random_ln=random_ln)
     ow = oracle_layer(t, quant_w)
-    w = B.LayerWeights.from_numpy(t, quant_w)
+    w = B.LayerWeights.from_numpy(t, quant_w, tiled=tiled)
     batch = batch or b
     cap = s + steps
     okv = O.KVCache.empty(batch, sh.nh, cap, sh.dh, quant_kv)
@@ -49,11 +49,13 @@ def _run_layer_sequence(sh, quant_w, quant_kv, b, s, steps, seed, biases, random
         assert np.all(kg[untouched] == 0) and np.all(vg[untouched] == 0)
 
 
-def test_opt125m_layer_q4_batch4_prompt32_8steps():
+@pytest.mark.parametrize("tiled", [False, True])
+def test_opt125m_layer_q4_batch4_prompt32_8steps(tiled):
     """The small parity configuration: hidden 768, 12 heads x 64, FFN 3072, weights ~N(0,0.02),
-    LN gamma=1/beta=0, 4-bit weights and cache, batch 4, prompt 32, 8 decode steps, seed 0."""
+    LN gamma=1/beta=0, 4-bit weights and cache, batch 4, prompt 32, 8 decode steps, seed 0; with the
+    weights in the canonical and in the streaming (tiled) order."""
     _run_layer_sequence(synth.OPT_125M_LAYER, True, True, b=4, s=32, steps=8, seed=0, biases=False,
-                        random_ln=False, x_std=0.03)
+                        random_ln=False, x_std=0.03, tiled=tiled)
 
 
 @pytest.mark.parametrize("quant_w,quant_kv", [(False, False), (True, False), (False, True)])
@@ -73,12 +75,15 @@ def test_layer_large_m_prefill_path():
     """b*s = 660 rows takes the large-M GEMM kernel in prefill; decode then uses the small-M one."""
     sh = synth.Shape(h1=256, nh=2, h2=1024, vocab=1000, max_pos=512)
     _run_layer_sequence(sh, True, True, b=5, s=132, steps=2, seed=3, biases=True, random_ln=True, x_std=0.5)
+    _run_layer_sequence(sh, True, True, b=5, s=132, steps=2, seed=3, biases=True, random_ln=True, x_std=0.5,
+                        tiled=True)
 
 
 def test_layer_6_7b_shape_slice():
     """Real width of OPT-6.7B (hidden 4096, 32 heads x 128, FFN 16384), two sequences."""
     sh = synth.Shape(h1=4096, nh=32, h2=16384, vocab=1000, max_pos=64)
-    _run_layer_sequence(sh, True, True, b=2, s=20, steps=2, seed=4, biases=False, random_ln=False, x_std=0.5)
+    _run_layer_sequence(sh, True, True, b=2, s=20, steps=2, seed=4, biases=False, random_ln=False, x_std=0.5,
+                        tiled=True)
 
 
 def test_prefill_then_decode_consistency_on_gpu_fp16():

@@ -194,3 +194,25 @@ def test_rejects_bad_arguments():
     bad[0, 3] = np.inf
     with pytest.raises(ValueError):
         O.quantize_groupwise(bad)
+
+
+def test_tiled_order_is_the_documented_permutation():
+    """Element by element in plain Python: piece (row, k-tile, half) of the canonical layout lands at
+    byte ((row//32 * ktiles + ktile) * 64 + 32*half + row%32) * 16 of the tiled one."""
+    n, k = 64, 192
+    rng = np.random.default_rng(3)
+    codes = rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8)
+    meta = rng.standard_normal((n, k // 64, 2)).astype(np.float32)
+    tc, tm = O.tile_weights(codes, meta)
+    assert tc.shape == codes.shape and tm.shape == meta.shape
+    flat, mflat = tc.reshape(-1), tm.reshape(-1, 2)
+    kt = k // 64
+    for row in range(n):
+        for t in range(kt):
+            tile = (row // 32) * kt + t
+            assert np.array_equal(mflat[tile * 32 + row % 32], meta[row, t])
+            for h in range(2):
+                src = codes[row, t * 32 + h * 16: t * 32 + h * 16 + 16]
+                dst = (tile * 64 + 32 * h + row % 32) * 16
+                assert np.array_equal(flat[dst:dst + 16], src)
+    assert sorted(flat.tolist()) == sorted(codes.reshape(-1).tolist())
