@@ -10,10 +10,12 @@
 // contiguous kilobytes, like the decode attention does.  Same bytes, same 0.625 B/element.
 //
 // Kernel: out[M, N] = act(x[M, K] . W^T + bias) + residual for M <= 160 per row block.
-//   * 4 waves, each owning 64 output columns (two 32-column tiles) and all rows: the activation tile
-//     is copied global -> LDS asynchronously (4 stages, XOR-swizzled) and shared as the A operand;
-//     weights go HBM -> registers -> exact FP16 (in registers) -> MFMA B operand, prefetched three K
-//     steps ahead, so ~6 KiB per wave are in flight at any time.
+//   * 4 waves, each owning 64 output columns (two 32-column tiles) and all rows.  Everything is
+//     copied global -> LDS asynchronously, without registers, five stages deep: the activation tile
+//     (XOR-swizzled, shared by the waves as the A operand) and each wave's own two weight tiles
+//     (1 KiB of codes + 256 B of {min,scale} each, one wave-wide copy apiece).  A wave reads its
+//     codes back one step ahead, dequantizes them exactly in registers and feeds them to the MFMA as
+//     the B operand; ~10 KiB per wave are in flight at any time.
 //   * stream-K over a fixed grid with a deterministic second-pass reduction, as in the canonical
 //     small-M kernel.
 #include "fg_common.h"
@@ -24,8 +26,9 @@ namespace {
 
 constexpr int kBN = 256;      // output columns per workgroup (4 waves x 2 tiles x 32)
 constexpr int kKS = 64;       // K elements per step = one quantization group
-constexpr int kPD = 3;        // prefetch distance in K steps
-constexpr int kNST = kPD + 1; // LDS stages of the activation tile
+constexpr int kPD = 4;        // prefetch distance in K steps
+constexpr int kNST = kPD + 1; // LDS stages (activation tile + this workgroup's weight tiles)
+constexpr int kBStage = 4 * 2 * (1024 + 256);   // bytes of weight codes + meta per stage (8 tiles)
 constexpr int kMaxMT = 5;     // 32-row tiles per workgroup tile (160 rows)
 
 struct StreamArgs {
@@ -53,14 +56,54 @@ __device__ __forceinline__ int swz(int row, int kc) { return kc ^ ((row >> 1) & 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
+// The compiler orders every LDS read it can see behind ALL outstanding asynchronous global -> LDS
+// copies (it cannot tell which copy an address belongs to), which would drain the prefetch queue on
+// every step.  The stages are therefore read with hand-placed ds_read instructions; the explicit
+// vmcnt wait plus the barrier at the top of each step are what make the data visible.
+template <int OFF>
+__device__ __forceinline__ u4_t lds_read128(uint32_t addr) {
+  u4_t r;
+  __asm__ volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+  return r;
+}
+template <int OFF>
+__device__ __forceinline__ float2 lds_read64(uint32_t addr) {
+  float2 r;
+  __asm__ volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+  return r;
+}
+// all ds_reads issued so far have landed
+__device__ __forceinline__ void lds_wait() { __asm__ volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+// makes later uses of v depend on a point after the preceding lds_wait()
+template <class T>
+__device__ __forceinline__ void lds_landed(T& v) {
+  __asm__ volatile("" : "+v"(v));
+}
+template <int I>
+struct IdxC {
+  static constexpr int value = I;
+};
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(IdxC<B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+
 template <int MT>
 __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
-  constexpr int kStage = MT * 32 * kKS;          // halves per LDS stage
-  constexpr int kWait = (kPD - 1) * (MT + 4);    // VMEM ops a wave issues after the copies of a step
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  half_t* As = reinterpret_cast<half_t*>(smem_raw);   // [kNST][MT*32][64]
+  constexpr int kAStage = MT * 32 * kKS * 2;            // bytes of the activation tile per stage
+  constexpr int kStageBytes = kAStage + kBStage;
+  constexpr int kCopies = MT + 4;                       // wave-wide copies a wave issues per K step
+  // Outstanding copies allowed when step ks+1 must have landed (end of slice 2 of step ks): those of
+  // steps ks+2 .. ks+4 and the weight copies of step ks+5.
+  constexpr int kWait = (kNST - 2) * kCopies + 4;
+  constexpr int kNM = 2 * MT;                           // MFMAs per K slice
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [kNST][A tile | B tiles]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, kb = lane >> 5;
 
   const int p = (blockIdx.x & 7) * (a.grid >> 3) + (blockIdx.x >> 3);
@@ -71,7 +114,11 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
   // operand read offsets inside a stage: lane (l32, kb) reads logical chunk 4*kb + kk of row 32*m + l32
   int a_off[4];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) a_off[kk] = l32 * kKS + swz(l32, 4 * kb + kk) * 8;
+  for (int kk = 0; kk < 4; ++kk) a_off[kk] = (l32 * kKS + swz(l32, 4 * kb + kk) * 8) * 2;
+  // this wave's weight tiles inside a stage
+  const int bq_off = kAStage + wave * 2 * 1024 + lane * 16;      // + j * 1024
+  const int bm_off = kAStage + 8 * 1024 + wave * 2 * 256 + l32 * 8;   // + j * 256
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
 
   while (pos < pos_end) {
     const int64_t tile = pos / a.ksteps;
@@ -102,91 +149,190 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
       a_src[i] = a.x + (int64_t)row * a.ldx + swz(prow, lane & 7) * 8;
     }
     const uint8_t* w_src[2];
-    const float2* m_src[2];
+    const float* m_src[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       int nt = nt0 + j;
       nt = nt < a.n32 ? nt : a.n32 - 1;   // ragged last column block: load valid data, never store it
       w_src[j] = a.w + (int64_t)nt * a.ksteps * 1024 + lane * 16;
-      m_src[j] = a.meta + (int64_t)nt * a.ksteps * 32 + l32;
+      m_src[j] = reinterpret_cast<const float*>(a.meta) + (int64_t)nt * a.ksteps * 64 + lane;
     }
 
-    u4_t bq[kPD][2];
-    float2 bm[kPD][2];
-    auto issue = [&](int ks, int stage, u4_t* q, float2* mm) {
-      const int kc = ks < ks1 ? ks : ks1 - 1;   // past the end: harmless re-fetch, keeps VMEM counts uniform
-#pragma unroll
-      for (int i = 0; i < MT; ++i)
-        __builtin_amdgcn_global_load_lds((gptr_t)(a_src[i] + kc * kKS),
-                                         (lptr_t)(As + stage * kStage + (wave + 4 * i) * 8 * kKS), 16, 0, 0);
+    // The kCopies wave-wide asynchronous global -> LDS transfers of one K step.  Past the end of the
+    // segment the last step is fetched again: harmless, and it keeps the VMEM counts uniform.
+    auto copy_a = [&](int i, int ks, int stage) {
+      const int kc = ks < ks1 ? ks : ks1 - 1;
+      __builtin_amdgcn_global_load_lds((gptr_t)(a_src[i] + kc * kKS),
+                                       (lptr_t)(smem + stage * kStageBytes + (wave + 4 * i) * 8 * kKS * 2), 16, 0, 0);
+    };
+    auto copy_b = [&](int c, int ks, int stage) {   // c = 2 * j + (0: codes, 1: {min, scale})
+      const int kc = ks < ks1 ? ks : ks1 - 1;
+      const int j = c >> 1;
+      unsigned char* st = smem + stage * kStageBytes + kAStage;
+      if ((c & 1) == 0)
+        __builtin_amdgcn_global_load_lds((gptr_t)(w_src[j] + (int64_t)kc * 1024), (lptr_t)(st + (wave * 2 + j) * 1024),
+                                         16, 0, 0);
+      else
+        __builtin_amdgcn_global_load_lds((gptr_t)(m_src[j] + (int64_t)kc * 64),
+                                         (lptr_t)(st + 8 * 1024 + (wave * 2 + j) * 256), 4, 0, 0);
+    };
+    u4_t cq[2];
+    float2 cm[2];
+    auto read_b = [&](int stage) {
+      const uint32_t st = lds0 + stage * kStageBytes;
+      cq[0] = lds_read128<0>(st + bq_off);
+      cq[1] = lds_read128<1024>(st + bq_off);
+      cm[0] = lds_read64<0>(st + bm_off);
+      cm[1] = lds_read64<256>(st + bm_off);
+    };
+    // operand slice kk of all MT row tiles of a stage
+    auto read_a = [&](uint32_t st, int kk, h8_t* dst) {
+      const uint32_t ad = st + a_off[kk];
+      static_for<0, MT>([&](auto m) {
+        constexpr int off = decltype(m)::value * 32 * kKS * 2;
+        dst[decltype(m)::value] = __builtin_bit_cast(h8_t, lds_read128<off>(ad));
+      });
+    };
+    h8_t aop[2][MT];
+    uint32_t bop[2][2][4];
+    float s24[2], s20[2], mn[2];
+    uint32_t msk[4];
+    // Exact dequantization (fg_common.h: dequant8_exact) of word kk of tile j, cut into three pieces so
+    // that it can be spread between MFMAs: 0 = masks, 1 = weights 0..3, 2 = weights 4..7.
+    auto dq = [&](int kk, int j, int sub, int buf) {
+      if (sub == 0) {
+        const uint32_t x = cq[j][kk], y = x >> 8;
+        msk[0] = x & 0x000F000Fu;
+        msk[1] = x & 0x00F000F0u;
+        msk[2] = y & 0x000F000Fu;
+        msk[3] = y & 0x00F000F0u;
+      } else {
+        const h2_t ha = __builtin_bit_cast(h2_t, msk[0]), hb = __builtin_bit_cast(h2_t, msk[1]);
+        const h2_t hc = __builtin_bit_cast(h2_t, msk[2]), hd = __builtin_bit_cast(h2_t, msk[3]);
+        if (sub == 1) {
+          const h2_t q0 = {(half_t)__builtin_fmaf((float)ha.x, s24[j], mn[j]), (half_t)__builtin_fmaf((float)hb.x, s20[j], mn[j])};
+          const h2_t q1 = {(half_t)__builtin_fmaf((float)hc.x, s24[j], mn[j]), (half_t)__builtin_fmaf((float)hd.x, s20[j], mn[j])};
+          bop[buf][j][0] = __builtin_bit_cast(uint32_t, q0);
+          bop[buf][j][1] = __builtin_bit_cast(uint32_t, q1);
+        } else {
+          const h2_t q2 = {(half_t)__builtin_fmaf((float)ha.y, s24[j], mn[j]), (half_t)__builtin_fmaf((float)hb.y, s20[j], mn[j])};
+          const h2_t q3 = {(half_t)__builtin_fmaf((float)hc.y, s24[j], mn[j]), (half_t)__builtin_fmaf((float)hd.y, s20[j], mn[j])};
+          bop[buf][j][2] = __builtin_bit_cast(uint32_t, q2);
+          bop[buf][j][3] = __builtin_bit_cast(uint32_t, q3);
+        }
+      }
+    };
+    // the freshly read {min, scale} pairs -> FMA constants
+    auto set_meta = [&]() {
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        q[j] = *reinterpret_cast<const u4_t*>(w_src[j] + (int64_t)kc * 1024);
-        mm[j] = m_src[j][(int64_t)kc * 32];
+        s24[j] = cm[j].y * 16777216.0f;
+        s20[j] = cm[j].y * 1048576.0f;
+        mn[j] = cm[j].x;
       }
     };
 
-    __syncthreads();   // the previous segment no longer reads any stage
+    // no copy of the previous segment may still be in flight towards a stage, and no wave still reads one
+    __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
 #pragma unroll
-    for (int t = 0; t < kPD; ++t) issue(ks0 + t, t, bq[t], bm[t]);
+    for (int t = 0; t < kNST; ++t) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) copy_b(c, ks0 + t, t);
+#pragma unroll
+      for (int i = 0; i < MT; ++i) copy_a(i, ks0 + t, t);
+    }
+    __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"((kNST - 1) * kCopies) : "memory");
+    __builtin_amdgcn_s_barrier();
+    read_a(lds0, 0, aop[0]);
+    read_b(0);
+    lds_wait();
+#pragma unroll
+    for (int m = 0; m < MT; ++m) lds_landed(aop[0][m]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      lds_landed(cq[j]);
+      lds_landed(cm[j]);
+    }
+    set_meta();
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int sub = 0; sub < 3; ++sub) dq(0, j, sub, 0);
 
+    // Steady state.  At the top of a step the operands of its first K slice are already in registers.
+    // Every slice issues its MFMAs with the preparation of the NEXT slice spread between them (a wave
+    // issues in order, and an MFMA occupies the matrix pipe for 32 cycles: a few independent
+    // instructions after each one are free, a block of them is not):
+    //   slices 0..2: LDS reads of the next A slice, dequantization of the next code word, and (slices
+    //                0, 1) the weight copies of step ks+5 into this wave's private part of the stage
+    //                whose weights were consumed one step ago;
+    //   end of 2   : this wave's copies of step ks+1 have landed (vmcnt), barrier: now every wave's
+    //                have, and nobody reads the A tile of this stage any more;
+    //   slice 3    : A copies of step ks+5 into this stage, LDS reads of step ks+1 (first A slice,
+    //                codes, meta), then dequantization of its first code word.
     int stage = 0;
     for (int ks = ks0; ks < ks1; ++ks) {
-      // copies and weights of this step were issued kPD steps ago; everything issued since may still fly
-      __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"(kWait) : "memory");
-      __syncthreads();
-      u4_t cq[2] = {bq[0][0], bq[0][1]};
-      float s24[2], s20[2], mn[2];
+      const int stage1 = stage + 1 == kNST ? 0 : stage + 1;
+      const uint32_t At = lds0 + stage * kStageBytes;
+      static_for<0, 4>([&](auto KK) __attribute__((always_inline)) {
+        constexpr int kk = decltype(KK)::value;
+        constexpr int cur = kk & 1, nxt = cur ^ 1;
+        if constexpr (kk < 3) {
+          read_a(At, kk + 1, aop[nxt]);
+        } else {
+          read_a(lds0 + stage1 * kStageBytes, 0, aop[nxt]);
+          read_b(stage1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        constexpr int n_items = kk < 2 ? 8 : 6;   // slices 0..2: six dequantization pieces (+ two weight copies)
+        static_for<0, kNM>([&](auto I) __attribute__((always_inline)) {
+          constexpr int i = decltype(I)::value;
+          constexpr int j = i / MT, m = i - j * MT;
+          const u4_t bw = {bop[cur][j][0], bop[cur][j][1], bop[cur][j][2], bop[cur][j][3]};
+          acc[m][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[cur][m], __builtin_bit_cast(h8_t, bw), acc[m][j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if constexpr (kk < 3) {
+            static_for<i * n_items / kNM, (i + 1) * n_items / kNM>([&](auto IT) __attribute__((always_inline)) {
+              constexpr int it = decltype(IT)::value;
+              if constexpr (it < 6)
+                dq(kk + 1, it / 3, it % 3, nxt);
+              else
+                copy_b(kk * 2 + it - 6, ks + kNST, stage);
+            });
+          } else if constexpr (i < MT) {
+            copy_a(i, ks + kNST, stage);
+            if constexpr (i == MT - 1) {
+              lds_wait();
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        s24[j] = bm[0][j].y * 16777216.0f;
-        s20[j] = bm[0][j].y * 1048576.0f;
-        mn[j] = bm[0][j].x;
-      }
+              for (int mm = 0; mm < MT; ++mm) lds_landed(aop[nxt][mm]);
 #pragma unroll
-      for (int t = 0; t + 1 < kPD; ++t) {
-        bq[t][0] = bq[t + 1][0];
-        bq[t][1] = bq[t + 1][1];
-        bm[t][0] = bm[t + 1][0];
-        bm[t][1] = bm[t + 1][1];
-      }
-      int nstage = stage + kPD;
-      nstage = nstage >= kNST ? nstage - kNST : nstage;
-      issue(ks + kPD, nstage, bq[kPD - 1], bm[kPD - 1]);
-      __builtin_amdgcn_sched_barrier(0);
-
-      const half_t* At = As + stage * kStage;
-      h8_t aop[2][MT];
-      uint32_t bop[2][2][4];
+              for (int jj = 0; jj < 2; ++jj) {
+                lds_landed(cq[jj]);
+                lds_landed(cm[jj]);
+              }
+              set_meta();
+            }
+          } else {
+            static_for<(i - MT) * 6 / MT, (i - MT + 1) * 6 / MT>([&](auto IT) __attribute__((always_inline)) {
+              constexpr int it = decltype(IT)::value;
+              dq(0, it / 3, it % 3, nxt);
+            });
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        });
+        if constexpr (kk < 3) {
+          lds_wait();
 #pragma unroll
-      for (int m = 0; m < MT; ++m) aop[0][m] = *reinterpret_cast<const h8_t*>(At + m * 32 * kKS + a_off[0]);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) dequant8_exact(cq[j][0], s24[j], s20[j], mn[j], bop[0][j]);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int cur = kk & 1, nxt = cur ^ 1;
-        if (kk < 3) {
-#pragma unroll
-          for (int m = 0; m < MT; ++m)
-            aop[nxt][m] = *reinterpret_cast<const h8_t*>(At + m * 32 * kKS + a_off[kk + 1]);
+          for (int m = 0; m < MT; ++m) lds_landed(aop[nxt][m]);
+          if constexpr (kk == 2) {
+            __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"(kWait) : "memory");
+            __builtin_amdgcn_s_barrier();   // bare barrier: no fence, the copies in flight stay in flight
+          }
           __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const u4_t bw = {bop[cur][j][0], bop[cur][j][1], bop[cur][j][2], bop[cur][j][3]};
-          const h8_t bv = __builtin_bit_cast(h8_t, bw);
-#pragma unroll
-          for (int m = 0; m < MT; ++m)
-            acc[m][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[cur][m], bv, acc[m][j], 0, 0, 0);
-          if (kk < 3) {   // next slice's weights are dequantized in the shadow of these MFMAs
-            __builtin_amdgcn_sched_barrier(0);
-            dequant8_exact(cq[j][kk + 1], s24[j], s20[j], mn[j], bop[nxt][j]);
-            __builtin_amdgcn_sched_barrier(0);
-          }
-        }
-      }
-      stage = stage + 1 == kNST ? 0 : stage + 1;
+      });
+      stage = stage1;
     }
 
     // ---- epilogue: lane holds column l32 of each 32x32 tile, rows 8*(r/4) + 4*kb + r%4
@@ -197,34 +343,43 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
         const int col = (nt0 + j) * 32 + l32;
         if (nt0 + j < a.n32) {
           const float bvv = a.bias ? (float)a.bias[col] : 0.f;
+          // running offsets instead of 16 * MT independent ones (which would all be kept in registers)
+          int row = m0 + kb * 4;
+          int64_t o_off = (int64_t)row * a.ldo + col, r_off = (int64_t)row * a.ldr + col;
 #pragma unroll
           for (int m = 0; m < MT; ++m) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-              const int row = m0 + m * 32 + (r >> 2) * 8 + kb * 4 + (r & 3);
               if (row < a.M) {
                 float v = acc[m][j][r] + bvv;
                 if (a.relu) v = fmaxf(v, 0.f);
-                if (a.residual) v += (float)a.residual[(int64_t)row * a.ldr + col];
+                if (a.residual) v += (float)a.residual[r_off];
                 if (a.out32)
-                  a.out32[(int64_t)row * a.ldo + col] = v;
+                  a.out32[o_off] = v;
                 else
-                  a.out16[(int64_t)row * a.ldo + col] = (half_t)v;
+                  a.out16[o_off] = (half_t)v;
               }
+              const int step = (r & 3) == 3 ? 5 : 1;   // rows 8*(r/4) + 4*kb + r%4
+              row += step;
+              o_off += step * a.ldo;
+              r_off += step * a.ldr;
             }
           }
         }
       }
     } else {
-      float* dst = a.partial + ((int64_t)p * 2 + (seg == 0 ? 0 : 1)) * (MT * 32 * kBN);
+      // partial sums in register order: float4 number ((m*2 + j)*4 + q) of thread tid holds rows
+      // 32m + 8q + 4kb + 0..3 of column (2*wave + j)*32 + l32 -> every store is 1 KiB contiguous per wave
+      float4* dst = reinterpret_cast<float4*>(a.partial + ((int64_t)p * 2 + (seg == 0 ? 0 : 1)) * (MT * 32 * kBN)) + tid;
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int cl = (wave * 2 + j) * 32 + l32;
+      for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int m = 0; m < MT; ++m)
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-          for (int r = 0; r < 16; ++r) dst[(m * 32 + (r >> 2) * 8 + kb * 4 + (r & 3)) * kBN + cl] = acc[m][j][r];
-      }
+          for (int q = 0; q < 4; ++q) {
+            *dst = make_float4(acc[m][j][4 * q], acc[m][j][4 * q + 1], acc[m][j][4 * q + 2], acc[m][j][4 * q + 3]);
+            dst += 256;
+          }
     }
     pos += ks1 - ks0;
     ++seg;
@@ -233,7 +388,8 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
 }
 
 // Second pass of the stream-K schedule: tiles whose K range was shared get their partial sums added
-// in ascending K order, then the epilogue.  One thread per four columns.
+// in ascending K order, then the epilogue.  Thread tid of a block takes the float4s that thread tid of
+// the GEMM kernel wrote (four rows of one column each).
 __global__ __launch_bounds__(256) void gemm_stream_finish_kernel(StreamArgs a, int mt) {
   const int64_t tile = blockIdx.x;
   const int64_t w0 = tile * a.ksteps, w1 = w0 + a.ksteps;
@@ -246,37 +402,38 @@ __global__ __launch_bounds__(256) void gemm_stream_finish_kernel(StreamArgs a, i
 
   const int n_tile = (int)(tile / a.m_blocks);
   const int mblk = (int)(tile - (int64_t)n_tile * a.m_blocks);
-  const int rows_t = mt * 32;
-  const int m0 = mblk * rows_t;
-  const int64_t slot = (int64_t)rows_t * kBN;
-  const int n_quads = rows_t * (kBN / 4);
-  for (int e = threadIdx.x + blockIdx.y * 256; e < n_quads; e += 256 * gridDim.y) {
-    const int r = e / (kBN / 4), c = (e - r * (kBN / 4)) * 4;
-    const int row = m0 + r, col = n_tile * kBN + c;
-    if (row >= a.M || col >= a.N) continue;   // N % 32 == 0, so a quad is inside or outside as a whole
+  const int m0 = mblk * mt * 32;
+  const int64_t slot = (int64_t)mt * 32 * kBN;
+  const int tid = threadIdx.x, wave = tid >> 6, l32 = tid & 31, kb = (tid >> 5) & 1;
+  for (int e = blockIdx.y; e < mt * 8; e += gridDim.y) {   // e = (m*2 + j)*4 + q
+    const int m = e >> 3, j = (e >> 2) & 1, q = e & 3;
+    const int row0 = m0 + m * 32 + q * 8 + kb * 4;
+    const int col = n_tile * kBN + (wave * 2 + j) * 32 + l32;
+    if (row0 >= a.M || col >= a.N) continue;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int p = p_lo; p <= p_hi; ++p) {
       const int64_t pb = work_begin(a.total_work, a.grid, p);
       if (work_begin(a.total_work, a.grid, p + 1) == pb) continue;
       const int s = pb >= w0 ? 0 : 1;
-      const float4 t = *reinterpret_cast<const float4*>(a.partial + ((int64_t)p * 2 + s) * slot + (int64_t)r * kBN + c);
+      const float4 t = reinterpret_cast<const float4*>(a.partial + ((int64_t)p * 2 + s) * slot)[e * 256 + tid];
       v.x += t.x;
       v.y += t.y;
       v.z += t.z;
       v.w += t.w;
     }
-    float o[4] = {v.x, v.y, v.z, v.w};
+    const float o[4] = {v.x, v.y, v.z, v.w};
+    const float bvv = a.bias ? (float)a.bias[col] : 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if (a.bias) o[i] += (float)a.bias[col + i];
-      if (a.relu) o[i] = fmaxf(o[i], 0.f);
-      if (a.residual) o[i] += (float)a.residual[(int64_t)row * a.ldr + col + i];
-    }
-    if (a.out32) {
-      *reinterpret_cast<float4*>(a.out32 + (int64_t)row * a.ldo + col) = make_float4(o[0], o[1], o[2], o[3]);
-    } else {
-      h4_t h = {(half_t)o[0], (half_t)o[1], (half_t)o[2], (half_t)o[3]};
-      *reinterpret_cast<h4_t*>(a.out16 + (int64_t)row * a.ldo + col) = h;
+      const int row = row0 + i;
+      if (row >= a.M) break;
+      float x = o[i] + bvv;
+      if (a.relu) x = fmaxf(x, 0.f);
+      if (a.residual) x += (float)a.residual[(int64_t)row * a.ldr + col];
+      if (a.out32)
+        a.out32[(int64_t)row * a.ldo + col] = x;
+      else
+        a.out16[(int64_t)row * a.ldo + col] = (half_t)x;
     }
   }
 }
@@ -313,7 +470,7 @@ int pick_mt(int64_t m) {
 
 template <int MT>
 int launch_t(const StreamArgs& a, hipStream_t stream) {
-  const size_t smem = (size_t)kNST * MT * 32 * kKS * sizeof(half_t);
+  const size_t smem = (size_t)kNST * (MT * 32 * kKS * sizeof(half_t) + kBStage);
   static bool attr_done = false;
   if (!attr_done) {
     FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MT>),
@@ -375,7 +532,7 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   }
   {
     ProfScope prof(FG_K_GEMM_SMALL_M_FINISH, stream);
-    hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3(a.m_blocks * a.n_tiles, mt >= 3 ? 4 : 2), dim3(256), 0, stream,
+    hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3(a.m_blocks * a.n_tiles, mt >= 3 ? 8 : 4), dim3(256), 0, stream,
                        a, mt);
     FG_LAUNCH_CHECK();
   }
