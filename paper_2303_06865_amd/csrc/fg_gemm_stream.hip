@@ -1,5 +1,6 @@
-// Decode-phase projections on TILED 4-bit weights (Section 3 decode: t.wQ, t.wK, t.wV, .wO, .w1, .w2;
-// weights stored as in Section 5), and the one-time repacking that produces the tiled layout.
+// Projections on TILED 4-bit weights (Section 3: t.wQ, t.wK, t.wV, .wO, .w1, .w2 in the prefill and
+// the decode phase; weights stored as in Section 5), and the one-time repacking that produces the
+// tiled layout.
 //
 // Why a second layout: in the canonical row-major format the 64 codes one lane pair needs per K step
 // are 32 bytes of a row, and neighbouring rows are K/2 bytes apart, so a weight-streaming kernel
@@ -9,27 +10,31 @@
 // codes k = 32*(l/32) .. +32), tiles of one column block consecutive along K.  A wave then streams
 // contiguous kilobytes, like the decode attention does.  Same bytes, same 0.625 B/element.
 //
-// Kernel: out[M, N] = act(x[M, K] . W^T + bias) + residual for M <= 160 per row block.
-//   * 4 waves, each owning 64 output columns (two 32-column tiles) and all rows.  Everything is
-//     copied global -> LDS asynchronously, without registers, five stages deep: the activation tile
-//     (XOR-swizzled, shared by the waves as the A operand) and each wave's own two weight tiles
-//     (1 KiB of codes + 256 B of {min,scale} each, one wave-wide copy apiece).  A wave reads its
-//     codes back one step ahead, dequantizes them exactly in registers and feeds them to the MFMA as
-//     the B operand; ~10 KiB per wave are in flight at any time.
-//   * stream-K over a fixed grid with a deterministic second-pass reduction, as in the canonical
-//     small-M kernel.
+// Kernel: out[M, N] = act(x[M, K] . W^T + bias) + residual.  One kernel template, two shapes:
+//   decode   M <= 160 per row block: 4 waves side by side, each all rows x 64 columns
+//            (MT = 1..5 row tiles of 32, NT = 2 column tiles, WM = 1);
+//   prefill  row blocks of 256: 2 x 2 waves, each 128 rows x 128 columns (MT = 4, NT = 4, WM = 2).
+//   * Nothing but MFMA operands passes through registers.  The activation tile (XOR-swizzled, the A
+//     operand) and the weight tiles (1 KiB of codes + 256 B of {min,scale} each) are copied
+//     global -> LDS asynchronously, several K steps ahead.  A wave reads its codes back, dequantizes
+//     them exactly in registers (no LDS round trip for FP16 weights) and feeds them to the MFMA as
+//     the B operand.
+//   * Work = (output tile, K step) pairs.  Whole rounds of tiles go one tile per workgroup, walked in
+//     groups of 8 row blocks so that concurrently running workgroups share activations and weights
+//     in L2; the remaining tiles are cut stream-K fashion into equal contiguous ranges with a
+//     deterministic second-pass reduction.  The grid is always 256 workgroups, one per CU.
 #include "fg_common.h"
 
 namespace fg {
 
 namespace {
 
-constexpr int kBN = 256;      // output columns per workgroup (4 waves x 2 tiles x 32)
+constexpr int kBN = 256;      // output columns per workgroup
 constexpr int kKS = 64;       // K elements per step = one quantization group
-constexpr int kPD = 4;        // prefetch distance in K steps
-constexpr int kNST = kPD + 1; // LDS stages (activation tile + this workgroup's weight tiles)
-constexpr int kBStage = 4 * 2 * (1024 + 256);   // bytes of weight codes + meta per stage (8 tiles)
-constexpr int kMaxMT = 5;     // 32-row tiles per workgroup tile (160 rows)
+constexpr int kBStage = 8 * (1024 + 256);   // bytes of weight codes + meta per stage (8 column tiles)
+constexpr int kMaxMT = 5;     // decode shape: up to 5 row tiles of 32 (160 rows)
+constexpr int kGroupM = 8;    // row blocks per group in the tile walk
+constexpr int kLdsBytes = 160 * 1024;
 
 struct StreamArgs {
   const uint8_t* w;     // tiled codes
@@ -38,7 +43,8 @@ struct StreamArgs {
   int64_t ldx;
   int M, N, K;
   int m_blocks, n_tiles, ksteps, n32;   // n32 = N / 32
-  int64_t total_work;
+  int rounds;           // whole rounds: tiles [0, rounds*grid) go one per workgroup per round
+  int64_t rem_work;     // (remaining tiles) * ksteps, cut into grid equal ranges
   int grid;
   const half_t* bias;
   const half_t* residual;
@@ -47,11 +53,23 @@ struct StreamArgs {
   half_t* out16;
   float* out32;
   int64_t ldo;
-  float* partial;       // [grid][2][MT*32][256]
+  float* partial;       // [grid][2][block rows][256]
 };
 
 __device__ __forceinline__ int64_t work_begin(int64_t total, int grid, int p) { return (total * p) / grid; }
 __device__ __forceinline__ int swz(int row, int kc) { return kc ^ ((row >> 1) & 7); }
+
+// linear tile number -> (row block, column block): groups of kGroupM row blocks, inside a group the
+// row block runs fastest, so 32 consecutive tiles (one XCD's share of a round) form an 8 x 4 patch
+__device__ __forceinline__ void tile_coords(int64_t t, int m_blocks, int n_tiles, int& mblk, int& n_tile) {
+  const int64_t per_group = (int64_t)kGroupM * n_tiles;
+  const int g = (int)(t / per_group);
+  const int first = g * kGroupM;
+  const int gm = m_blocks - first < kGroupM ? m_blocks - first : kGroupM;
+  const int r = (int)(t - (int64_t)g * per_group);
+  mblk = first + r % gm;
+  n_tile = r / gm;
+}
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -91,68 +109,96 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-template <int MT>
+
+template <int MT, int NT, int WM>
+struct StreamCfg {
+  static constexpr int kWN = 4 / WM;                       // waves along N
+  static constexpr int kRows = WM * MT * 32;               // rows per workgroup tile
+  static constexpr int kAStage = kRows * kKS * 2;          // bytes of the activation tile per stage
+  static constexpr int kStageBytes = kAStage + kBStage;
+  static constexpr int kNST = kLdsBytes / kStageBytes > 5 ? 5 : kLdsBytes / kStageBytes;   // LDS stages
+  static constexpr int kACopies = WM * MT;                 // wave-wide copies per wave per K step
+  static constexpr int kCopies = kACopies + 4;
+  static_assert(kWN * NT == 8, "a workgroup covers 8 column tiles of 32");
+  static_assert(kNST >= 3, "needs three stages");
+};
+
+template <int MT, int NT, int WM>
 __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
-  constexpr int kAStage = MT * 32 * kKS * 2;            // bytes of the activation tile per stage
-  constexpr int kStageBytes = kAStage + kBStage;
-  constexpr int kCopies = MT + 4;                       // wave-wide copies a wave issues per K step
+  using C = StreamCfg<MT, NT, WM>;
+  constexpr int kWN = C::kWN, kAStage = C::kAStage, kStageBytes = C::kStageBytes, kNST = C::kNST;
+  constexpr int kACopies = C::kACopies, kCopies = C::kCopies;
   // Outstanding copies allowed when step ks+1 must have landed (end of slice 2 of step ks): those of
-  // steps ks+2 .. ks+4 and the weight copies of step ks+5.
-  constexpr int kWait = (kNST - 2) * kCopies + 4;
-  constexpr int kNM = 2 * MT;                           // MFMAs per K slice
+  // the steps after it that are already issued.
+  constexpr int kWait = (kNST - 2) * kCopies;
+  constexpr int kNM = MT * NT;                          // MFMAs per K slice
+  constexpr int kDq = 3 * NT;                           // dequantization pieces per K slice
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [kNST][A tile | B tiles]
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / kWN, wn = wave - wm * kWN;
   const int l32 = lane & 31, kb = lane >> 5;
 
   const int p = (blockIdx.x & 7) * (a.grid >> 3) + (blockIdx.x >> 3);
-  int64_t pos = work_begin(a.total_work, a.grid, p);
-  const int64_t pos_end = work_begin(a.total_work, a.grid, p + 1);
-  int seg = 0;
+  const int64_t rem_begin = work_begin(a.rem_work, a.grid, p), rem_end = work_begin(a.rem_work, a.grid, p + 1);
+  int64_t pos = rem_begin;
+  int round = 0, seg = 0;
 
-  // operand read offsets inside a stage: lane (l32, kb) reads logical chunk 4*kb + kk of row 32*m + l32
+  // operand read offsets inside a stage: lane (l32, kb) reads logical chunk 4*kb + kk of its row
   int a_off[4];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) a_off[kk] = (l32 * kKS + swz(l32, 4 * kb + kk) * 8) * 2;
+  for (int kk = 0; kk < 4; ++kk) a_off[kk] = ((wm * MT * 32 + l32) * kKS + swz(l32, 4 * kb + kk) * 8) * 2;
   // this wave's weight tiles inside a stage
-  const int bq_off = kAStage + wave * 2 * 1024 + lane * 16;      // + j * 1024
-  const int bm_off = kAStage + 8 * 1024 + wave * 2 * 256 + l32 * 8;   // + j * 256
+  const int bq_off = kAStage + wn * NT * 1024 + lane * 16;           // + j * 1024
+  const int bm_off = kAStage + 8 * 1024 + wn * NT * 256 + l32 * 8;   // + j * 256
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
 
-  while (pos < pos_end) {
-    const int64_t tile = pos / a.ksteps;
-    const int ks0 = (int)(pos - tile * a.ksteps);
-    const int64_t left = pos_end - pos;
-    const int ks1 = (int)((int64_t)(a.ksteps - ks0) < left ? a.ksteps : ks0 + left);
-    const int n_tile = (int)(tile / a.m_blocks);
-    const int mblk = (int)(tile - (int64_t)n_tile * a.m_blocks);
-    const int m0 = mblk * (MT * 32);
-    const int nt0 = n_tile * 8 + wave * 2;   // first 32-column tile of this wave
+  while (round < a.rounds || pos < rem_end) {
+    // ---- next segment: a whole tile of a round, or a piece of this workgroup's stream-K range
+    int64_t tile;
+    int ks0, ks1;
+    const bool whole_round = round < a.rounds;
+    if (whole_round) {
+      tile = (int64_t)round * a.grid + p;
+      ks0 = 0;
+      ks1 = a.ksteps;
+    } else {
+      const int64_t t = pos / a.ksteps;
+      tile = (int64_t)a.rounds * a.grid + t;
+      ks0 = (int)(pos - t * a.ksteps);
+      const int64_t left = rem_end - pos;
+      ks1 = (int)((int64_t)(a.ksteps - ks0) < left ? a.ksteps : ks0 + left);
+    }
+    int mblk, n_tile;
+    tile_coords(tile, a.m_blocks, a.n_tiles, mblk, n_tile);
+    const int m0 = mblk * C::kRows;
+    const int nt0 = n_tile * 8 + wn * NT;   // first 32-column tile of this wave
 
-    f16_t acc[MT][2];
+    f16_t acc[MT][NT];
 #pragma unroll
     for (int m = 0; m < MT; ++m)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < NT; ++j)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[m][j][r] = 0.f;
 
-    // this wave's MT async activation copies per step: copy c covers rows 8c .. 8c+7 of the tile
-    const half_t* a_src[MT];
+    // this wave's async activation copies per step: copy c covers rows 8c .. 8c+7 of the tile
+    const half_t* a_src[kACopies];
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
+    for (int i = 0; i < kACopies; ++i) {
       const int c = wave + 4 * i;
       const int prow = 8 * c + (lane >> 3);
       int row = m0 + prow;
       row = row < a.M ? row : a.M - 1;
       a_src[i] = a.x + (int64_t)row * a.ldx + swz(prow, lane & 7) * 8;
     }
+    // ... and its share of the weight copies: column tiles 2*wave and 2*wave+1 of the workgroup's 8
     const uint8_t* w_src[2];
     const float* m_src[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      int nt = nt0 + j;
+      int nt = n_tile * 8 + wave * 2 + j;
       nt = nt < a.n32 ? nt : a.n32 - 1;   // ragged last column block: load valid data, never store it
       w_src[j] = a.w + (int64_t)nt * a.ksteps * 1024 + lane * 16;
       m_src[j] = reinterpret_cast<const float*>(a.meta) + (int64_t)nt * a.ksteps * 64 + lane;
@@ -160,42 +206,43 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
 
     // The kCopies wave-wide asynchronous global -> LDS transfers of one K step.  Past the end of the
     // segment the last step is fetched again: harmless, and it keeps the VMEM counts uniform.
-    auto copy_a = [&](int i, int ks, int stage) {
+    auto copy_one = [&](int c, int ks, int stage) {
       const int kc = ks < ks1 ? ks : ks1 - 1;
-      __builtin_amdgcn_global_load_lds((gptr_t)(a_src[i] + kc * kKS),
-                                       (lptr_t)(smem + stage * kStageBytes + (wave + 4 * i) * 8 * kKS * 2), 16, 0, 0);
+      unsigned char* st = smem + stage * kStageBytes;
+      if (c < kACopies) {
+        __builtin_amdgcn_global_load_lds((gptr_t)(a_src[c] + kc * kKS), (lptr_t)(st + (wave + 4 * c) * 8 * kKS * 2), 16,
+                                         0, 0);
+      } else {
+        const int b = c - kACopies, j = b >> 1;   // b = 2 * j + (0: codes, 1: {min, scale})
+        if ((b & 1) == 0)
+          __builtin_amdgcn_global_load_lds((gptr_t)(w_src[j] + (int64_t)kc * 1024),
+                                           (lptr_t)(st + kAStage + (wave * 2 + j) * 1024), 16, 0, 0);
+        else
+          __builtin_amdgcn_global_load_lds((gptr_t)(m_src[j] + (int64_t)kc * 64),
+                                           (lptr_t)(st + kAStage + 8 * 1024 + (wave * 2 + j) * 256), 4, 0, 0);
+      }
     };
-    auto copy_b = [&](int c, int ks, int stage) {   // c = 2 * j + (0: codes, 1: {min, scale})
-      const int kc = ks < ks1 ? ks : ks1 - 1;
-      const int j = c >> 1;
-      unsigned char* st = smem + stage * kStageBytes + kAStage;
-      if ((c & 1) == 0)
-        __builtin_amdgcn_global_load_lds((gptr_t)(w_src[j] + (int64_t)kc * 1024), (lptr_t)(st + (wave * 2 + j) * 1024),
-                                         16, 0, 0);
-      else
-        __builtin_amdgcn_global_load_lds((gptr_t)(m_src[j] + (int64_t)kc * 64),
-                                         (lptr_t)(st + 8 * 1024 + (wave * 2 + j) * 256), 4, 0, 0);
-    };
-    u4_t cq[2];
-    float2 cm[2];
+    u4_t cq[NT];
+    float2 cm[NT];
     auto read_b = [&](int stage) {
       const uint32_t st = lds0 + stage * kStageBytes;
-      cq[0] = lds_read128<0>(st + bq_off);
-      cq[1] = lds_read128<1024>(st + bq_off);
-      cm[0] = lds_read64<0>(st + bm_off);
-      cm[1] = lds_read64<256>(st + bm_off);
+      static_for<0, NT>([&](auto J) __attribute__((always_inline)) {
+        constexpr int j = decltype(J)::value;
+        cq[j] = lds_read128<j * 1024>(st + bq_off);
+        cm[j] = lds_read64<j * 256>(st + bm_off);
+      });
     };
-    // operand slice kk of all MT row tiles of a stage
+    // operand slice kk of this wave's MT row tiles of a stage
     auto read_a = [&](uint32_t st, int kk, h8_t* dst) {
       const uint32_t ad = st + a_off[kk];
-      static_for<0, MT>([&](auto m) {
+      static_for<0, MT>([&](auto m) __attribute__((always_inline)) {
         constexpr int off = decltype(m)::value * 32 * kKS * 2;
         dst[decltype(m)::value] = __builtin_bit_cast(h8_t, lds_read128<off>(ad));
       });
     };
     h8_t aop[2][MT];
-    uint32_t bop[2][2][4];
-    float s24[2], s20[2], mn[2];
+    uint32_t bop[2][NT][4];
+    float s24[NT], s20[NT], mn[NT];
     uint32_t msk[4];
     // Exact dequantization (fg_common.h: dequant8_exact) of word kk of tile j, cut into three pieces so
     // that it can be spread between MFMAs: 0 = masks, 1 = weights 0..3, 2 = weights 4..7.
@@ -225,10 +272,17 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
     // the freshly read {min, scale} pairs -> FMA constants
     auto set_meta = [&]() {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < NT; ++j) {
         s24[j] = cm[j].y * 16777216.0f;
         s20[j] = cm[j].y * 1048576.0f;
         mn[j] = cm[j].x;
+      }
+    };
+    auto landed_b = [&]() {
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        lds_landed(cq[j]);
+        lds_landed(cm[j]);
       }
     };
 
@@ -236,12 +290,9 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
     __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 #pragma unroll
-    for (int t = 0; t < kNST; ++t) {
+    for (int t = 0; t < kNST; ++t)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) copy_b(c, ks0 + t, t);
-#pragma unroll
-      for (int i = 0; i < MT; ++i) copy_a(i, ks0 + t, t);
-    }
+      for (int c = 0; c < kCopies; ++c) copy_one(c, ks0 + t, t);
     __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"((kNST - 1) * kCopies) : "memory");
     __builtin_amdgcn_s_barrier();
     read_a(lds0, 0, aop[0]);
@@ -249,14 +300,10 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
     lds_wait();
 #pragma unroll
     for (int m = 0; m < MT; ++m) lds_landed(aop[0][m]);
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      lds_landed(cq[j]);
-      lds_landed(cm[j]);
-    }
+    landed_b();
     set_meta();
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < NT; ++j)
 #pragma unroll
       for (int sub = 0; sub < 3; ++sub) dq(0, j, sub, 0);
 
@@ -264,12 +311,10 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
     // Every slice issues its MFMAs with the preparation of the NEXT slice spread between them (a wave
     // issues in order, and an MFMA occupies the matrix pipe for 32 cycles: a few independent
     // instructions after each one are free, a block of them is not):
-    //   slices 0..2: LDS reads of the next A slice, dequantization of the next code word, and (slices
-    //                0, 1) the weight copies of step ks+5 into this wave's private part of the stage
-    //                whose weights were consumed one step ago;
+    //   slices 0..2: LDS reads of the next A slice and dequantization of the next code word;
     //   end of 2   : this wave's copies of step ks+1 have landed (vmcnt), barrier: now every wave's
-    //                have, and nobody reads the A tile of this stage any more;
-    //   slice 3    : A copies of step ks+5 into this stage, LDS reads of step ks+1 (first A slice,
+    //                have, and nobody reads this stage any more (its weights were read one step ago);
+    //   slice 3    : copies of step ks+kNST into this stage, LDS reads of step ks+1 (first A slice,
     //                codes, meta), then dequantization of its first code word.
     int stage = 0;
     for (int ks = ks0; ks < ks1; ++ks) {
@@ -285,7 +330,8 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
           read_b(stage1);
         }
         __builtin_amdgcn_sched_barrier(0);
-        constexpr int n_items = kk < 2 ? 8 : 6;   // slices 0..2: six dequantization pieces (+ two weight copies)
+        // slice 3: the copies go between the MFMAs of the first kH, the dequantization between the rest
+        constexpr int kH = kNM / 2 > 0 ? kNM / 2 : 1;
         static_for<0, kNM>([&](auto I) __attribute__((always_inline)) {
           constexpr int i = decltype(I)::value;
           constexpr int j = i / MT, m = i - j * MT;
@@ -293,28 +339,23 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
           acc[m][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[cur][m], __builtin_bit_cast(h8_t, bw), acc[m][j], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
           if constexpr (kk < 3) {
-            static_for<i * n_items / kNM, (i + 1) * n_items / kNM>([&](auto IT) __attribute__((always_inline)) {
+            static_for<i * kDq / kNM, (i + 1) * kDq / kNM>([&](auto IT) __attribute__((always_inline)) {
               constexpr int it = decltype(IT)::value;
-              if constexpr (it < 6)
-                dq(kk + 1, it / 3, it % 3, nxt);
-              else
-                copy_b(kk * 2 + it - 6, ks + kNST, stage);
+              dq(kk + 1, it / 3, it % 3, nxt);
             });
-          } else if constexpr (i < MT) {
-            copy_a(i, ks + kNST, stage);
-            if constexpr (i == MT - 1) {
+          } else if constexpr (i < kH) {
+            static_for<i * kCopies / kH, (i + 1) * kCopies / kH>([&](auto CC) __attribute__((always_inline)) {
+              copy_one(decltype(CC)::value, ks + kNST, stage);
+            });
+            if constexpr (i == kH - 1) {
               lds_wait();
 #pragma unroll
               for (int mm = 0; mm < MT; ++mm) lds_landed(aop[nxt][mm]);
-#pragma unroll
-              for (int jj = 0; jj < 2; ++jj) {
-                lds_landed(cq[jj]);
-                lds_landed(cm[jj]);
-              }
+              landed_b();
               set_meta();
             }
           } else {
-            static_for<(i - MT) * 6 / MT, (i - MT + 1) * 6 / MT>([&](auto IT) __attribute__((always_inline)) {
+            static_for<(i - kH) * kDq / (kNM - kH), (i - kH + 1) * kDq / (kNM - kH)>([&](auto IT) __attribute__((always_inline)) {
               constexpr int it = decltype(IT)::value;
               dq(0, it / 3, it % 3, nxt);
             });
@@ -339,12 +380,12 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
     const bool full = (ks0 == 0) && (ks1 == a.ksteps);
     if (full) {
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < NT; ++j) {
         const int col = (nt0 + j) * 32 + l32;
         if (nt0 + j < a.n32) {
           const float bvv = a.bias ? (float)a.bias[col] : 0.f;
           // running offsets instead of 16 * MT independent ones (which would all be kept in registers)
-          int row = m0 + kb * 4;
+          int row = m0 + wm * MT * 32 + kb * 4;
           int64_t o_off = (int64_t)row * a.ldo + col, r_off = (int64_t)row * a.ldr + col;
 #pragma unroll
           for (int m = 0; m < MT; ++m) {
@@ -368,58 +409,65 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
         }
       }
     } else {
-      // partial sums in register order: float4 number ((m*2 + j)*4 + q) of thread tid holds rows
-      // 32m + 8q + 4kb + 0..3 of column (2*wave + j)*32 + l32 -> every store is 1 KiB contiguous per wave
-      float4* dst = reinterpret_cast<float4*>(a.partial + ((int64_t)p * 2 + (seg == 0 ? 0 : 1)) * (MT * 32 * kBN)) + tid;
+      // partial sums in register order: float4 number ((m*NT + j)*4 + q) of thread tid holds rows
+      // 32m + 8q + 4kb + 0..3 of one column -> every store is 1 KiB contiguous per wave
+      float4* dst = reinterpret_cast<float4*>(a.partial + ((int64_t)p * 2 + (seg == 0 ? 0 : 1)) * ((int64_t)C::kRows * kBN)) + tid;
 #pragma unroll
       for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NT; ++j)
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             *dst = make_float4(acc[m][j][4 * q], acc[m][j][4 * q + 1], acc[m][j][4 * q + 2], acc[m][j][4 * q + 3]);
             dst += 256;
           }
     }
-    pos += ks1 - ks0;
-    ++seg;
+    if (whole_round) {
+      ++round;
+    } else {
+      pos += ks1 - ks0;
+      ++seg;
+    }
   }
   __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no copy may still target LDS when the wave ends
 }
 
 // Second pass of the stream-K schedule: tiles whose K range was shared get their partial sums added
 // in ascending K order, then the epilogue.  Thread tid of a block takes the float4s that thread tid of
-// the GEMM kernel wrote (four rows of one column each).
-__global__ __launch_bounds__(256) void gemm_stream_finish_kernel(StreamArgs a, int mt) {
-  const int64_t tile = blockIdx.x;
-  const int64_t w0 = tile * a.ksteps, w1 = w0 + a.ksteps;
-  int p_lo = (int)((w0 * a.grid) / a.total_work);
-  while (p_lo + 1 < a.grid && work_begin(a.total_work, a.grid, p_lo + 1) <= w0) ++p_lo;
-  while (p_lo > 0 && work_begin(a.total_work, a.grid, p_lo) > w0) --p_lo;
-  if (work_begin(a.total_work, a.grid, p_lo + 1) >= w1) return;   // one workgroup owned the whole tile
+// the GEMM kernel wrote (four rows of one column each).  blockIdx.x counts the tiles after the whole
+// rounds.
+__global__ __launch_bounds__(256) void gemm_stream_finish_kernel(StreamArgs a, int mt, int nt, int wm_n) {
+  const int64_t t = blockIdx.x;
+  const int64_t w0 = t * a.ksteps, w1 = w0 + a.ksteps;
+  int p_lo = (int)((w0 * a.grid) / a.rem_work);
+  while (p_lo + 1 < a.grid && work_begin(a.rem_work, a.grid, p_lo + 1) <= w0) ++p_lo;
+  while (p_lo > 0 && work_begin(a.rem_work, a.grid, p_lo) > w0) --p_lo;
+  if (work_begin(a.rem_work, a.grid, p_lo + 1) >= w1) return;   // one workgroup owned the whole tile
   int p_hi = p_lo;
-  while (p_hi + 1 < a.grid && work_begin(a.total_work, a.grid, p_hi + 1) < w1) ++p_hi;
+  while (p_hi + 1 < a.grid && work_begin(a.rem_work, a.grid, p_hi + 1) < w1) ++p_hi;
 
-  const int n_tile = (int)(tile / a.m_blocks);
-  const int mblk = (int)(tile - (int64_t)n_tile * a.m_blocks);
-  const int m0 = mblk * mt * 32;
-  const int64_t slot = (int64_t)mt * 32 * kBN;
+  int mblk, n_tile;
+  tile_coords((int64_t)a.rounds * a.grid + t, a.m_blocks, a.n_tiles, mblk, n_tile);
+  const int rows_t = wm_n * mt * 32, wn_n = 4 / wm_n;
+  const int m0 = mblk * rows_t;
+  const int64_t slot = (int64_t)rows_t * kBN;
   const int tid = threadIdx.x, wave = tid >> 6, l32 = tid & 31, kb = (tid >> 5) & 1;
-  for (int e = blockIdx.y; e < mt * 8; e += gridDim.y) {   // e = (m*2 + j)*4 + q
-    const int m = e >> 3, j = (e >> 2) & 1, q = e & 3;
-    const int row0 = m0 + m * 32 + q * 8 + kb * 4;
-    const int col = n_tile * kBN + (wave * 2 + j) * 32 + l32;
+  const int wm = wave / wn_n, wn = wave - wm * wn_n;
+  for (int e = blockIdx.y; e < mt * nt * 4; e += gridDim.y) {   // e = (m*nt + j)*4 + q
+    const int q = e & 3, mj = e >> 2, m = mj / nt, j = mj - m * nt;
+    const int row0 = m0 + (wm * mt + m) * 32 + q * 8 + kb * 4;
+    const int col = n_tile * kBN + (wn * nt + j) * 32 + l32;
     if (row0 >= a.M || col >= a.N) continue;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int p = p_lo; p <= p_hi; ++p) {
-      const int64_t pb = work_begin(a.total_work, a.grid, p);
-      if (work_begin(a.total_work, a.grid, p + 1) == pb) continue;
+      const int64_t pb = work_begin(a.rem_work, a.grid, p);
+      if (work_begin(a.rem_work, a.grid, p + 1) == pb) continue;
       const int s = pb >= w0 ? 0 : 1;
-      const float4 t = reinterpret_cast<const float4*>(a.partial + ((int64_t)p * 2 + s) * slot)[e * 256 + tid];
-      v.x += t.x;
-      v.y += t.y;
-      v.z += t.z;
-      v.w += t.w;
+      const float4 x = reinterpret_cast<const float4*>(a.partial + ((int64_t)p * 2 + s) * slot)[e * 256 + tid];
+      v.x += x.x;
+      v.y += x.y;
+      v.z += x.z;
+      v.w += x.w;
     }
     const float o[4] = {v.x, v.y, v.z, v.w};
     const float bvv = a.bias ? (float)a.bias[col] : 0.f;
@@ -459,25 +507,31 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint8_t* __rest
   }
 }
 
-int pick_mt(int64_t m) {
-  if (m > kMaxMT * 32) {
-    const int64_t blocks = ceil_div(m, kMaxMT * 32);
-    m = ceil_div(m, blocks);
-  }
+// rows per workgroup tile and the kernel shape for m rows
+struct Shape {
+  int mt, nt, wm;
+  int rows() const { return wm * mt * 32; }
+};
+Shape pick_shape(int64_t m) {
+  // Up to two row blocks the side-by-side shape wins (few tiles: the 256-row shape would leave most of
+  // its stream-K pieces short); beyond that the weights would be re-read too often.
+  if (m > 2 * kMaxMT * 32) return {4, 4, 2};
+  if (m > kMaxMT * 32) m = ceil_div(m, 2);
   const int need = (int)ceil_div(m, 32);
-  return need < 1 ? 1 : (need > kMaxMT ? kMaxMT : need);
+  return {need < 1 ? 1 : need, 2, 1};
 }
 
-template <int MT>
+template <int MT, int NT, int WM>
 int launch_t(const StreamArgs& a, hipStream_t stream) {
-  const size_t smem = (size_t)kNST * (MT * 32 * kKS * sizeof(half_t) + kBStage);
+  using C = StreamCfg<MT, NT, WM>;
+  const size_t smem = (size_t)C::kNST * C::kStageBytes;
   static bool attr_done = false;
   if (!attr_done) {
-    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MT>),
+    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MT, NT, WM>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_done = true;
   }
-  hipLaunchKernelGGL((gemm_stream_kernel<MT>), dim3(a.grid), dim3(256), smem, stream, a);
+  hipLaunchKernelGGL((gemm_stream_kernel<MT, NT, WM>), dim3(a.grid), dim3(256), smem, stream, a);
   FG_LAUNCH_CHECK();
   return FG_OK;
 }
@@ -487,13 +541,12 @@ int launch_t(const StreamArgs& a, hipStream_t stream) {
 size_t gemm_stream_workspace(int64_t n, int64_t k, int64_t m) {
   (void)n;
   (void)k;
-  if (m <= 0) return 0;
-  return (size_t)256 * 2 * pick_mt(m) * 32 * kBN * sizeof(float);
+  return (size_t)256 * 2 * pick_shape(m).rows() * kBN * sizeof(float);
 }
 
 int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStream_t stream) {
   if (la.m == 0 || la.n == 0) return FG_OK;
-  const int mt = pick_mt(la.m);
+  const Shape sh = pick_shape(la.m);
   StreamArgs a;
   a.w = reinterpret_cast<const uint8_t*>(la.w_data);
   a.meta = reinterpret_cast<const float2*>(la.w_meta);
@@ -502,12 +555,15 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   a.M = (int)la.m;
   a.N = (int)la.n;
   a.K = (int)la.k;
-  a.m_blocks = (int)ceil_div(la.m, mt * 32);
+  a.m_blocks = (int)ceil_div(la.m, sh.rows());
   a.n_tiles = (int)ceil_div(la.n, kBN);
   a.ksteps = (int)(la.k / kKS);
   a.n32 = (int)(la.n / 32);
-  a.total_work = (int64_t)a.m_blocks * a.n_tiles * a.ksteps;
   a.grid = 256;
+  const int64_t tiles = (int64_t)a.m_blocks * a.n_tiles;
+  a.rounds = (int)(tiles / a.grid);
+  const int64_t rem_tiles = tiles - (int64_t)a.rounds * a.grid;
+  a.rem_work = rem_tiles * a.ksteps;
   a.bias = la.bias;
   a.residual = la.residual;
   a.ldr = la.ldr;
@@ -518,22 +574,35 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   a.partial = reinterpret_cast<float*>(ws);
   const size_t need = gemm_stream_workspace(la.n, la.k, la.m);
   if (!ws || ws_bytes < need) return FG_ERR_WORKSPACE;
+  if (sh.wm == 2) {   // prefill shape: GEMM and reduction of the last partial round are one profile record
+    ProfScope prof(FG_K_GEMM_LARGE_M, stream);
+    const int rc = launch_t<4, 4, 2>(a, stream);
+    if (rc) return rc;
+    if (rem_tiles > 0) {
+      hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, 8), dim3(256), 0, stream, a, sh.mt, sh.nt,
+                         sh.wm);
+      FG_LAUNCH_CHECK();
+    }
+    return FG_OK;
+  }
   {
     ProfScope prof(FG_K_GEMM_SMALL_M, stream);
     int rc = FG_ERR_UNSUPPORTED;
-    switch (mt) {
-      case 1: rc = launch_t<1>(a, stream); break;
-      case 2: rc = launch_t<2>(a, stream); break;
-      case 3: rc = launch_t<3>(a, stream); break;
-      case 4: rc = launch_t<4>(a, stream); break;
-      case 5: rc = launch_t<5>(a, stream); break;
+    {
+      switch (sh.mt) {
+        case 1: rc = launch_t<1, 2, 1>(a, stream); break;
+        case 2: rc = launch_t<2, 2, 1>(a, stream); break;
+        case 3: rc = launch_t<3, 2, 1>(a, stream); break;
+        case 4: rc = launch_t<4, 2, 1>(a, stream); break;
+        case 5: rc = launch_t<5, 2, 1>(a, stream); break;
+      }
     }
     if (rc) return rc;
   }
-  {
+  if (rem_tiles > 0) {
     ProfScope prof(FG_K_GEMM_SMALL_M_FINISH, stream);
-    hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3(a.m_blocks * a.n_tiles, mt >= 3 ? 8 : 4), dim3(256), 0, stream,
-                       a, mt);
+    hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, sh.mt * sh.nt >= 6 ? 8 : 4), dim3(256), 0,
+                       stream, a, sh.mt, sh.nt, sh.wm);
     FG_LAUNCH_CHECK();
   }
   return FG_OK;

@@ -99,13 +99,14 @@ static int check_layer(const fg_model_cfg* cfg, const fg_layer_weights* w) {
 static const int64_t kSmallMLimit = 512;   // rows up to which the weight-streaming kernel is used
 
 size_t linear_workspace_bytes(int dtype, int64_t n, int64_t k, int64_t m) {
+  if (dtype == FG_Q4G64_TILED) return gemm_stream_workspace(n, k, m);   // one kernel family at every m
   if (m > kSmallMLimit) return 0;
-  return dtype == FG_Q4G64_TILED ? gemm_stream_workspace(n, k, m) : gemm_small_m_workspace(dtype, n, k, m);
+  return gemm_small_m_workspace(dtype, n, k, m);
 }
 
 int linear_launch(const LinearArgs& a, void* ws, size_t ws_bytes, hipStream_t stream) {
-  if (a.m > kSmallMLimit) return gemm_large_m_launch(a, stream);
   if (a.dtype == FG_Q4G64_TILED) return gemm_stream_launch(a, ws, ws_bytes, stream);
+  if (a.m > kSmallMLimit) return gemm_large_m_launch(a, stream);
   return gemm_small_m_launch(a, ws, ws_bytes, stream);
 }
 

@@ -150,8 +150,12 @@ TILED_CASES = [
     (150, 768, 768, False, False, False),
     (200, 512, 256, True, True, True),       # two row blocks
     (300, 800, 448, True, False, True),
-    (600, 768, 768, True, False, True),      # large-M kernel reading tiled weights
+    (161, 320, 64, True, False, True),       # smallest prefill-shape launch: one ragged 256-row block, one K step
+    (600, 768, 768, True, False, True),      # prefill shape (2 x 2 waves), stream-K pieces only
     (1100, 544, 448, True, True, False),
+    (4100, 4352, 128, True, False, True),    # 17 x 17 tiles: one whole round + 33 stream-K tiles, ragged last block
+    (2304, 15360, 64, False, True, False),   # 540 tiles: two whole rounds + 28
+    (2049, 8224, 192, True, False, False),   # 9 x 33 tiles, ragged rows and a ragged column block
 ]
 
 
