@@ -54,11 +54,11 @@ __device__ __forceinline__ void async_copy16(const void* g, half_t* lds_base) {
   __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)lds_base, 16, 0, 0);
 }
 
-// WF: weight format, 0 = FP16, 1 = 4-bit canonical (row-major codes), 2 = 4-bit tiled
+// WF: weight format, 0 = FP16, 1 = 4-bit canonical (row-major codes); tiled 4-bit weights have their
+// own kernel family (fg_gemm_stream.hip)
 template <int WF>
 __global__ __launch_bounds__(256) void gemm_large_m_kernel(LargeArgs a) {
   constexpr bool Q4 = WF != 0;
-  constexpr bool TILED = WF == 2;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   half_t* As = reinterpret_cast<half_t*>(smem_raw);   // [2][BM][KS]
   half_t* Bs = As + 2 * STAGE;                        // [2][BN][KS]
@@ -121,28 +121,18 @@ __global__ __launch_bounds__(256) void gemm_large_m_kernel(LargeArgs a) {
   const uint8_t* bq_src[2];
   const float2* bm_src[2];
   int bq_row[2], bq_hb[2];
-  constexpr int kBqStep = TILED ? 1024 : KS / 2;   // bytes between K steps
-  constexpr int kBmStep = TILED ? 32 : 1;          // pairs between K steps
+  constexpr int kBqStep = KS / 2;   // bytes between K steps
+  constexpr int kBmStep = 1;        // pairs between K steps
   if (Q4) {
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       const int id = tid + 256 * c;
-      if (TILED) {
-        bq_row[c] = (id >> 6) * 32 + (id & 31);
-        bq_hb[c] = (id >> 5) & 1;
-        const int n32 = a.N >> 5;
-        int nt = (n0 >> 5) + (id >> 6);
-        nt = nt < n32 ? nt : n32 - 1;
-        bq_src[c] = a.w + (int64_t)nt * (a.K >> 6) * 1024 + (id & 63) * 16;
-        bm_src[c] = a.meta + (int64_t)nt * (a.K >> 6) * 32 + (id & 31);
-      } else {
-        bq_row[c] = id >> 1;
-        bq_hb[c] = id & 1;
-        int col = n0 + (id >> 1);
-        col = col < a.N ? col : a.N - 1;
-        bq_src[c] = a.w + (int64_t)col * (a.K >> 1) + (id & 1) * 16;
-        bm_src[c] = a.meta + (int64_t)col * (a.K >> 6);
-      }
+      bq_row[c] = id >> 1;
+      bq_hb[c] = id & 1;
+      int col = n0 + (id >> 1);
+      col = col < a.N ? col : a.N - 1;
+      bq_src[c] = a.w + (int64_t)col * (a.K >> 1) + (id & 1) * 16;
+      bm_src[c] = a.meta + (int64_t)col * (a.K >> 6);
     }
   }
 
@@ -319,10 +309,10 @@ int gemm_large_m_launch(const LinearArgs& la, hipStream_t stream) {
   const int64_t tiles = (int64_t)a.tm * a.tn;
   const unsigned grid = (unsigned)(ceil_div(tiles, 8) * 8);
   const size_t smem = (size_t)4 * STAGE * sizeof(half_t);   // 128 KiB
-  const int wf = la.dtype == FG_F16 ? 0 : (la.dtype == FG_Q4G64 ? 1 : 2);
-  static bool attr_done[3] = {false, false, false};
-  const void* fn = wf == 0 ? (const void*)&gemm_large_m_kernel<0>
-                           : (wf == 1 ? (const void*)&gemm_large_m_kernel<1> : (const void*)&gemm_large_m_kernel<2>);
+  if (la.dtype != FG_F16 && la.dtype != FG_Q4G64) return FG_ERR_UNSUPPORTED;
+  const int wf = la.dtype == FG_F16 ? 0 : 1;
+  static bool attr_done[2] = {false, false};
+  const void* fn = wf == 0 ? (const void*)&gemm_large_m_kernel<0> : (const void*)&gemm_large_m_kernel<1>;
   if (!attr_done[wf]) {
     FG_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_done[wf] = true;
@@ -330,10 +320,8 @@ int gemm_large_m_launch(const LinearArgs& la, hipStream_t stream) {
   ProfScope prof(FG_K_GEMM_LARGE_M, stream);
   if (wf == 0)
     hipLaunchKernelGGL(gemm_large_m_kernel<0>, dim3(grid), dim3(256), smem, stream, a);
-  else if (wf == 1)
-    hipLaunchKernelGGL(gemm_large_m_kernel<1>, dim3(grid), dim3(256), smem, stream, a);
   else
-    hipLaunchKernelGGL(gemm_large_m_kernel<2>, dim3(grid), dim3(256), smem, stream, a);
+    hipLaunchKernelGGL(gemm_large_m_kernel<1>, dim3(grid), dim3(256), smem, stream, a);
   FG_LAUNCH_CHECK();
   return FG_OK;
 }

@@ -13,7 +13,8 @@
 // Kernel: out[M, N] = act(x[M, K] . W^T + bias) + residual.  One kernel template, two shapes:
 //   decode   M <= 160 per row block: 4 waves side by side, each all rows x 64 columns
 //            (MT = 1..5 row tiles of 32, NT = 2 column tiles, WM = 1);
-//   prefill  row blocks of 256: 2 x 2 waves, each 128 rows x 128 columns (MT = 4, NT = 4, WM = 2).
+//   prefill  row blocks of 256: 8 waves as 2 x 4, each 128 rows x 64 columns (MT = 4, NT = 2, WM = 2,
+//            two waves per SIMD so that one wave's MFMAs overlap the other's dequantization).
 //   * Nothing but MFMA operands passes through registers.  The activation tile (XOR-swizzled, the A
 //     operand) and the weight tiles (1 KiB of codes + 256 B of {min,scale} each) are copied
 //     global -> LDS asynchronously, several K steps ahead.  A wave reads its codes back, dequantizes
@@ -110,24 +111,27 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 
 
-template <int MT, int NT, int WM>
+template <int MT, int NT, int WM, int NW>
 struct StreamCfg {
-  static constexpr int kWN = 4 / WM;                       // waves along N
+  static constexpr int kWN = NW / WM;                      // waves along N
   static constexpr int kRows = WM * MT * 32;               // rows per workgroup tile
   static constexpr int kAStage = kRows * kKS * 2;          // bytes of the activation tile per stage
   static constexpr int kStageBytes = kAStage + kBStage;
   static constexpr int kNST = kLdsBytes / kStageBytes > 5 ? 5 : kLdsBytes / kStageBytes;   // LDS stages
-  static constexpr int kACopies = WM * MT;                 // wave-wide copies per wave per K step
-  static constexpr int kCopies = kACopies + 4;
+  static constexpr int kACopies = kRows / 8 / NW;          // wave-wide copies per wave per K step: activations
+  static constexpr int kBCopies = 16 / NW;                 // ... weights (8 tiles x {codes, meta})
+  static constexpr int kCopies = kACopies + kBCopies;
   static_assert(kWN * NT == 8, "a workgroup covers 8 column tiles of 32");
+  static_assert(kACopies * 8 * NW == kRows, "activation rows must split evenly over the waves");
   static_assert(kNST >= 3, "needs three stages");
 };
 
-template <int MT, int NT, int WM>
-__global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
-  using C = StreamCfg<MT, NT, WM>;
+template <int MT, int NT, int WM, int NW>
+__global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
+  using C = StreamCfg<MT, NT, WM, NW>;
   constexpr int kWN = C::kWN, kAStage = C::kAStage, kStageBytes = C::kStageBytes, kNST = C::kNST;
-  constexpr int kACopies = C::kACopies, kCopies = C::kCopies;
+  constexpr int kACopies = C::kACopies, kBCopies = C::kBCopies, kCopies = C::kCopies;
+  constexpr int kBT = (kBCopies + 1) / 2;               // weight tiles this wave copies
   // Outstanding copies allowed when step ks+1 must have landed (end of slice 2 of step ks): those of
   // the steps after it that are already issued.
   constexpr int kWait = (kNST - 2) * kCopies;
@@ -187,18 +191,18 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
     const half_t* a_src[kACopies];
 #pragma unroll
     for (int i = 0; i < kACopies; ++i) {
-      const int c = wave + 4 * i;
+      const int c = wave + NW * i;
       const int prow = 8 * c + (lane >> 3);
       int row = m0 + prow;
       row = row < a.M ? row : a.M - 1;
       a_src[i] = a.x + (int64_t)row * a.ldx + swz(prow, lane & 7) * 8;
     }
-    // ... and its share of the weight copies: column tiles 2*wave and 2*wave+1 of the workgroup's 8
-    const uint8_t* w_src[2];
-    const float* m_src[2];
+    // ... and its share of the weight copies: kBT of the workgroup's 8 column tiles
+    const uint8_t* w_src[kBT];
+    const float* m_src[kBT];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      int nt = n_tile * 8 + wave * 2 + j;
+    for (int j = 0; j < kBT; ++j) {
+      int nt = n_tile * 8 + wave * kBT + j;
       nt = nt < a.n32 ? nt : a.n32 - 1;   // ragged last column block: load valid data, never store it
       w_src[j] = a.w + (int64_t)nt * a.ksteps * 1024 + lane * 16;
       m_src[j] = reinterpret_cast<const float*>(a.meta) + (int64_t)nt * a.ksteps * 64 + lane;
@@ -210,16 +214,16 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
       const int kc = ks < ks1 ? ks : ks1 - 1;
       unsigned char* st = smem + stage * kStageBytes;
       if (c < kACopies) {
-        __builtin_amdgcn_global_load_lds((gptr_t)(a_src[c] + kc * kKS), (lptr_t)(st + (wave + 4 * c) * 8 * kKS * 2), 16,
+        __builtin_amdgcn_global_load_lds((gptr_t)(a_src[c] + kc * kKS), (lptr_t)(st + (wave + NW * c) * 8 * kKS * 2), 16,
                                          0, 0);
       } else {
         const int b = c - kACopies, j = b >> 1;   // b = 2 * j + (0: codes, 1: {min, scale})
         if ((b & 1) == 0)
           __builtin_amdgcn_global_load_lds((gptr_t)(w_src[j] + (int64_t)kc * 1024),
-                                           (lptr_t)(st + kAStage + (wave * 2 + j) * 1024), 16, 0, 0);
+                                           (lptr_t)(st + kAStage + (wave * kBT + j) * 1024), 16, 0, 0);
         else
           __builtin_amdgcn_global_load_lds((gptr_t)(m_src[j] + (int64_t)kc * 64),
-                                           (lptr_t)(st + kAStage + 8 * 1024 + (wave * 2 + j) * 256), 4, 0, 0);
+                                           (lptr_t)(st + kAStage + 8 * 1024 + (wave * kBT + j) * 256), 4, 0, 0);
       }
     };
     u4_t cq[NT];
@@ -419,7 +423,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             *dst = make_float4(acc[m][j][4 * q], acc[m][j][4 * q + 1], acc[m][j][4 * q + 2], acc[m][j][4 * q + 3]);
-            dst += 256;
+            dst += NW * 64;
           }
     }
     if (whole_round) {
@@ -436,7 +440,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(StreamArgs a) {
 // in ascending K order, then the epilogue.  Thread tid of a block takes the float4s that thread tid of
 // the GEMM kernel wrote (four rows of one column each).  blockIdx.x counts the tiles after the whole
 // rounds.
-__global__ __launch_bounds__(256) void gemm_stream_finish_kernel(StreamArgs a, int mt, int nt, int wm_n) {
+__global__ __launch_bounds__(512) void gemm_stream_finish_kernel(StreamArgs a, int mt, int nt, int wm_n) {
   const int64_t t = blockIdx.x;
   const int64_t w0 = t * a.ksteps, w1 = w0 + a.ksteps;
   int p_lo = (int)((w0 * a.grid) / a.rem_work);
@@ -448,7 +452,8 @@ __global__ __launch_bounds__(256) void gemm_stream_finish_kernel(StreamArgs a, i
 
   int mblk, n_tile;
   tile_coords((int64_t)a.rounds * a.grid + t, a.m_blocks, a.n_tiles, mblk, n_tile);
-  const int rows_t = wm_n * mt * 32, wn_n = 4 / wm_n;
+  const int nthr = blockDim.x;   // = threads of the GEMM workgroup
+  const int rows_t = wm_n * mt * 32, wn_n = (nthr >> 6) / wm_n;
   const int m0 = mblk * rows_t;
   const int64_t slot = (int64_t)rows_t * kBN;
   const int tid = threadIdx.x, wave = tid >> 6, l32 = tid & 31, kb = (tid >> 5) & 1;
@@ -463,7 +468,7 @@ __global__ __launch_bounds__(256) void gemm_stream_finish_kernel(StreamArgs a, i
       const int64_t pb = work_begin(a.rem_work, a.grid, p);
       if (work_begin(a.rem_work, a.grid, p + 1) == pb) continue;
       const int s = pb >= w0 ? 0 : 1;
-      const float4 x = reinterpret_cast<const float4*>(a.partial + ((int64_t)p * 2 + s) * slot)[e * 256 + tid];
+      const float4 x = reinterpret_cast<const float4*>(a.partial + ((int64_t)p * 2 + s) * slot)[e * nthr + tid];
       v.x += x.x;
       v.y += x.y;
       v.z += x.z;
@@ -509,29 +514,29 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint8_t* __rest
 
 // rows per workgroup tile and the kernel shape for m rows
 struct Shape {
-  int mt, nt, wm;
+  int mt, nt, wm, nw;
   int rows() const { return wm * mt * 32; }
 };
 Shape pick_shape(int64_t m) {
   // Up to two row blocks the side-by-side shape wins (few tiles: the 256-row shape would leave most of
   // its stream-K pieces short); beyond that the weights would be re-read too often.
-  if (m > 2 * kMaxMT * 32) return {4, 4, 2};
+  if (m > 2 * kMaxMT * 32) return {4, 2, 2, 8};
   if (m > kMaxMT * 32) m = ceil_div(m, 2);
   const int need = (int)ceil_div(m, 32);
-  return {need < 1 ? 1 : need, 2, 1};
+  return {need < 1 ? 1 : need, 2, 1, 4};
 }
 
-template <int MT, int NT, int WM>
+template <int MT, int NT, int WM, int NW>
 int launch_t(const StreamArgs& a, hipStream_t stream) {
-  using C = StreamCfg<MT, NT, WM>;
+  using C = StreamCfg<MT, NT, WM, NW>;
   const size_t smem = (size_t)C::kNST * C::kStageBytes;
   static bool attr_done = false;
   if (!attr_done) {
-    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MT, NT, WM>),
+    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MT, NT, WM, NW>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_done = true;
   }
-  hipLaunchKernelGGL((gemm_stream_kernel<MT, NT, WM>), dim3(a.grid), dim3(256), smem, stream, a);
+  hipLaunchKernelGGL((gemm_stream_kernel<MT, NT, WM, NW>), dim3(a.grid), dim3(NW * 64), smem, stream, a);
   FG_LAUNCH_CHECK();
   return FG_OK;
 }
@@ -576,11 +581,11 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   if (!ws || ws_bytes < need) return FG_ERR_WORKSPACE;
   if (sh.wm == 2) {   // prefill shape: GEMM and reduction of the last partial round are one profile record
     ProfScope prof(FG_K_GEMM_LARGE_M, stream);
-    const int rc = launch_t<4, 4, 2>(a, stream);
+    const int rc = launch_t<4, 2, 2, 8>(a, stream);
     if (rc) return rc;
     if (rem_tiles > 0) {
-      hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, 8), dim3(256), 0, stream, a, sh.mt, sh.nt,
-                         sh.wm);
+      hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, 8), dim3(sh.nw * 64), 0, stream, a, sh.mt,
+                         sh.nt, sh.wm);
       FG_LAUNCH_CHECK();
     }
     return FG_OK;
@@ -590,19 +595,19 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
     int rc = FG_ERR_UNSUPPORTED;
     {
       switch (sh.mt) {
-        case 1: rc = launch_t<1, 2, 1>(a, stream); break;
-        case 2: rc = launch_t<2, 2, 1>(a, stream); break;
-        case 3: rc = launch_t<3, 2, 1>(a, stream); break;
-        case 4: rc = launch_t<4, 2, 1>(a, stream); break;
-        case 5: rc = launch_t<5, 2, 1>(a, stream); break;
+        case 1: rc = launch_t<1, 2, 1, 4>(a, stream); break;
+        case 2: rc = launch_t<2, 2, 1, 4>(a, stream); break;
+        case 3: rc = launch_t<3, 2, 1, 4>(a, stream); break;
+        case 4: rc = launch_t<4, 2, 1, 4>(a, stream); break;
+        case 5: rc = launch_t<5, 2, 1, 4>(a, stream); break;
       }
     }
     if (rc) return rc;
   }
   if (rem_tiles > 0) {
     ProfScope prof(FG_K_GEMM_SMALL_M_FINISH, stream);
-    hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, sh.mt * sh.nt >= 6 ? 8 : 4), dim3(256), 0,
-                       stream, a, sh.mt, sh.nt, sh.wm);
+    hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, sh.mt * sh.nt >= 6 ? 8 : 4),
+                       dim3(sh.nw * 64), 0, stream, a, sh.mt, sh.nt, sh.wm);
     FG_LAUNCH_CHECK();
   }
   return FG_OK;
