@@ -1,10 +1,14 @@
 // Decode-phase attention over the stored KV cache (Section 3, decode: softmax(tQ.K^T/sqrt(h)).V),
 // with the cache read in its storage format of Section 5 and dequantized in registers.
 //
-// One workgroup of four waves per (sequence, head).  The rows of that head's K and V are one
-// contiguous byte stream in the cache, read 16 bytes per lane (1 KiB per wave load).  Waves take
-// 4 KiB chunks of the stream round-robin, keep a running (max, sum, output) triple each, and the
-// four triples are merged through LDS at the end (log-sum-exp merge).
+// WPH = 1, 2 or 4 waves per (sequence, head), four waves per workgroup.  The rows of that head's K
+// and V are one contiguous byte stream in the cache, read 16 bytes per lane (1 KiB per wave load).
+// The waves of a head take 4 KiB chunks of the stream round-robin, keep a running (max, sum, output)
+// triple each, and the triples are merged through LDS at the end (log-sum-exp merge); with one wave
+// per head there is nothing to merge.  The host picks the smallest WPH that still fills the chip:
+// a stream of c chunks costs ceil(c / WPH) chunk times, so at 528 rows (8.25 chunks) four waves
+// per head would idle a quarter of the time.  The next chunk's loads are issued before the current
+// one is processed.
 //
 // 4-bit path, per chunk of 128 quantization groups (64 rows at head size 128, 128 rows at 64):
 //   scores  : q.k_hat = sum_g scale_g * (q_g . c_g) + min_g * sum(q_g).  The code dot products run on
@@ -14,9 +18,9 @@
 //             groups a lane pair covers.  Sixteen MFMAs leave, in lane L, the two group sums of
 //             groups 2L and 2L+1 of the chunk, which is also the lane that loaded their {min,scale}.
 //   softmax : one or two scores per lane, wavefront shuffles for the running max.
-//   output  : sum_j p_j v_hat_j = sum_j (p_j scale_j)(c_j - 8) + sum_j p_j (min_j + 8 scale_j); the
-//             first term is accumulated per lane over its 32 head dimensions with FP16->FP32 mixed
-//             FMAs, the second is one scalar per group.
+//   output  : sum_j p_j v_hat_j = sum_j (p_j scale_j) c_j + sum_j p_j min_j; the first term is
+//             accumulated per lane over its 32 head dimensions with FP16->FP32 mixed FMAs on the
+//             nibbles taken in place as FP16 subnormals, the second is one scalar per group.
 #include "fg_common.h"
 
 namespace fg {
@@ -34,40 +38,53 @@ struct AttnArgs {
   const float2* v_meta;
   half_t* out;       // [b, nh*dh]
   int nh, cap, rows, batch_offset;
+  int n_heads;       // b * nh
   float scale;       // 1/sqrt(dh)
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Merge the four per-wave triples and write the head's output.  o_w already includes the
-// per-group constant term.
-template <int DH>
-__device__ __forceinline__ void merge_and_store(float* sm_m, float* sm_l, float* sm_o, half_t* out) {
+// Merge the WPH per-wave triples of each head of the block and write the outputs.  o_w already
+// includes the per-group constant term.  out0 = output row of the block's first head.
+template <int DH, int WPH>
+__device__ __forceinline__ void merge_and_store(const float* sm_m, const float* sm_l, const float* sm_o, half_t* out0,
+                                                int heads_valid) {
   __syncthreads();
-  const int t = threadIdx.x;
-  if (t < DH) {
-    float M = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
+  constexpr int HPB = 4 / WPH;
+  for (int idx = threadIdx.x; idx < HPB * DH; idx += 256) {
+    const int hl = idx / DH, t = idx - hl * DH;
+    if (hl >= heads_valid) break;
+    const float* mm = sm_m + hl * WPH;
+    float M = mm[0];
+#pragma unroll
+    for (int w = 1; w < WPH; ++w) M = fmaxf(M, mm[w]);
     float num = 0.f, den = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float f = sm_m[w] == -INFINITY ? 0.f : fast_exp2((sm_m[w] - M) * kLog2e);
-      num += f * sm_o[w * DH + t];
-      den += f * sm_l[w];
+    for (int w = 0; w < WPH; ++w) {
+      const float f = mm[w] == -INFINITY ? 0.f : fast_exp2((mm[w] - M) * kLog2e);
+      num += f * sm_o[(hl * WPH + w) * DH + t];
+      den += f * sm_l[hl * WPH + w];
     }
-    out[t] = (half_t)(num / den);
+    out0[(int64_t)hl * DH + t] = (half_t)(num / den);
   }
 }
 
-template <int DH>
+template <int DH, int WPH>
 __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
   constexpr int GPR = DH / 64;       // quantization groups per row of this head
   constexpr int NS = 2 / GPR;        // scores per lane per chunk (lane owns groups 2L, 2L+1)
-  __shared__ __attribute__((aligned(16))) half_t sm_q[DH];
+  constexpr int HPB = 4 / WPH;       // heads per workgroup
+  __shared__ __attribute__((aligned(16))) half_t sm_q[HPB * DH];
   __shared__ float sm_m[4], sm_l[4];
-  __shared__ float sm_o[4 * DH];
+  __shared__ float sm_o[WPH > 1 ? 4 * DH : 1];
 
-  const int head = blockIdx.x, seq = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int hl = wave / WPH, part = wave - hl * WPH;
+  const int hid0 = blockIdx.x * HPB;
+  const int heads_valid = a.n_heads - hid0 < HPB ? a.n_heads - hid0 : HPB;
+  const int hid = hl < heads_valid ? hid0 + hl : hid0;   // surplus waves of the last block redo its first head
+  const int seq = hid / a.nh, head = hid - seq * a.nh;
   const int r = lane & 15, q4 = lane >> 4, h = q4 >> 1, half = q4 & 1;
 
   const int64_t hrow = ((int64_t)(a.batch_offset + seq) * a.nh + head) * a.cap;   // first cache row
@@ -78,17 +95,18 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
   const int G = a.rows * GPR;                  // groups in the stream
   const int n_chunks = (G + 127) >> 7;
 
-  if (tid < DH / 8)
-    *reinterpret_cast<u4_t*>(sm_q + tid * 8) =
-        *reinterpret_cast<const u4_t*>(a.q + (int64_t)seq * a.q_stride + head * DH + tid * 8);
+  half_t* my_q = sm_q + hl * DH;
+  if (part == 0 && lane < DH / 8)
+    *reinterpret_cast<u4_t*>(my_q + lane * 8) =
+        *reinterpret_cast<const u4_t*>(a.q + (int64_t)seq * a.q_stride + head * DH + lane * 8);
   __syncthreads();
 
   // per-group query sums: Qs = sum q_d, Os = sum off_d q_d with off = 1024 (even d) / 64 (odd d),
   // the biases the register unpacking leaves on the codes.
   float Qs[2], Os[2];
   {
-    const float qa_ = (float)sm_q[lane];
-    const float qb_ = DH == 128 ? (float)sm_q[(lane + 64) % DH] : qa_;
+    const float qa_ = (float)my_q[lane];
+    const float qb_ = DH == 128 ? (float)my_q[(lane + 64) % DH] : qa_;
     const float off = (lane & 1) ? 64.f : 1024.f;
     Qs[0] = wave_sum(qa_);
     Os[0] = wave_sum(qa_ * off);
@@ -105,7 +123,7 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int d0 = (DH == 128 ? 64 * h : 0) + 32 * half + 8 * u;
-      const u4_t raw = *reinterpret_cast<const u4_t*>(sm_q + d0);
+      const u4_t raw = *reinterpret_cast<const u4_t*>(my_q + d0);
       const u4_t pm = permute8_like_codes(raw);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -117,26 +135,36 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
   }
 
   float m_run = -INFINITY, l_run = 0.f;
-  float mterm[2] = {0.f, 0.f};   // sum_j p_j (min_j + 8 scale_j) for the groups this lane owns
+  float mterm[2] = {0.f, 0.f};   // sum_j p_j min_j for the groups this lane owns
   float o[32];
 #pragma unroll
   for (int e = 0; e < 32; ++e) o[e] = 0.f;
 
-  for (int chunk = wave; chunk < n_chunks; chunk += 4) {
-    const int gbase = chunk << 7;
-    // ---- loads (all addresses clamped into the stream; masked later)
+  // one chunk's worth of registers: 4 + 4 code loads of 16 bytes and the meta of the lane's two groups
+  struct Buf {
     u4_t kq[4], vq[4];
+    float2 km0, km1, vm0, vm1;
+  };
+  // all addresses clamped into the stream; rows past the end are masked when the chunk is processed
+  auto load = [&](Buf& b, int chunk) {
+    const int gbase = chunk << 7;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       int g = gbase + 32 * i + 2 * r + h;
       g = g < G ? g : G - 1;
-      kq[i] = *reinterpret_cast<const u4_t*>(kc + (int64_t)g * 32 + half * 16);
-      vq[i] = *reinterpret_cast<const u4_t*>(vc + (int64_t)g * 32 + half * 16);
+      b.kq[i] = *reinterpret_cast<const u4_t*>(kc + (int64_t)g * 32 + half * 16);
+      b.vq[i] = *reinterpret_cast<const u4_t*>(vc + (int64_t)g * 32 + half * 16);
     }
     const int g0 = gbase + 2 * lane, g1 = g0 + 1;
-    const float2 km0 = km[g0 < G ? g0 : G - 1], km1 = km[g1 < G ? g1 : G - 1];
-    const float2 vm0 = vm[g0 < G ? g0 : G - 1], vm1 = vm[g1 < G ? g1 : G - 1];
-
+    const int c0 = g0 < G ? g0 : G - 1, c1 = g1 < G ? g1 : G - 1;
+    b.km0 = km[c0];
+    b.km1 = km[c1];
+    b.vm0 = vm[c0];
+    b.vm1 = vm[c1];
+  };
+  auto process = [&](const Buf& b, int chunk) {
+    const int gbase = chunk << 7;
+    const int g0 = gbase + 2 * lane, g1 = g0 + 1;
     // ---- scores on the matrix cores
     f4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -144,13 +172,13 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         uint32_t pk[4];
-        unpack8_biased(kq[i][u], pk);
+        unpack8_biased(b.kq[i][u], pk);
         const u4_t bw = {pk[0], pk[1], pk[2], pk[3]};
         acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qop[i][u], __builtin_bit_cast(h8_t, bw), acc, 0, 0, 0);
       }
     }
-    const float s0 = km0.y * (acc[0] - Os[0]) + km0.x * Qs[0];
-    const float s1 = km1.y * (acc[1] - Os[1]) + km1.x * Qs[1];
+    const float s0 = b.km0.y * (acc[0] - Os[0]) + b.km0.x * Qs[0];
+    const float s1 = b.km1.y * (acc[1] - Os[1]) + b.km1.x * Qs[1];
     float sc[NS];
     if (DH == 128) {
       sc[0] = g0 < G ? (s0 + s1) * a.scale : -INFINITY;
@@ -158,7 +186,7 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
       sc[0] = g0 < G ? s0 * a.scale : -INFINITY;
       sc[NS - 1] = g1 < G ? s1 * a.scale : -INFINITY;
     }
-    // ---- online softmax (chunk 0 of every wave has at least one valid row)
+    // ---- online softmax (every processed chunk has at least one valid row)
     float cmax = sc[0];
     if (NS == 2) cmax = fmaxf(cmax, sc[NS - 1]);
     cmax = wave_max(cmax);
@@ -177,35 +205,50 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
     p[1] = NS == 2 ? fast_exp2((sc[NS - 1] - m_run) * kLog2e) : p[0];
     l_run += NS == 2 ? p[0] + p[1] : p[0];
     // weights of the V codes of the two groups this lane owns, and their constant terms
-    const float wv0 = p[0] * vm0.y, wv1 = p[1] * vm1.y;
-    mterm[0] += p[0] * (vm0.x + 8.f * vm0.y);
-    mterm[1] += p[1] * (vm1.x + 8.f * vm1.y);
+    const float wv0 = p[0] * b.vm0.y, wv1 = p[1] * b.vm1.y;
+    mterm[0] += p[0] * b.vm0.x;
+    mterm[1] += p[1] * b.vm1.x;
 
-    // ---- output accumulation: lane (r, q4) handles group 32 i + 2 r + h of each load, half `half`
+    // ---- output accumulation: lane (r, q4) handles group 32 i + 2 r + h of each load, half `half`.
+    // A nibble masked in place is the FP16 subnormal c * 2^-24 (low nibble of a half) or c * 2^-20;
+    // the mixed-precision FMA takes it as it is, the weight carries the inverse power of two.
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int src = 16 * i + r;
       const float w0 = __shfl(wv0, src, 64), w1 = __shfl(wv1, src, 64);
       const float w = h ? w1 : w0;
+      const float w24 = w * 16777216.0f, w20 = w * 1048576.0f;
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        uint32_t pk[4];
-        unpack8_biased(vq[i][u], pk);
-        const h2_t k1032 = {(half_t)1032.0f, (half_t)1032.0f};
-        const h2_t k72 = {(half_t)72.0f, (half_t)72.0f};
-        const h2_t c04 = __builtin_bit_cast(h2_t, pk[0]) - k1032;   // codes - 8, exact
-        const h2_t c15 = __builtin_bit_cast(h2_t, pk[1]) - k72;
-        const h2_t c26 = __builtin_bit_cast(h2_t, pk[2]) - k1032;
-        const h2_t c37 = __builtin_bit_cast(h2_t, pk[3]) - k72;
-        o[8 * u + 0] += w * (float)c04.x;
-        o[8 * u + 4] += w * (float)c04.y;
-        o[8 * u + 1] += w * (float)c15.x;
-        o[8 * u + 5] += w * (float)c15.y;
-        o[8 * u + 2] += w * (float)c26.x;
-        o[8 * u + 6] += w * (float)c26.y;
-        o[8 * u + 3] += w * (float)c37.x;
-        o[8 * u + 7] += w * (float)c37.y;
+        const uint32_t x = b.vq[i][u], y = x >> 8;
+        const h2_t c04 = __builtin_bit_cast(h2_t, x & 0x000F000Fu);
+        const h2_t c15 = __builtin_bit_cast(h2_t, x & 0x00F000F0u);
+        const h2_t c26 = __builtin_bit_cast(h2_t, y & 0x000F000Fu);
+        const h2_t c37 = __builtin_bit_cast(h2_t, y & 0x00F000F0u);
+        o[8 * u + 0] = __builtin_fmaf((float)c04.x, w24, o[8 * u + 0]);
+        o[8 * u + 4] = __builtin_fmaf((float)c04.y, w24, o[8 * u + 4]);
+        o[8 * u + 1] = __builtin_fmaf((float)c15.x, w20, o[8 * u + 1]);
+        o[8 * u + 5] = __builtin_fmaf((float)c15.y, w20, o[8 * u + 5]);
+        o[8 * u + 2] = __builtin_fmaf((float)c26.x, w24, o[8 * u + 2]);
+        o[8 * u + 6] = __builtin_fmaf((float)c26.y, w24, o[8 * u + 6]);
+        o[8 * u + 3] = __builtin_fmaf((float)c37.x, w20, o[8 * u + 3]);
+        o[8 * u + 7] = __builtin_fmaf((float)c37.y, w20, o[8 * u + 7]);
       }
+    }
+  };
+
+  // two register buffers, the loop unrolled by two so that neither is ever moved while loads fly
+  Buf b0, b1;
+  if (part < n_chunks) load(b0, part);
+  for (int chunk = part; chunk < n_chunks; chunk += 2 * WPH) {
+    const bool more1 = chunk + WPH < n_chunks;
+    if (more1) load(b1, chunk + WPH);
+    __builtin_amdgcn_sched_barrier(0);
+    process(b0, chunk);
+    if (more1) {
+      if (chunk + 2 * WPH < n_chunks) load(b0, chunk + 2 * WPH);
+      __builtin_amdgcn_sched_barrier(0);
+      process(b1, chunk + WPH);
     }
   }
 
@@ -222,40 +265,63 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
   }
   const float lw = wave_sum(l_run);
   const float mt0 = wave_sum(mterm[0]), mt1 = wave_sum(mterm[1]);
-  if (lane == 0) {
-    sm_m[wave] = m_run;
-    sm_l[wave] = lw;
-  }
-  if (r == 0 && (DH == 128 || h == 0)) {
-    // this lane's range: head dims [dbase, dbase + 32), all in one quantization group
-    const int dbase = DH == 128 ? 32 * q4 : 32 * half;
-    const float c = DH == 128 ? (h ? mt1 : mt0) : (mt0 + mt1);
+  // this lane's range: head dims [dbase, dbase + 32), all in one quantization group
+  const int dbase = DH == 128 ? 32 * q4 : 32 * half;
+  const float c = DH == 128 ? (h ? mt1 : mt0) : (mt0 + mt1);
+  const bool writer = r == 0 && (DH == 128 || h == 0);
+  half_t* out0 = a.out + (int64_t)hid0 * DH;
+  if (WPH == 1) {
+    if (writer && hl < heads_valid) {
+      const float inv = 1.0f / lw;
+      half_t* dst = out0 + (int64_t)hl * DH + dbase;
 #pragma unroll
-    for (int e = 0; e < 32; ++e) sm_o[wave * DH + dbase + e] = o[e] + c;
+      for (int v8 = 0; v8 < 4; ++v8) {
+        h8_t pk;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pk[e] = (half_t)((o[8 * v8 + e] + c) * inv);
+        *reinterpret_cast<h8_t*>(dst + 8 * v8) = pk;
+      }
+    }
+  } else {
+    if (lane == 0) {
+      sm_m[wave] = m_run;
+      sm_l[wave] = lw;
+    }
+    if (writer) {
+#pragma unroll
+      for (int e = 0; e < 32; ++e) sm_o[wave * DH + dbase + e] = o[e] + c;
+    }
+    merge_and_store<DH, WPH>(sm_m, sm_l, sm_o, out0, heads_valid);
   }
-  merge_and_store<DH>(sm_m, sm_l, sm_o, a.out + (int64_t)seq * a.nh * DH + head * DH);
 }
 
 // FP16 cache: the same streaming structure without the unpacking.  K rows are the B operand
 // directly (lane = row, 8 consecutive head dimensions per lane).
-template <int DH>
+template <int DH, int WPH>
 __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
   constexpr int NU = DH / 32;        // 32-wide head-dimension blocks
-  __shared__ __attribute__((aligned(16))) half_t sm_q[DH];
+  constexpr int HPB = 4 / WPH;       // heads per workgroup
+  __shared__ __attribute__((aligned(16))) half_t sm_q[HPB * DH];
   __shared__ float sm_m[4], sm_l[4];
-  __shared__ float sm_o[4 * DH];
+  __shared__ float sm_o[WPH > 1 ? 4 * DH : 1];
 
-  const int head = blockIdx.x, seq = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int hl = wave / WPH, part = wave - hl * WPH;
+  const int hid0 = blockIdx.x * HPB;
+  const int heads_valid = a.n_heads - hid0 < HPB ? a.n_heads - hid0 : HPB;
+  const int hid = hl < heads_valid ? hid0 + hl : hid0;
+  const int seq = hid / a.nh, head = hid - seq * a.nh;
   const int r = lane & 15, q4 = lane >> 4;
   const int64_t hrow = ((int64_t)(a.batch_offset + seq) * a.nh + head) * a.cap;
   const half_t* kp = reinterpret_cast<const half_t*>(a.k_codes) + hrow * DH;
   const half_t* vp = reinterpret_cast<const half_t*>(a.v_codes) + hrow * DH;
   const int n_chunks = (a.rows + 63) >> 6;
 
-  if (tid < DH / 8)
-    *reinterpret_cast<u4_t*>(sm_q + tid * 8) =
-        *reinterpret_cast<const u4_t*>(a.q + (int64_t)seq * a.q_stride + head * DH + tid * 8);
+  half_t* my_q = sm_q + hl * DH;
+  if (part == 0 && lane < DH / 8)
+    *reinterpret_cast<u4_t*>(my_q + lane * 8) =
+        *reinterpret_cast<const u4_t*>(a.q + (int64_t)seq * a.q_stride + head * DH + lane * 8);
   __syncthreads();
 
   h8_t qop[4][NU];
@@ -263,7 +329,7 @@ __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
     const int m = lane & 15;
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
-      const u4_t raw = *reinterpret_cast<const u4_t*>(sm_q + 32 * u + 8 * q4);
+      const u4_t raw = *reinterpret_cast<const u4_t*>(my_q + 32 * u + 8 * q4);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const u4_t z = {0u, 0u, 0u, 0u};
@@ -277,7 +343,7 @@ __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
 #pragma unroll
   for (int e = 0; e < 8 * NU; ++e) o[e] = 0.f;
 
-  for (int chunk = wave; chunk < n_chunks; chunk += 4) {
+  for (int chunk = part; chunk < n_chunks; chunk += WPH) {
     const int rbase = chunk << 6;
     f4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -326,17 +392,31 @@ __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
     o[e] = v;
   }
   const float lw = wave_sum(l_run);
-  if (lane == 0) {
-    sm_m[wave] = m_run;
-    sm_l[wave] = lw;
-  }
-  if (r == 0) {
+  half_t* out0 = a.out + (int64_t)hid0 * DH;
+  if (WPH == 1) {
+    if (r == 0 && hl < heads_valid) {
+      const float inv = 1.0f / lw;
 #pragma unroll
-    for (int u = 0; u < NU; ++u)
+      for (int u = 0; u < NU; ++u) {
+        h8_t pk;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) sm_o[wave * DH + 32 * u + 8 * q4 + e] = o[8 * u + e];
+        for (int e = 0; e < 8; ++e) pk[e] = (half_t)(o[8 * u + e] * inv);
+        *reinterpret_cast<h8_t*>(out0 + (int64_t)hl * DH + 32 * u + 8 * q4) = pk;
+      }
+    }
+  } else {
+    if (lane == 0) {
+      sm_m[wave] = m_run;
+      sm_l[wave] = lw;
+    }
+    if (r == 0) {
+#pragma unroll
+      for (int u = 0; u < NU; ++u)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sm_o[wave * DH + 32 * u + 8 * q4 + e] = o[8 * u + e];
+    }
+    merge_and_store<DH, WPH>(sm_m, sm_l, sm_o, out0, heads_valid);
   }
-  merge_and_store<DH>(sm_m, sm_l, sm_o, a.out + (int64_t)seq * a.nh * DH + head * DH);
 }
 
 }  // namespace
@@ -359,19 +439,35 @@ int decode_attention_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_
   a.rows = rows;
   a.batch_offset = batch_offset;
   a.scale = 1.0f / sqrtf((float)dh);
-  const dim3 grid(cfg.nh, b);
+  a.n_heads = b * cfg.nh;
+  // Waves per head: one wave per head wastes the least (a stream of c chunks costs ceil(c / WPH) chunk
+  // times), but the chip wants at least ~8 waves on each of its 256 CUs.
+  const int64_t heads = (int64_t)b * cfg.nh;
+  const int wph = heads >= 2048 ? 1 : (heads >= 1024 ? 2 : 4);
+  const dim3 grid((unsigned)ceil_div(heads * wph, 4));
+  const bool q4 = kv.dtype == FG_Q4G64;
   ProfScope prof(FG_K_ATTN_DECODE, stream);
-  if (kv.dtype == FG_Q4G64) {
+#define FG_ATTN_LAUNCH(KERNEL, DH_)                                                                   \
+  do {                                                                                                \
+    if (wph == 1)                                                                                     \
+      hipLaunchKernelGGL((KERNEL<DH_, 1>), grid, dim3(256), 0, stream, a);                            \
+    else if (wph == 2)                                                                                \
+      hipLaunchKernelGGL((KERNEL<DH_, 2>), grid, dim3(256), 0, stream, a);                            \
+    else                                                                                              \
+      hipLaunchKernelGGL((KERNEL<DH_, 4>), grid, dim3(256), 0, stream, a);                            \
+  } while (0)
+  if (q4) {
     if (dh == 128)
-      hipLaunchKernelGGL(attn_decode_q4_kernel<128>, grid, dim3(256), 0, stream, a);
+      FG_ATTN_LAUNCH(attn_decode_q4_kernel, 128);
     else
-      hipLaunchKernelGGL(attn_decode_q4_kernel<64>, grid, dim3(256), 0, stream, a);
+      FG_ATTN_LAUNCH(attn_decode_q4_kernel, 64);
   } else {
     if (dh == 128)
-      hipLaunchKernelGGL(attn_decode_f16_kernel<128>, grid, dim3(256), 0, stream, a);
+      FG_ATTN_LAUNCH(attn_decode_f16_kernel, 128);
     else
-      hipLaunchKernelGGL(attn_decode_f16_kernel<64>, grid, dim3(256), 0, stream, a);
+      FG_ATTN_LAUNCH(attn_decode_f16_kernel, 64);
   }
+#undef FG_ATTN_LAUNCH
   FG_LAUNCH_CHECK();
   return FG_OK;
 }

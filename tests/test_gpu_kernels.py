@@ -239,6 +239,18 @@ def test_decode_attention(rows, nh, dh, quant):
 
 
 @pytest.mark.parametrize("quant", [True, False])
+@pytest.mark.parametrize("b,nh,dh,rows", [
+    (33, 33, 64, 200),     # 1089 heads: two waves per head, the last workgroup has one head only
+    (41, 51, 128, 150),    # 2091 heads: one wave per head, one surplus wave in the last workgroup
+    (40, 52, 64, 70),      # 2080 heads, a single chunk each (one wave per head, no second buffer)
+])
+def test_decode_attention_many_heads(b, nh, dh, rows, quant):
+    """The kernel uses fewer waves per head when there are many heads: cover those launch shapes."""
+    got, ref = _decode_attn_case(nh, dh, quant, rows, b=b, batch=b + 1, boff=1, seed=b + rows)
+    assert_close(got, ref, "decode attention b=%d nh=%d dh=%d rows=%d q=%s" % (b, nh, dh, rows, quant))
+
+
+@pytest.mark.parametrize("quant", [True, False])
 def test_decode_attention_peaked_softmax(quant):
     """Large key norm: a near one-hot softmax, where a wrong max/rescale shows immediately."""
     got, ref = _decode_attn_case(2, 128, quant, 300, seed=77, kstd=4.0)
