@@ -31,6 +31,9 @@ WORKLOADS = {
     "opt30b_q4": ("OPT_30B", True, True, 8, 32, 512, 32),
     "opt6.7b_f16": ("OPT_6_7B", False, False, 4, 32, 512, 32),
     "opt125m_layer_q4": ("OPT_125M_LAYER", True, True, 1, 4, 32, 9),
+    # KV-bound decode stress: ONE OPT-175B-shaped layer, batch 512, 2048 cached rows, 64 decode steps
+    # (handled by run_kv_stress: the cache is filled synthetically, there is no prefill)
+    "kv_stress_175b_layer": ("OPT_175B", True, True, 1, 512, 2048, 64),
 }
 
 
@@ -38,7 +41,7 @@ def bpe(q):
     return 0.625 if q else 2.0
 
 
-def build_model(sh, wq, seed, torch, B):
+def build_model(sh, wq, seed, torch, B, embeddings=True):
     """Random-init weights ~N(0, 0.02) generated and quantized on the device, one layer at a time."""
     g = torch.Generator(device="cuda")
     layers = []
@@ -56,6 +59,8 @@ def build_model(sh, wq, seed, torch, B):
     for j in range(sh.l):
         layers.append(B.LayerWeights(mat(3 * sh.h1, sh.h1, j, 0), mat(sh.h1, sh.h1, j, 1), mat(sh.h2, sh.h1, j, 2),
                                      mat(sh.h1, sh.h2, j, 3), ones, zeros, ones, zeros))
+    if not embeddings:
+        return layers, None, None, ones, zeros
     g.manual_seed(seed * 1000003 + 999983)
     emb = torch.empty((sh.vocab, sh.h1), dtype=torch.float16, device="cuda").normal_(0.0, 0.02, generator=g)
     pos = torch.empty((sh.max_pos, sh.h1), dtype=torch.float16, device="cuda").normal_(0.0, 0.02, generator=g)
@@ -116,6 +121,78 @@ def cpu_baseline(sh, wq, kvq, s, n, budget_s=25.0):
                       "to the full matrix, then x%d layers" % (rows + 1, h1, h2, nh, sh.l)}
 
 
+def run_kv_stress(args, torch, B, synth):
+    """64 decode steps of one OPT-175B-shaped layer over a 4-bit cache that already holds 2048 rows of
+    N(0,1) keys/values for each of 512 sequences; every step appends one quantized K/V row per
+    sequence and attends over all rows so far.  One bench step = those 64 layer steps."""
+    shape_name, wq, kvq, ngb, b, ctx, n = WORKLOADS[args.workload]
+    sh0 = getattr(synth, shape_name)
+    sh = synth.Shape(sh0.h1, sh0.nh, sh0.h2, sh0.vocab, sh0.max_pos, 1, sh0.ln_eps)
+    cfg = B.Cfg(sh.h1, sh.nh, sh.h2, sh.vocab, max(sh.max_pos, ctx + n), sh.ln_eps)
+    layers, _, _, _, _ = build_model(sh, wq, args.seed, torch, B, embeddings=False)
+    w = layers[0]
+    kv = B.KVCache(cfg, b, ctx + n, kvq, zero=False)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(args.seed * 1000003 + 77)
+    chunk = 256   # rows per fill call: 512 x 256 x 12288 FP16 = 3.2 GB of K and of V at a time
+    for r0 in range(0, ctx, chunk):
+        r1 = min(ctx, r0 + chunk)
+        k = torch.empty((b * (r1 - r0), sh.h1), dtype=torch.float16, device="cuda").normal_(0.0, 1.0, generator=g)
+        v = torch.empty((b * (r1 - r0), sh.h1), dtype=torch.float16, device="cuda").normal_(0.0, 1.0, generator=g)
+        B.fg_kv_append(cfg, k, v, sh.h1, b, r1 - r0, kv, 0, r0)
+        del k, v
+    x = torch.empty((b, sh.h1), dtype=torch.float16, device="cuda").normal_(0.0, 1.0, generator=g)
+    out = torch.empty_like(x)
+    ws = torch.empty(B.lib().fg_layer_workspace_bytes(B.C.byref(cfg.c), B.C.byref(w.c), b), dtype=torch.uint8,
+                     device="cuda")
+    torch.cuda.synchronize()
+
+    def step():
+        for i in range(n):
+            B.fg_decode_layer(cfg, w, x, ctx + i, kv, 0, ws=ws, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.fg_profile_begin()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = B.fg_profile_end()
+    K = args.steps
+    kv_bytes = sum(2.0 * b * sh.h1 * (ctx + i + 1) * bpe(kvq) for i in range(n))
+    P = 4 * sh.h1 * sh.h1 + 2 * sh.h1 * sh.h2
+    rl = {}
+    for name, bound, work in (("attn_decode", "hbm", kv_bytes), ("gemm_large_m", "mfma", 2.0 * b * P * n),
+                              ("kv_append", "hbm", n * 2.0 * b * sh.h1 * (2 + bpe(kvq)))):
+        if name not in prof:
+            continue
+        ms = prof[name]["ms"] / K
+        peak = HBM_PEAK if bound == "hbm" else MFMA_F16_PEAK
+        ach = work / (ms * 1e-3)
+        rl[name] = {"bound": bound, "achieved": ach / (1e9 if bound == "hbm" else 1e12),
+                    "peak": peak / (1e9 if bound == "hbm" else 1e12), "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
+                    "frac": ach / peak, "traffic": None, "ms_per_step": ms,
+                    "launches_per_step": prof[name]["launches"] / K,
+                    "avg_launch_us": 1e3 * prof[name]["ms"] / prof[name]["launches"]}
+    dominant = max(rl, key=lambda k: rl[k]["ms_per_step"])
+    line = {
+        "metric": "generated tokens/s + % peak HBM BW, 4-bit OPT-175B-shape decode, 1 GPU",
+        "value": b * n * K / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": 1e3 * elapsed / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": args.workload, "shape": {"l": 1, "h1": sh.h1, "nh": sh.nh, "h2": sh.h2},
+                   "weights": "q4g64", "kv_cache": "q4g64", "block": "1x%d" % b, "context": ctx, "decode_steps": n},
+        "decode": {"ms_per_layer_step": 1e3 * elapsed / K / n,
+                   "hbm_frac_avg": (kv_bytes + n * P * bpe(wq)) / (elapsed / K) / HBM_PEAK},
+        "roofline": dict(rl[dominant], kernel=dominant), "roofline_kernels": rl,
+        "kernel_ms": {k: v["ms"] / K for k, v in prof.items() if v["launches"]},
+    }
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -140,6 +217,8 @@ def main():
     B.lib()   # fails loudly if the HIP library is not built
     torch.cuda.set_device(0)
 
+    if args.workload.startswith("kv_stress"):
+        return run_kv_stress(args, torch, B, synth)
     shape_name, wq, kvq, ngb, gbs, s, n = WORKLOADS[args.workload]
     sh = getattr(synth, shape_name)
     if args.layers:
@@ -254,6 +333,7 @@ def main():
         "prefill_s": prefill_s, "decode_s": decode_s, "decode": decode,
         "roofline": (dict(rl[dominant], kernel=dominant) if dominant else None),
         "roofline_kernels": rl,
+        "kernel_ms": {k: v["ms"] / K for k, v in prof.items() if v["launches"]},
         "paper_context": "FlexGen reports 1.12 token/s for OPT-175B (4-bit) on one 16 GB T4 with CPU offloading",
     }
     if not args.no_cpu_baseline:
