@@ -32,7 +32,8 @@ namespace {
 
 constexpr int kBN = 256;      // output columns per workgroup
 constexpr int kKS = 64;       // K elements per step = one quantization group
-constexpr int kBStage = 8 * (1024 + 256);   // bytes of weight codes + meta per stage (8 column tiles)
+constexpr int kBStageQ4 = 8 * (1024 + 256);   // bytes of weight codes + meta per stage (8 column tiles)
+constexpr int kBStageF16 = kBN * kKS * 2;     // FP16 weights: 256 rows of 128 bytes, laid out like the activations
 constexpr int kMaxMT = 5;     // decode shape: up to 5 row tiles of 32 (160 rows)
 constexpr int kGroupM = 8;    // row blocks per group in the tile walk
 constexpr int kLdsBytes = 160 * 1024;
@@ -111,27 +112,30 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 
 
-template <int MT, int NT, int WM, int NW>
+// F16W: the weights are plain row-major FP16 (no repacking needed: a [256 columns][64 k] block of W is
+// copied and read exactly like the activation tile) instead of tiled 4-bit codes.
+template <int MT, int NT, int WM, int NW, bool F16W>
 struct StreamCfg {
   static constexpr int kWN = NW / WM;                      // waves along N
   static constexpr int kRows = WM * MT * 32;               // rows per workgroup tile
   static constexpr int kAStage = kRows * kKS * 2;          // bytes of the activation tile per stage
+  static constexpr int kBStage = F16W ? kBStageF16 : kBStageQ4;
   static constexpr int kStageBytes = kAStage + kBStage;
   static constexpr int kNST = kLdsBytes / kStageBytes > 5 ? 5 : kLdsBytes / kStageBytes;   // LDS stages
   static constexpr int kACopies = kRows / 8 / NW;          // wave-wide copies per wave per K step: activations
-  static constexpr int kBCopies = 16 / NW;                 // ... weights (8 tiles x {codes, meta})
+  static constexpr int kBCopies = (F16W ? kBN / 8 : 16) / NW;   // ... weights (8 tiles x {codes, meta}, or 32 x 8 rows)
   static constexpr int kCopies = kACopies + kBCopies;
   static_assert(kWN * NT == 8, "a workgroup covers 8 column tiles of 32");
   static_assert(kACopies * 8 * NW == kRows, "activation rows must split evenly over the waves");
   static_assert(kNST >= 3, "needs three stages");
 };
 
-template <int MT, int NT, int WM, int NW>
+template <int MT, int NT, int WM, int NW, bool F16W>
 __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
-  using C = StreamCfg<MT, NT, WM, NW>;
+  using C = StreamCfg<MT, NT, WM, NW, F16W>;
   constexpr int kWN = C::kWN, kAStage = C::kAStage, kStageBytes = C::kStageBytes, kNST = C::kNST;
   constexpr int kACopies = C::kACopies, kBCopies = C::kBCopies, kCopies = C::kCopies;
-  constexpr int kBT = (kBCopies + 1) / 2;               // weight tiles this wave copies
+  constexpr int kBT = F16W ? kBCopies : (kBCopies + 1) / 2;   // weight tiles (FP16: 8-row pieces) this wave copies
   // Outstanding copies allowed when step ks+1 must have landed (end of slice 2 of step ks): those of
   // the steps after it that are already issued.
   constexpr int kWait = (kNST - 2) * kCopies;
@@ -156,6 +160,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
   // this wave's weight tiles inside a stage
   const int bq_off = kAStage + wn * NT * 1024 + lane * 16;           // + j * 1024
   const int bm_off = kAStage + 8 * 1024 + wn * NT * 256 + l32 * 8;   // + j * 256
+  // FP16 weights: operand offsets like a_off, for this wave's first column tile
+  int b_off[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) b_off[kk] = kAStage + ((wn * NT * 32 + l32) * kKS + swz(l32, 4 * kb + kk) * 8) * 2;
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
 
   while (round < a.rounds || pos < rem_end) {
@@ -199,13 +207,21 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
     }
     // ... and its share of the weight copies: kBT of the workgroup's 8 column tiles
     const uint8_t* w_src[kBT];
-    const float* m_src[kBT];
+    const float* m_src[F16W ? 1 : kBT];
 #pragma unroll
     for (int j = 0; j < kBT; ++j) {
-      int nt = n_tile * 8 + wave * kBT + j;
-      nt = nt < a.n32 ? nt : a.n32 - 1;   // ragged last column block: load valid data, never store it
-      w_src[j] = a.w + (int64_t)nt * a.ksteps * 1024 + lane * 16;
-      m_src[j] = reinterpret_cast<const float*>(a.meta) + (int64_t)nt * a.ksteps * 64 + lane;
+      if constexpr (F16W) {   // piece c = wave + NW*j covers weight rows (output columns) 8c .. 8c+7 of the block
+        const int c = wave + NW * j;
+        const int prow = 8 * c + (lane >> 3);
+        int col = n_tile * kBN + prow;
+        col = col < a.N ? col : a.N - 1;
+        w_src[j] = a.w + ((int64_t)col * a.K + swz(prow, lane & 7) * 8) * 2;
+      } else {
+        int nt = n_tile * 8 + wave * kBT + j;
+        nt = nt < a.n32 ? nt : a.n32 - 1;   // ragged last column block: load valid data, never store it
+        w_src[j] = a.w + (int64_t)nt * a.ksteps * 1024 + lane * 16;
+        m_src[j] = reinterpret_cast<const float*>(a.meta) + (int64_t)nt * a.ksteps * 64 + lane;
+      }
     }
 
     // The kCopies wave-wide asynchronous global -> LDS transfers of one K step.  Past the end of the
@@ -216,6 +232,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
       if (c < kACopies) {
         __builtin_amdgcn_global_load_lds((gptr_t)(a_src[c] + kc * kKS), (lptr_t)(st + (wave + NW * c) * 8 * kKS * 2), 16,
                                          0, 0);
+      } else if constexpr (F16W) {
+        const int j = c - kACopies;
+        __builtin_amdgcn_global_load_lds((gptr_t)(w_src[j] + (int64_t)kc * (kKS * 2)),
+                                         (lptr_t)(st + kAStage + (wave + NW * j) * 8 * kKS * 2), 16, 0, 0);
       } else {
         const int b = c - kACopies, j = b >> 1;   // b = 2 * j + (0: codes, 1: {min, scale})
         if ((b & 1) == 0)
@@ -244,8 +264,16 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
         dst[decltype(m)::value] = __builtin_bit_cast(h8_t, lds_read128<off>(ad));
       });
     };
+    // FP16 weights: operand slice kk of this wave's NT column tiles, straight from the stage
+    auto read_w16 = [&](uint32_t st, int kk, u4_t* dst) {
+      const uint32_t ad = st + b_off[kk];
+      static_for<0, NT>([&](auto J) __attribute__((always_inline)) {
+        constexpr int j = decltype(J)::value;
+        dst[j] = lds_read128<j * 32 * kKS * 2>(ad);
+      });
+    };
     h8_t aop[2][MT];
-    uint32_t bop[2][NT][4];
+    u4_t bop[2][NT];
     float s24[NT], s20[NT], mn[NT];
     uint32_t msk[4];
     // Exact dequantization (fg_common.h: dequant8_exact) of word kk of tile j, cut into three pieces so
@@ -300,16 +328,21 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
     __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"((kNST - 1) * kCopies) : "memory");
     __builtin_amdgcn_s_barrier();
     read_a(lds0, 0, aop[0]);
-    read_b(0);
+    if constexpr (F16W) read_w16(lds0, 0, bop[0]); else read_b(0);
     lds_wait();
 #pragma unroll
     for (int m = 0; m < MT; ++m) lds_landed(aop[0][m]);
-    landed_b();
-    set_meta();
+    if constexpr (F16W) {
 #pragma unroll
-    for (int j = 0; j < NT; ++j)
+      for (int j = 0; j < NT; ++j) lds_landed(bop[0][j]);
+    } else {
+      landed_b();
+      set_meta();
 #pragma unroll
-      for (int sub = 0; sub < 3; ++sub) dq(0, j, sub, 0);
+      for (int j = 0; j < NT; ++j)
+#pragma unroll
+        for (int sub = 0; sub < 3; ++sub) dq(0, j, sub, 0);
+    }
 
     // Steady state.  At the top of a step the operands of its first K slice are already in registers.
     // Every slice issues its MFMAs with the preparation of the NEXT slice spread between them (a wave
@@ -329,9 +362,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
         constexpr int cur = kk & 1, nxt = cur ^ 1;
         if constexpr (kk < 3) {
           read_a(At, kk + 1, aop[nxt]);
+          if constexpr (F16W) read_w16(At, kk + 1, bop[nxt]);
         } else {
           read_a(lds0 + stage1 * kStageBytes, 0, aop[nxt]);
-          read_b(stage1);
+          if constexpr (F16W) read_w16(lds0 + stage1 * kStageBytes, 0, bop[nxt]); else read_b(stage1);
         }
         __builtin_amdgcn_sched_barrier(0);
         // slice 3: the copies go between the MFMAs of the first kH, the dequantization between the rest
@@ -339,14 +373,14 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
         static_for<0, kNM>([&](auto I) __attribute__((always_inline)) {
           constexpr int i = decltype(I)::value;
           constexpr int j = i / MT, m = i - j * MT;
-          const u4_t bw = {bop[cur][j][0], bop[cur][j][1], bop[cur][j][2], bop[cur][j][3]};
-          acc[m][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[cur][m], __builtin_bit_cast(h8_t, bw), acc[m][j], 0, 0, 0);
+          acc[m][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop[cur][m], __builtin_bit_cast(h8_t, bop[cur][j]), acc[m][j], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
           if constexpr (kk < 3) {
-            static_for<i * kDq / kNM, (i + 1) * kDq / kNM>([&](auto IT) __attribute__((always_inline)) {
-              constexpr int it = decltype(IT)::value;
-              dq(kk + 1, it / 3, it % 3, nxt);
-            });
+            if constexpr (!F16W)
+              static_for<i * kDq / kNM, (i + 1) * kDq / kNM>([&](auto IT) __attribute__((always_inline)) {
+                constexpr int it = decltype(IT)::value;
+                dq(kk + 1, it / 3, it % 3, nxt);
+              });
           } else if constexpr (i < kH) {
             static_for<i * kCopies / kH, (i + 1) * kCopies / kH>([&](auto CC) __attribute__((always_inline)) {
               copy_one(decltype(CC)::value, ks + kNST, stage);
@@ -355,10 +389,15 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
               lds_wait();
 #pragma unroll
               for (int mm = 0; mm < MT; ++mm) lds_landed(aop[nxt][mm]);
-              landed_b();
-              set_meta();
+              if constexpr (F16W) {
+#pragma unroll
+                for (int jj = 0; jj < NT; ++jj) lds_landed(bop[nxt][jj]);
+              } else {
+                landed_b();
+                set_meta();
+              }
             }
-          } else {
+          } else if constexpr (!F16W) {
             static_for<(i - kH) * kDq / (kNM - kH), (i - kH + 1) * kDq / (kNM - kH)>([&](auto IT) __attribute__((always_inline)) {
               constexpr int it = decltype(IT)::value;
               dq(0, it / 3, it % 3, nxt);
@@ -370,6 +409,10 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
           lds_wait();
 #pragma unroll
           for (int m = 0; m < MT; ++m) lds_landed(aop[nxt][m]);
+          if constexpr (F16W) {
+#pragma unroll
+            for (int j = 0; j < NT; ++j) lds_landed(bop[nxt][j]);
+          }
           if constexpr (kk == 2) {
             __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"(kWait) : "memory");
             __builtin_amdgcn_s_barrier();   // bare barrier: no fence, the copies in flight stay in flight
@@ -526,17 +569,17 @@ Shape pick_shape(int64_t m) {
   return {need < 1 ? 1 : need, 2, 1, 4};
 }
 
-template <int MT, int NT, int WM, int NW>
+template <int MT, int NT, int WM, int NW, bool F16W>
 int launch_t(const StreamArgs& a, hipStream_t stream) {
-  using C = StreamCfg<MT, NT, WM, NW>;
+  using C = StreamCfg<MT, NT, WM, NW, F16W>;
   const size_t smem = (size_t)C::kNST * C::kStageBytes;
   static bool attr_done = false;
   if (!attr_done) {
-    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MT, NT, WM, NW>),
+    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MT, NT, WM, NW, F16W>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_done = true;
   }
-  hipLaunchKernelGGL((gemm_stream_kernel<MT, NT, WM, NW>), dim3(a.grid), dim3(NW * 64), smem, stream, a);
+  hipLaunchKernelGGL((gemm_stream_kernel<MT, NT, WM, NW, F16W>), dim3(a.grid), dim3(NW * 64), smem, stream, a);
   FG_LAUNCH_CHECK();
   return FG_OK;
 }
@@ -581,7 +624,8 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   if (!ws || ws_bytes < need) return FG_ERR_WORKSPACE;
   if (sh.wm == 2) {   // prefill shape: GEMM and reduction of the last partial round are one profile record
     ProfScope prof(FG_K_GEMM_LARGE_M, stream);
-    const int rc = launch_t<4, 2, 2, 8>(a, stream);
+    if (la.dtype != FG_Q4G64_TILED) return FG_ERR_UNSUPPORTED;
+    const int rc = launch_t<4, 2, 2, 8, false>(a, stream);
     if (rc) return rc;
     if (rem_tiles > 0) {
       hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, 8), dim3(sh.nw * 64), 0, stream, a, sh.mt,
@@ -593,13 +637,14 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   {
     ProfScope prof(FG_K_GEMM_SMALL_M, stream);
     int rc = FG_ERR_UNSUPPORTED;
+    const bool f16w = la.dtype == FG_F16;
     {
       switch (sh.mt) {
-        case 1: rc = launch_t<1, 2, 1, 4>(a, stream); break;
-        case 2: rc = launch_t<2, 2, 1, 4>(a, stream); break;
-        case 3: rc = launch_t<3, 2, 1, 4>(a, stream); break;
-        case 4: rc = launch_t<4, 2, 1, 4>(a, stream); break;
-        case 5: rc = launch_t<5, 2, 1, 4>(a, stream); break;
+        case 1: rc = f16w ? launch_t<1, 2, 1, 4, true>(a, stream) : launch_t<1, 2, 1, 4, false>(a, stream); break;
+        case 2: rc = f16w ? launch_t<2, 2, 1, 4, true>(a, stream) : launch_t<2, 2, 1, 4, false>(a, stream); break;
+        case 3: rc = f16w ? launch_t<3, 2, 1, 4, true>(a, stream) : launch_t<3, 2, 1, 4, false>(a, stream); break;
+        case 4: rc = f16w ? launch_t<4, 2, 1, 4, true>(a, stream) : launch_t<4, 2, 1, 4, false>(a, stream); break;
+        case 5: rc = f16w ? launch_t<5, 2, 1, 4, true>(a, stream) : launch_t<5, 2, 1, 4, false>(a, stream); break;
       }
     }
     if (rc) return rc;

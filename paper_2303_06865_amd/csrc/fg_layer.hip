@@ -98,14 +98,21 @@ static int check_layer(const fg_model_cfg* cfg, const fg_layer_weights* w) {
 // ---------------------------------------------------------------- linear dispatch
 static const int64_t kSmallMLimit = 512;   // rows up to which the weight-streaming kernel is used
 
+// Tiled 4-bit weights always take the stream kernels; row-major FP16 weights take them for up to two
+// row blocks (the decode phase and the LM head), where the kernel is a pure weight streamer.
+static bool use_stream(int dtype, int64_t n, int64_t m) {
+  if (dtype == FG_Q4G64_TILED) return true;
+  return dtype == FG_F16 && m <= 320 && n % 32 == 0;
+}
+
 size_t linear_workspace_bytes(int dtype, int64_t n, int64_t k, int64_t m) {
-  if (dtype == FG_Q4G64_TILED) return gemm_stream_workspace(n, k, m);   // one kernel family at every m
+  if (use_stream(dtype, n, m)) return gemm_stream_workspace(n, k, m);
   if (m > kSmallMLimit) return 0;
   return gemm_small_m_workspace(dtype, n, k, m);
 }
 
 int linear_launch(const LinearArgs& a, void* ws, size_t ws_bytes, hipStream_t stream) {
-  if (a.dtype == FG_Q4G64_TILED) return gemm_stream_launch(a, ws, ws_bytes, stream);
+  if (use_stream(a.dtype, a.n, a.m)) return gemm_stream_launch(a, ws, ws_bytes, stream);
   if (a.m > kSmallMLimit) return gemm_large_m_launch(a, stream);
   return gemm_small_m_launch(a, ws, ws_bytes, stream);
 }
