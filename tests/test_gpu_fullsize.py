@@ -1,0 +1,112 @@
+"""Parity at the benchmark's full sizes, in the launch configurations bench.py times (same kernel
+templates, grids and stream-K splits).  The oracle cannot compute a whole 144 x 36864 x 12288 product
+in seconds, so these tests check SAMPLED outputs one by one: output columns (weight rows) and
+activation rows are drawn at tile and block boundaries and at random, the oracle quantizes exactly
+those weight rows itself, its codes must equal the device's bit for bit, and its FP64 dot products
+bound the device outputs with the usual tolerance.  Bulk operands are drawn on the device with a
+seeded generator (they are inputs, not results); everything the oracle consumes is copied from
+those inputs, never from a kernel's output."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fg_oracle as O
+from paper_2303_06865_amd import binding as B
+from tests.util import assert_close, host
+
+pytestmark = pytest.mark.gpu
+
+
+def _gen(shape, std, seed):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    return torch.empty(shape, dtype=torch.float16, device="cuda").normal_(0.0, std, generator=g)
+
+
+def _sample(n, edges, k, seed):
+    rng = np.random.default_rng(seed)
+    pts = {0, n - 1}
+    for e in edges:
+        for d in (-1, 0):
+            if 0 <= e + d < n:
+                pts.add(e + d)
+    pts.update(int(v) for v in rng.integers(0, n, size=k))
+    return np.array(sorted(pts), dtype=np.int64)
+
+
+# (rows, out features, in features, quantized): the four projection shapes of the OPT-175B workload in
+# the decode phase (144 rows) and in the prefill phase (36 x 512 rows), and the FP16 LM head
+FULL_LINEAR = [
+    (144, 36864, 12288, True),
+    (144, 12288, 49152, True),
+    (144, 49152, 12288, True),
+    (18432, 36864, 12288, True),
+    (18432, 12288, 49152, True),
+    (144, 50272, 12288, False),
+]
+
+
+@pytest.mark.parametrize("m,n,k,quant", FULL_LINEAR)
+def test_linear_full_size_sampled(m, n, k, quant):
+    w = _gen((n, k), 0.02, 1000 + n % 97 + k % 89)
+    x = _gen((m, k), 1.0, 2000 + m)
+    res = _gen((m, n), 1.0, 3000 + m)
+    bias = _gen((n,), 0.5, 4000)
+    wm = B.Mat.from_f16(w, quant, tiled=quant)
+    out = B.fg_linear(wm, bias, x, res, False)
+    torch.cuda.synchronize()
+
+    cols = _sample(n, [255, 256, 32 * 1151, n - 256, n // 2], 24, n + k)
+    rows = _sample(m, [31, 32, 159, 160, 255, 256, m // 2, m - 33], 24, m + k) if m > 160 else np.arange(m)
+    w_rows = host(w[torch.from_numpy(cols).cuda()])
+    om = O.Mat.from_f16(w_rows, quant)
+    if quant:   # the device quantized the very same rows to the very same bytes (checked on the canonical form)
+        canon = B.Mat.from_f16(w[torch.from_numpy(cols).cuda()].contiguous(), True)
+        assert np.array_equal(host(canon.data), om.codes)
+        assert np.array_equal(host(canon.meta).view(np.uint32), om.meta.view(np.uint32))
+    ti = torch.from_numpy(rows).cuda()
+    tj = torch.from_numpy(cols).cuda()
+    x_s = host(x[ti]).astype(np.float64)
+    y = x_s @ om.dense().T + host(bias[tj]).astype(np.float64)[None, :]
+    y = y + host(res[ti][:, tj]).astype(np.float64)
+    got = host(out[ti][:, tj])
+    assert_close(got, O.round_f16(y), "full-size linear m=%d n=%d k=%d q=%s" % (m, n, k, quant))
+
+
+@pytest.mark.parametrize("b,rows", [(144, 528), (144, 543)])
+def test_decode_attention_full_size_sampled(b, rows):
+    """OPT-175B decode attention launch (144 x 96 heads, 4-bit cache).  The cache is filled with
+    arbitrary bytes on the device; the sampled (sequence, head) streams are then overwritten with rows
+    the oracle quantized, and only those heads are compared."""
+    nh, dh = 96, 128
+    h1 = nh * dh
+    cfg = B.Cfg(h1, nh, 4 * h1, 50272, 4096)
+    cap = rows + 5
+    kv = B.KVCache(cfg, b, cap, True, zero=False)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(99)
+    kv.k_codes.random_(0, 256, generator=g)
+    kv.v_codes.random_(0, 256, generator=g)
+    kv.k_meta.normal_(0.0, 0.3, generator=g).abs_()
+    kv.v_meta.normal_(0.0, 0.3, generator=g).abs_()
+    q = _gen((b, 3 * h1), 1.0, 7)
+    rng = np.random.default_rng(rows)
+    pairs = [(0, 0), (b - 1, nh - 1), (b // 2, 37)] + [(int(rng.integers(0, b)), int(rng.integers(0, nh))) for _ in range(9)]
+    refs = []
+    for (si, hi) in pairs:
+        k16 = (rng.standard_normal((1, rows, dh))).astype(np.float16)
+        v16 = (rng.standard_normal((1, rows, dh))).astype(np.float16)
+        okv = O.KVCache.empty(1, 1, cap, dh, True)
+        okv.store(0, 0, k16, v16)
+        kv.k_codes[si, hi].copy_(torch.from_numpy(okv.k_codes[0, 0]).cuda())
+        kv.v_codes[si, hi].copy_(torch.from_numpy(okv.v_codes[0, 0]).cuda())
+        kv.k_meta[si, hi].copy_(torch.from_numpy(okv.k_meta[0, 0]).cuda())
+        kv.v_meta[si, hi].copy_(torch.from_numpy(okv.v_meta[0, 0]).cuda())
+        kh, vh = okv.load(0, 0, rows)
+        qv = host(q[si, hi * dh:(hi + 1) * dh]).astype(np.float64)
+        refs.append(O.attn_decode(qv, kh, vh))
+    out = B.fg_decode_attention(cfg, q, 3 * h1, b, rows, kv, 0)
+    torch.cuda.synchronize()
+    got = np.stack([host(out[si, hi * dh:(hi + 1) * dh]) for (si, hi) in pairs])
+    assert_close(got, O.round_f16(np.stack(refs)), "full-size decode attention rows=%d" % rows)
+    assert bool(torch.isfinite(out.float()).all())
