@@ -559,6 +559,9 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const uint8_t* __rest
 struct Shape {
   int mt, nt, wm, nw;
   int rows() const { return wm * mt * 32; }
+  // One workgroup per CU, except for the 32-row shape: its stages are small enough for two workgroups
+  // per CU, which doubles the bytes in flight of what is then a pure weight streamer.
+  int grid() const { return (wm == 1 && mt == 1) ? 512 : 256; }
 };
 Shape pick_shape(int64_t m) {
   // Up to two row blocks the side-by-side shape wins (few tiles: the 256-row shape would leave most of
@@ -589,7 +592,8 @@ int launch_t(const StreamArgs& a, hipStream_t stream) {
 size_t gemm_stream_workspace(int64_t n, int64_t k, int64_t m) {
   (void)n;
   (void)k;
-  return (size_t)256 * 2 * pick_shape(m).rows() * kBN * sizeof(float);
+  const Shape sh = pick_shape(m);
+  return (size_t)sh.grid() * 2 * sh.rows() * kBN * sizeof(float);
 }
 
 int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStream_t stream) {
@@ -607,7 +611,7 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   a.n_tiles = (int)ceil_div(la.n, kBN);
   a.ksteps = (int)(la.k / kKS);
   a.n32 = (int)(la.n / 32);
-  a.grid = 256;
+  a.grid = sh.grid();
   const int64_t tiles = (int64_t)a.m_blocks * a.n_tiles;
   a.rounds = (int)(tiles / a.grid);
   const int64_t rem_tiles = tiles - (int64_t)a.rounds * a.grid;
