@@ -165,10 +165,14 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
   auto process = [&](const Buf& b, int chunk) {
     const int gbase = chunk << 7;
     const int g0 = gbase + 2 * lane, g1 = g0 + 1;
+    // load i of a chunk covers 32 groups; the last chunk of a stream may need only the first few
+    // (wave-uniform count, so the skipped work costs nothing)
+    const int ni = (G - gbase + 31) >> 5;
     // ---- scores on the matrix cores
     f4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+      if (i >= ni) break;
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         uint32_t pk[4];
@@ -214,6 +218,7 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
     // the mixed-precision FMA takes it as it is, the weight carries the inverse power of two.
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+      if (i >= ni) break;
       const int src = 16 * i + r;
       const float w0 = __shfl(wv0, src, 64), w1 = __shfl(wv1, src, 64);
       const float w = h ? w1 : w0;
