@@ -95,6 +95,32 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
   const int G = a.rows * GPR;                  // groups in the stream
   const int n_chunks = (G + 127) >> 7;
 
+  // one chunk's worth of registers: 4 + 4 code loads of 16 bytes and the meta of the lane's two groups
+  struct Buf {
+    u4_t kq[4], vq[4];
+    float2 km0, km1, vm0, vm1;
+  };
+  // all addresses clamped into the stream; rows past the end are masked when the chunk is processed
+  auto load = [&](Buf& b, int chunk) {
+    const int gbase = chunk << 7;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int g = gbase + 32 * i + 2 * r + h;
+      g = g < G ? g : G - 1;
+      b.kq[i] = *reinterpret_cast<const u4_t*>(kc + (int64_t)g * 32 + half * 16);
+      b.vq[i] = *reinterpret_cast<const u4_t*>(vc + (int64_t)g * 32 + half * 16);
+    }
+    const int g0 = gbase + 2 * lane, g1 = g0 + 1;
+    const int c0 = g0 < G ? g0 : G - 1, c1 = g1 < G ? g1 : G - 1;
+    b.km0 = km[c0];
+    b.km1 = km[c1];
+    b.vm0 = vm[c0];
+    b.vm1 = vm[c1];
+  };
+  // the first chunk's loads go out before anything else: they overlap the query set-up below
+  Buf b0, b1;
+  if (part < n_chunks) load(b0, part);
+
   half_t* my_q = sm_q + hl * DH;
   if (part == 0 && lane < DH / 8)
     *reinterpret_cast<u4_t*>(my_q + lane * 8) =
@@ -140,28 +166,6 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
 #pragma unroll
   for (int e = 0; e < 32; ++e) o[e] = 0.f;
 
-  // one chunk's worth of registers: 4 + 4 code loads of 16 bytes and the meta of the lane's two groups
-  struct Buf {
-    u4_t kq[4], vq[4];
-    float2 km0, km1, vm0, vm1;
-  };
-  // all addresses clamped into the stream; rows past the end are masked when the chunk is processed
-  auto load = [&](Buf& b, int chunk) {
-    const int gbase = chunk << 7;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int g = gbase + 32 * i + 2 * r + h;
-      g = g < G ? g : G - 1;
-      b.kq[i] = *reinterpret_cast<const u4_t*>(kc + (int64_t)g * 32 + half * 16);
-      b.vq[i] = *reinterpret_cast<const u4_t*>(vc + (int64_t)g * 32 + half * 16);
-    }
-    const int g0 = gbase + 2 * lane, g1 = g0 + 1;
-    const int c0 = g0 < G ? g0 : G - 1, c1 = g1 < G ? g1 : G - 1;
-    b.km0 = km[c0];
-    b.km1 = km[c1];
-    b.vm0 = vm[c0];
-    b.vm1 = vm[c1];
-  };
   auto process = [&](const Buf& b, int chunk) {
     const int gbase = chunk << 7;
     const int g0 = gbase + 2 * lane, g1 = g0 + 1;
@@ -242,9 +246,8 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
     }
   };
 
-  // two register buffers, the loop unrolled by two so that neither is ever moved while loads fly
-  Buf b0, b1;
-  if (part < n_chunks) load(b0, part);
+  // (the first chunk is already on its way; the loop is unrolled by two so that neither buffer is ever
+  // moved while loads fly)
   for (int chunk = part; chunk < n_chunks; chunk += 2 * WPH) {
     const bool more1 = chunk + WPH < n_chunks;
     if (more1) load(b1, chunk + WPH);
