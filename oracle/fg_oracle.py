@@ -200,6 +200,34 @@ def attn_decode(q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.ndarray:
     return p @ v
 
 
+def attn_decode_scores(q: np.ndarray, k: np.ndarray) -> np.ndarray:
+    """Scaled attention scores of one query against the cached keys: q . K^T / sqrt(dh)."""
+    return (k @ q) / math.sqrt(q.shape[-1])
+
+
+def topk_indices(s: np.ndarray, topk: int) -> np.ndarray:
+    """Indices of the `topk` largest scores, ascending; among equal scores the lowest index wins
+    (the paper does not say: this is the reading both sides use)."""
+    order = np.argsort(-s, kind="stable")      # stable: equal scores keep index order
+    return np.sort(order[:topk])
+
+
+def attn_decode_subset(q: np.ndarray, k: np.ndarray, v: np.ndarray, idx: np.ndarray) -> np.ndarray:
+    """Sparse decode attention for a given set of kept rows (Section 5, sparse attention): the
+    attention weights are those of the FULL softmax over all cached rows; the rows outside `idx` are
+    dropped, i.e. only the V rows in `idx` are read, and nothing is renormalised."""
+    p = softmax_rows(attn_decode_scores(q, k)[None, :])[0]
+    return p[idx] @ v[idx]
+
+
+def attn_decode_topk(q: np.ndarray, k: np.ndarray, v: np.ndarray, topk: int):
+    """Top-K sparse decode attention (Section 5, sparse attention): after the attention weights of
+    the query are known, keep its `topk` highest-weighted rows and load only those rows of V.
+    Returns (output [dh], kept indices ascending)."""
+    idx = topk_indices(attn_decode_scores(q, k), topk)
+    return attn_decode_subset(q, k, v, idx), idx
+
+
 def attn_prefill(q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.ndarray:
     """One head, s queries, causal (Section 3, prefill phase): row i attends
     to rows 0..i.  q, k, v are [s, dh]."""

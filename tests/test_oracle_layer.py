@@ -105,6 +105,47 @@ def test_decode_attention_special_cases():
     assert np.allclose(O.attn_decode(q, k[:1], v[:1]), v[0], atol=1e-15)
 
 
+def test_topk_sparse_attention_pins():
+    """Top-K sparse attention (Section 5): brute force in pure Python, the dense limit, a dominant
+    key, the tie rule, and the monotone kept mass."""
+    q = _r(16, 1.0, 40)
+    k = _r((23, 16), 1.0, 41)
+    v = _r((23, 16), 1.0, 42)
+    # brute force: full softmax in pure Python, keep the 5 largest weights, drop the rest
+    s = [sum(a * b for a, b in zip(row, q.tolist())) / 4.0 for row in k.tolist()]
+    mx = max(s)
+    e = [math.exp(x - mx) for x in s]
+    den = sum(e)
+    order = sorted(range(23), key=lambda i: (-s[i], i))[:5]
+    ref = [sum(e[i] / den * v[i, d] for i in order) for d in range(16)]
+    out, idx = O.attn_decode_topk(q, k, v, 5)
+    assert sorted(order) == idx.tolist()
+    assert np.allclose(out, ref, atol=1e-13)
+    # keeping every row is dense attention
+    out_all, idx_all = O.attn_decode_topk(q, k, v, 23)
+    assert idx_all.tolist() == list(range(23))
+    assert np.allclose(out_all, O.attn_decode(q, k, v), atol=1e-14)
+    # one dominant key: keeping a single row returns (almost exactly) its V row
+    k2 = _r((23, 16), 0.01, 43)
+    k2[7] = q * 40.0
+    out1, idx1 = O.attn_decode_topk(q, k2, v, 1)
+    assert idx1.tolist() == [7] and np.allclose(out1, v[7], atol=1e-9)
+    # equal scores: the lowest indices are kept
+    k3 = np.tile(_r((1, 16), 1.0, 44), (9, 1))
+    _, idx3 = O.attn_decode_topk(q, k3, v[:9], 4)
+    assert idx3.tolist() == [0, 1, 2, 3]
+    # the weights are those of the FULL softmax (no renormalisation): uniform weights 1/9 each
+    out3 = O.attn_decode_subset(q, k3, v[:9], np.array([0, 1, 2, 3]))
+    assert np.allclose(out3, v[:4].sum(axis=0) / 9.0, atol=1e-13)
+    # the kept probability mass grows with k and reaches 1
+    p = O.softmax_rows(O.attn_decode_scores(q, k)[None, :])[0]
+    masses = [p[O.topk_indices(O.attn_decode_scores(q, k), kk)].sum() for kk in range(1, 24)]
+    assert all(b >= a for a, b in zip(masses, masses[1:])) and abs(masses[-1] - 1.0) < 1e-14
+    # and the kept set is optimal: no dropped row outweighs a kept one
+    kept = set(idx.tolist())
+    assert min(p[i] for i in kept) >= max(p[i] for i in range(23) if i not in kept)
+
+
 def test_decode_attention_split_merge_invariance():
     """Attention over rows [0,n) equals the log-sum-exp merge of attention over
     any two-way split of the rows."""
