@@ -167,6 +167,17 @@ int fg_decode_attention(const fg_model_cfg* cfg, const void* q_f16, int64_t q_ro
                         int32_t rows, const fg_kv_cache* kv, int32_t batch_offset, void* out_f16,
                         void* stream);
 
+/* Top-K sparse variant of fg_decode_attention (Section 5, sparse attention), FG_Q4G64 caches only
+ * (FG_ERR_UNSUPPORTED otherwise): the attention weights are those of the full softmax over rows
+ * 0 .. rows-1; only the topk highest-weighted rows of V are read and summed with those weights (no
+ * renormalisation); among equal scores the lowest row index is kept.  1 <= topk <= rows
+ * (FG_ERR_SHAPE otherwise); rows (rounded up to a multiple of 128) + topk may not exceed 36864
+ * (FG_ERR_UNSUPPORTED: the scores of one head are kept on chip).  kept_rows, if not NULL, is a device
+ * int32 [b, nh, topk] array that receives the kept row indices in ascending order. */
+int fg_decode_attention_topk(const fg_model_cfg* cfg, const void* q_f16, int64_t q_row_stride, int32_t b,
+                             int32_t rows, int32_t topk, const fg_kv_cache* kv, int32_t batch_offset,
+                             void* out_f16, int32_t* kept_rows, void* stream);
+
 /* Prefill-phase attention (Section 3): causal softmax(q . k^T / sqrt(dh)) . v per sequence and
  * head over the fresh FP16 q, k, v held in qkv [b*s, 3*h1] (columns q | k | v); out [b*s, h1]. */
 int fg_prefill_attention(const fg_model_cfg* cfg, const void* qkv_f16, int32_t b, int32_t s,

@@ -66,6 +66,9 @@ EXPORTS = {
                                C.POINTER(fg_kv_cache), C.c_int32, C.c_int32, C.c_void_p]),
     "fg_decode_attention": (C.c_int, [C.POINTER(fg_model_cfg), C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
                                       C.POINTER(fg_kv_cache), C.c_int32, C.c_void_p, C.c_void_p]),
+    "fg_decode_attention_topk": (C.c_int, [C.POINTER(fg_model_cfg), C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
+                                           C.c_int32, C.POINTER(fg_kv_cache), C.c_int32, C.c_void_p, C.c_void_p,
+                                           C.c_void_p]),
     "fg_prefill_attention": (C.c_int, [C.POINTER(fg_model_cfg), C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                        C.c_void_p]),
     "fg_embed": (C.c_int, [C.POINTER(fg_model_cfg), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
@@ -285,6 +288,16 @@ def fg_decode_attention(cfg: Cfg, q: torch.Tensor, q_row_stride: int, b: int, ro
     _check(lib().fg_decode_attention(C.byref(cfg.c), _p(q), q_row_stride, b, rows, C.byref(kv.c), batch_offset,
                                      _p(out), _stream()), "fg_decode_attention")
     return out
+
+
+def fg_decode_attention_topk(cfg: Cfg, q: torch.Tensor, q_row_stride: int, b: int, rows: int, topk: int, kv: KVCache,
+                             batch_offset: int = 0, want_rows: bool = False):
+    """Returns out [b, h1] (and the kept row indices int32 [b, nh, topk] if want_rows)."""
+    out = torch.empty((b, cfg.h1), dtype=torch.float16, device=q.device)
+    kept = torch.empty((b, cfg.nh, topk), dtype=torch.int32, device=q.device) if want_rows else None
+    _check(lib().fg_decode_attention_topk(C.byref(cfg.c), _p(q), q_row_stride, b, rows, topk, C.byref(kv.c),
+                                          batch_offset, _p(out), _p(kept), _stream()), "fg_decode_attention_topk")
+    return (out, kept) if want_rows else out
 
 
 def fg_prefill_attention(cfg: Cfg, qkv: torch.Tensor, b: int, s: int) -> torch.Tensor:

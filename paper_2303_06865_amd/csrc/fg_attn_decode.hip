@@ -21,13 +21,11 @@
 //   output  : sum_j p_j v_hat_j = sum_j (p_j scale_j) c_j + sum_j p_j min_j; the first term is
 //             accumulated per lane over its 32 head dimensions with FP16->FP32 mixed FMAs on the
 //             nibbles taken in place as FP16 subnormals, the second is one scalar per group.
-#include "fg_common.h"
+#include "fg_attn_common.h"
 
 namespace fg {
 
 namespace {
-
-constexpr float kLog2e = 1.4426950408889634f;
 
 struct AttnArgs {
   const half_t* q;
@@ -41,8 +39,6 @@ struct AttnArgs {
   int n_heads;       // b * nh
   float scale;       // 1/sqrt(dh)
 };
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Merge the WPH per-wave triples of each head of the block and write the outputs.  o_w already
 // includes the per-group constant term.  out0 = output row of the block's first head.
@@ -127,38 +123,8 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
         *reinterpret_cast<const u4_t*>(a.q + (int64_t)seq * a.q_stride + head * DH + lane * 8);
   __syncthreads();
 
-  // per-group query sums: Qs = sum q_d, Os = sum off_d q_d with off = 1024 (even d) / 64 (odd d),
-  // the biases the register unpacking leaves on the codes.
-  float Qs[2], Os[2];
-  {
-    const float qa_ = (float)my_q[lane];
-    const float qb_ = DH == 128 ? (float)my_q[(lane + 64) % DH] : qa_;
-    const float off = (lane & 1) ? 64.f : 1024.f;
-    Qs[0] = wave_sum(qa_);
-    Os[0] = wave_sum(qa_ * off);
-    Qs[1] = wave_sum(qb_);
-    Os[1] = wave_sum(qb_ * off);
-  }
-
-  // A operands: qop[i][u] is non-zero only in lanes whose output row (lane&15) equals 4*i + h,
-  // so that load i's sixteen rows land in lane group i of the accumulator.
-  h8_t qop[4][4];
-  {
-    const int m = lane & 15;
-    const bool valid_h = (m & 3) == h;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int d0 = (DH == 128 ? 64 * h : 0) + 32 * half + 8 * u;
-      const u4_t raw = *reinterpret_cast<const u4_t*>(my_q + d0);
-      const u4_t pm = permute8_like_codes(raw);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bool valid = valid_h && ((m >> 2) == i);
-        const u4_t z = {0u, 0u, 0u, 0u};
-        qop[i][u] = __builtin_bit_cast(h8_t, valid ? pm : z);
-      }
-    }
-  }
+  QueryOps<DH> Q;
+  query_setup<DH>(my_q, lane, Q);
 
   float m_run = -INFINITY, l_run = 0.f;
   float mterm[2] = {0.f, 0.f};   // sum_j p_j min_j for the groups this lane owns
@@ -168,32 +134,10 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
 
   auto process = [&](const Buf& b, int chunk) {
     const int gbase = chunk << 7;
-    const int g0 = gbase + 2 * lane, g1 = g0 + 1;
-    // load i of a chunk covers 32 groups; the last chunk of a stream may need only the first few
-    // (wave-uniform count, so the skipped work costs nothing)
-    const int ni = (G - gbase + 31) >> 5;
+    const int ni = (G - gbase + 31) >> 5;   // 32-group loads of this chunk that hold valid rows
     // ---- scores on the matrix cores
-    f4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (i >= ni) break;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        uint32_t pk[4];
-        unpack8_biased(b.kq[i][u], pk);
-        const u4_t bw = {pk[0], pk[1], pk[2], pk[3]};
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qop[i][u], __builtin_bit_cast(h8_t, bw), acc, 0, 0, 0);
-      }
-    }
-    const float s0 = b.km0.y * (acc[0] - Os[0]) + b.km0.x * Qs[0];
-    const float s1 = b.km1.y * (acc[1] - Os[1]) + b.km1.x * Qs[1];
     float sc[NS];
-    if (DH == 128) {
-      sc[0] = g0 < G ? (s0 + s1) * a.scale : -INFINITY;
-    } else {
-      sc[0] = g0 < G ? s0 * a.scale : -INFINITY;
-      sc[NS - 1] = g1 < G ? s1 * a.scale : -INFINITY;
-    }
+    chunk_scores<DH>(b.kq, b.km0, b.km1, Q, a.scale, G, gbase, lane, sc);
     // ---- online softmax (every processed chunk has at least one valid row)
     float cmax = sc[0];
     if (NS == 2) cmax = fmaxf(cmax, sc[NS - 1]);

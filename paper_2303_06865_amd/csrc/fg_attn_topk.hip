@@ -1,0 +1,351 @@
+// Top-K sparse decode attention over the 4-bit KV cache (Section 5, sparse attention; decode phase of
+// Section 3): the attention weights of the query are those of the full softmax over all cached rows;
+// only the `topk` highest-weighted rows of V are then read, the rest is dropped without
+// renormalisation.  Among equal scores the lowest row index is kept.
+//
+// One workgroup of four waves per (sequence, head), three phases:
+//   1. scores   the K stream is read once, exactly as in the dense kernel (MFMA on the codes); the
+//               scaled scores of all rows go to LDS;
+//   2. select   exact k-th largest score by a four-pass radix select over the order-preserving
+//               integer image of the scores (256-bin LDS histograms), then a compaction in row order:
+//               rows above the threshold, plus the first rows equal to it until k rows are kept;
+//   3. gather   the kept rows of V (DH/2 bytes of codes + their {min,scale} each) are fetched by
+//               DH/16 lanes per row and accumulated with the full-softmax weights.
+// K is half of the dense kernel's bytes and V shrinks to k/rows of it.
+#include "fg_attn_common.h"
+
+namespace fg {
+
+namespace {
+
+struct TopkArgs {
+  const half_t* q;
+  int64_t q_stride;
+  const uint8_t* k_codes;
+  const uint8_t* v_codes;
+  const float2* k_meta;
+  const float2* v_meta;
+  half_t* out;       // [b, nh*dh]
+  int32_t* sel_out;  // [b, nh, topk] kept row indices, ascending, or NULL
+  int nh, cap, rows, topk, batch_offset;
+  int rows_pad;      // rows rounded up to whole chunks: size of the score array in LDS
+  float scale;       // 1/sqrt(dh)
+};
+
+__device__ __forceinline__ uint32_t order_key(float s) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, s);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);   // larger score <=> larger key
+}
+
+// exclusive prefix sum of one value per thread over the 256 threads; *total gets the sum
+__device__ __forceinline__ int block_excl_scan(int v, int* s_wave, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int incl = v;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += t;
+  }
+  __syncthreads();   // s_wave may still be read from a previous call
+  if (lane == 63) s_wave[wave] = incl;
+  __syncthreads();
+  int base = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+    if (w < wave) base += s_wave[w];
+  *total = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+  return base + incl - v;
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
+  constexpr int GPR = DH / 64;       // quantization groups per row
+  constexpr int NS = 2 / GPR;        // scores per lane per chunk
+  constexpr int RPC = 128 / GPR;     // rows per chunk
+  constexpr int LPR = DH / 16;       // gather: lanes per V row (8 bytes = 16 codes each)
+  constexpr int RPI = 64 / LPR;      // gather: rows per wave iteration
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn[];
+  float* s_sc = reinterpret_cast<float*>(dyn);                    // [rows_pad]
+  int* s_sel = reinterpret_cast<int*>(dyn) + a.rows_pad;          // [topk]
+  __shared__ __attribute__((aligned(16))) half_t sm_q[DH];
+  __shared__ int s_hist[256];
+  __shared__ int s_wave[4];
+  __shared__ float s_red[4];
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_need;
+  __shared__ float s_o[4 * DH];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int hid = blockIdx.x;
+  const int seq = hid / a.nh, head = hid - seq * a.nh;
+  const int r = lane & 15, q4 = lane >> 4, h = q4 >> 1, half = q4 & 1;
+  const int n = a.rows;
+
+  const int64_t hrow = ((int64_t)(a.batch_offset + seq) * a.nh + head) * a.cap;   // first cache row
+  const uint8_t* kc = a.k_codes + hrow * (DH / 2);
+  const uint8_t* vc = a.v_codes + hrow * (DH / 2);
+  const float2* km = a.k_meta + hrow * GPR;
+  const float2* vm = a.v_meta + hrow * GPR;
+  const int G = n * GPR;
+  const int n_chunks = (G + 127) >> 7;
+
+  struct Buf {
+    u4_t kq[4];
+    float2 km0, km1;
+  };
+  auto load = [&](Buf& b, int chunk) {
+    const int gbase = chunk << 7;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int g = gbase + 32 * i + 2 * r + h;
+      g = g < G ? g : G - 1;
+      b.kq[i] = *reinterpret_cast<const u4_t*>(kc + (int64_t)g * 32 + half * 16);
+    }
+    const int g0 = gbase + 2 * lane, g1 = g0 + 1;
+    b.km0 = km[g0 < G ? g0 : G - 1];
+    b.km1 = km[g1 < G ? g1 : G - 1];
+  };
+  Buf b0, b1;
+  if (wave < n_chunks) load(b0, wave);
+
+  if (tid < DH / 8)
+    *reinterpret_cast<u4_t*>(sm_q + tid * 8) =
+        *reinterpret_cast<const u4_t*>(a.q + (int64_t)seq * a.q_stride + head * DH + tid * 8);
+  __syncthreads();
+  QueryOps<DH> Q;
+  query_setup<DH>(sm_q, lane, Q);
+
+  // ---- phase 1: scores of all rows -> LDS (rows past the end hold -inf)
+  auto scores = [&](const Buf& b, int chunk) {
+    float sc[NS];
+    chunk_scores<DH>(b.kq, b.km0, b.km1, Q, a.scale, G, chunk << 7, lane, sc);
+    if (DH == 128) {
+      s_sc[chunk * RPC + lane] = sc[0];
+    } else {
+      s_sc[chunk * RPC + 2 * lane] = sc[0];
+      s_sc[chunk * RPC + 2 * lane + 1] = sc[NS - 1];
+    }
+  };
+  for (int chunk = wave; chunk < n_chunks; chunk += 8) {
+    const bool more1 = chunk + 4 < n_chunks;
+    if (more1) load(b1, chunk + 4);
+    __builtin_amdgcn_sched_barrier(0);
+    scores(b0, chunk);
+    if (more1) {
+      if (chunk + 8 < n_chunks) load(b0, chunk + 8);
+      __builtin_amdgcn_sched_barrier(0);
+      scores(b1, chunk + 4);
+    }
+  }
+  __syncthreads();
+
+  // ---- maximum and softmax denominator over all rows
+  float mx = -INFINITY;
+  for (int i = tid; i < n; i += 256) mx = fmaxf(mx, s_sc[i]);
+  mx = wave_max(mx);
+  if (lane == 0) s_red[wave] = mx;
+  __syncthreads();
+  const float M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+  float den = 0.f;
+  for (int i = tid; i < n; i += 256) den += fast_exp2((s_sc[i] - M) * kLog2e);
+  den = wave_sum(den);
+  __syncthreads();
+  if (lane == 0) s_red[wave] = den;
+  __syncthreads();
+  const float inv_den = 1.0f / (s_red[0] + s_red[1] + s_red[2] + s_red[3]);
+
+  // ---- phase 2: radix select of the topk-th largest key, most significant byte first
+  if (tid == 0) {
+    s_prefix = 0u;
+    s_need = a.topk;
+  }
+  uint32_t mask = 0u;
+#pragma unroll 1
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    s_hist[tid] = 0;
+    __syncthreads();
+    const uint32_t prefix = s_prefix;
+    for (int i = tid; i < n; i += 256) {
+      const uint32_t key = order_key(s_sc[i]);
+      if ((key & mask) == prefix) atomicAdd(&s_hist[(key >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    if (wave == 0) {
+      // bins in descending order: lane l owns bins 255-4l .. 252-4l
+      const int need = s_need;
+      int c[4], sum = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        c[j] = s_hist[255 - (4 * lane + j)];
+        sum += c[j];
+      }
+      int incl = sum;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int t = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += t;
+      }
+      const uint64_t reach = __builtin_amdgcn_ballot_w64(incl >= need);
+      const int first = __builtin_ctzll(reach);   // reach != 0: the candidates number at least `need`
+      if (lane == first) {
+        int above = incl - sum;                   // keys in higher bins
+        int j = 0;
+        while (j < 3 && above + c[j] < need) {
+          above += c[j];
+          ++j;
+        }
+        s_prefix = prefix | ((uint32_t)(255 - (4 * lane + j)) << shift);
+        s_need = need - above;
+      }
+    }
+    mask |= 255u << shift;
+    __syncthreads();
+  }
+  const uint32_t T = s_prefix;     // key of the topk-th largest score
+  const int need_eq = s_need;      // rows equal to it that are kept (the lowest indices)
+
+  // ---- compaction in row order: thread t owns rows [t*per, (t+1)*per)
+  const int per = (n + 255) >> 8;
+  const int r0 = tid * per, r1 = (r0 + per) < n ? (r0 + per) : n;
+  int n_gt = 0, n_eq = 0;
+  for (int i = r0; i < r1; ++i) {
+    const uint32_t key = order_key(s_sc[i]);
+    n_gt += key > T;
+    n_eq += key == T;
+  }
+  int tot;
+  const int eq_before = block_excl_scan(n_eq, s_wave, &tot);
+  int eq_take = need_eq - eq_before;
+  eq_take = eq_take < 0 ? 0 : (eq_take > n_eq ? n_eq : eq_take);
+  int pos = block_excl_scan(n_gt + eq_take, s_wave, &tot);
+  for (int i = r0; i < r1; ++i) {
+    const uint32_t key = order_key(s_sc[i]);
+    bool keep = key > T;
+    if (key == T && eq_take > 0) {
+      keep = true;
+      --eq_take;
+    }
+    if (keep) s_sel[pos++] = i;
+  }
+  __syncthreads();
+  if (a.sel_out)
+    for (int e = tid; e < a.topk; e += 256) a.sel_out[(int64_t)hid * a.topk + e] = s_sel[e];
+
+  // ---- phase 3: gather the kept V rows.  Lane = (row slot rs, 8-byte piece pc of the row).
+  const int rs = lane / LPR, pc = lane - rs * LPR;
+  float o[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) o[e] = 0.f;
+  float mterm = 0.f;
+  for (int e0 = wave * RPI; e0 < a.topk; e0 += 4 * RPI) {
+    const int e = e0 + rs;
+    const bool valid = e < a.topk;
+    const int row = s_sel[valid ? e : a.topk - 1];
+    const float p = valid ? fast_exp2((s_sc[row] - M) * kLog2e) * inv_den : 0.f;
+    const uint2 cw = *reinterpret_cast<const uint2*>(vc + (int64_t)row * (DH / 2) + pc * 8);
+    const float2 mt = vm[(int64_t)row * GPR + (pc >> 2)];
+    const float w = p * mt.y;
+    const float w24 = w * 16777216.0f, w20 = w * 1048576.0f;   // nibbles are read as FP16 subnormals
+    mterm += p * mt.x;
+    const uint32_t xs[2] = {cw.x, cw.y};
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const uint32_t x = xs[u], y = x >> 8;
+      const h2_t c04 = __builtin_bit_cast(h2_t, x & 0x000F000Fu);
+      const h2_t c15 = __builtin_bit_cast(h2_t, x & 0x00F000F0u);
+      const h2_t c26 = __builtin_bit_cast(h2_t, y & 0x000F000Fu);
+      const h2_t c37 = __builtin_bit_cast(h2_t, y & 0x00F000F0u);
+      o[8 * u + 0] = __builtin_fmaf((float)c04.x, w24, o[8 * u + 0]);
+      o[8 * u + 4] = __builtin_fmaf((float)c04.y, w24, o[8 * u + 4]);
+      o[8 * u + 1] = __builtin_fmaf((float)c15.x, w20, o[8 * u + 1]);
+      o[8 * u + 5] = __builtin_fmaf((float)c15.y, w20, o[8 * u + 5]);
+      o[8 * u + 2] = __builtin_fmaf((float)c26.x, w24, o[8 * u + 2]);
+      o[8 * u + 6] = __builtin_fmaf((float)c26.y, w24, o[8 * u + 6]);
+      o[8 * u + 3] = __builtin_fmaf((float)c37.x, w20, o[8 * u + 3]);
+      o[8 * u + 7] = __builtin_fmaf((float)c37.y, w20, o[8 * u + 7]);
+    }
+  }
+  // lanes with the same piece add up over the row slots, then the four waves through LDS
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    float v = o[e] + mterm;
+#pragma unroll
+    for (int d = LPR; d < 64; d <<= 1) v += __shfl_xor(v, d, 64);
+    o[e] = v;
+  }
+  if (lane < LPR) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s_o[wave * DH + 16 * pc + e] = o[e];
+  }
+  __syncthreads();
+  if (tid < DH)
+    a.out[(int64_t)hid * DH + tid] = (half_t)(s_o[tid] + s_o[DH + tid] + s_o[2 * DH + tid] + s_o[3 * DH + tid]);
+}
+
+constexpr int kMaxLdsWords = 36 * 1024;   // score array + index list, 4 bytes each (144 KiB)
+
+}  // namespace
+
+int decode_attention_topk_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_stride, int32_t b, int32_t rows,
+                                 int32_t topk, const fg_kv_cache& kv, int32_t batch_offset, half_t* out,
+                                 int32_t* sel_out, hipStream_t stream) {
+  if (b == 0) return FG_OK;
+  const int dh = cfg.h1 / cfg.nh;
+  const int rpc = dh == 128 ? 64 : 128;
+  TopkArgs a;
+  a.q = q;
+  a.q_stride = q_stride;
+  a.k_codes = reinterpret_cast<const uint8_t*>(kv.k_codes);
+  a.v_codes = reinterpret_cast<const uint8_t*>(kv.v_codes);
+  a.k_meta = reinterpret_cast<const float2*>(kv.k_meta);
+  a.v_meta = reinterpret_cast<const float2*>(kv.v_meta);
+  a.out = out;
+  a.sel_out = sel_out;
+  a.nh = cfg.nh;
+  a.cap = kv.cap;
+  a.rows = rows;
+  a.topk = topk;
+  a.batch_offset = batch_offset;
+  a.rows_pad = (int)(ceil_div(rows, rpc) * rpc);
+  a.scale = 1.0f / sqrtf((float)dh);
+  if ((int64_t)a.rows_pad + topk > kMaxLdsWords) return FG_ERR_UNSUPPORTED;
+  const size_t smem = ((size_t)a.rows_pad + topk) * 4;
+  const dim3 grid((unsigned)(b * cfg.nh));
+  static bool attr_done[2] = {false, false};
+  const void* fn = dh == 128 ? (const void*)&attn_decode_topk_q4_kernel<128> : (const void*)&attn_decode_topk_q4_kernel<64>;
+  if (!attr_done[dh == 128]) {
+    FG_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsWords * 4));
+    attr_done[dh == 128] = true;
+  }
+  ProfScope prof(FG_K_ATTN_DECODE, stream);
+  if (dh == 128)
+    hipLaunchKernelGGL(attn_decode_topk_q4_kernel<128>, grid, dim3(256), smem, stream, a);
+  else
+    hipLaunchKernelGGL(attn_decode_topk_q4_kernel<64>, grid, dim3(256), smem, stream, a);
+  FG_LAUNCH_CHECK();
+  return FG_OK;
+}
+
+}  // namespace fg
+
+using namespace fg;
+
+extern "C" int fg_decode_attention_topk(const fg_model_cfg* cfg, const void* q_f16, int64_t q_row_stride, int32_t b,
+                                        int32_t rows, int32_t topk, const fg_kv_cache* kv, int32_t batch_offset,
+                                        void* out_f16, int32_t* kept_rows, void* stream) {
+  if (!cfg || !kv) return FG_ERR_NULL;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  rc = check_kv(cfg, kv);
+  if (rc) return rc;
+  if (kv->dtype != FG_Q4G64) return FG_ERR_UNSUPPORTED;
+  if (b < 0 || rows < 1 || rows > kv->cap || batch_offset < 0 || (int64_t)batch_offset + b > kv->batch)
+    return FG_ERR_SHAPE;
+  if (topk < 1 || topk > rows) return FG_ERR_SHAPE;
+  if (q_row_stride < cfg->h1 || q_row_stride % 8 != 0) return FG_ERR_SHAPE;
+  if (b == 0) return FG_OK;
+  if (!q_f16 || !out_f16) return FG_ERR_NULL;
+  return decode_attention_topk_launch(*cfg, reinterpret_cast<const half_t*>(q_f16), q_row_stride, b, rows, topk, *kv,
+                                      batch_offset, reinterpret_cast<half_t*>(out_f16), kept_rows, as_stream(stream));
+}

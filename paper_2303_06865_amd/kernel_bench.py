@@ -5,6 +5,7 @@ algorithmic bytes / flops per launch.  It exists so that `rocprofv3 --kernel-tra
 
   python3 -m paper_2303_06865_amd.kernel_bench linear --m 144 --n 36864 --k 12288 --wdtype q4t
   python3 -m paper_2303_06865_amd.kernel_bench attn_decode --batch 144 --nh 96 --rows 528
+  python3 -m paper_2303_06865_amd.kernel_bench attn_decode_topk --batch 144 --nh 96 --rows 528 --topk 53
   python3 -m paper_2303_06865_amd.kernel_bench attn_prefill --batch 8 --nh 96 --seq 512
   python3 -m paper_2303_06865_amd.kernel_bench copy --mib 1024      # calibration for HBM counters
 
@@ -46,7 +47,7 @@ def _torch_time(fn, iters, warm):
 
 def main(argv=None):
     ap = argparse.ArgumentParser()
-    ap.add_argument("op", choices=["linear", "attn_decode", "attn_prefill", "copy"])
+    ap.add_argument("op", choices=["linear", "attn_decode", "attn_decode_topk", "attn_prefill", "copy"])
     ap.add_argument("--m", type=int, default=144)
     ap.add_argument("--n", type=int, default=36864)
     ap.add_argument("--k", type=int, default=12288)
@@ -57,6 +58,7 @@ def main(argv=None):
     ap.add_argument("--dh", type=int, default=128)
     ap.add_argument("--rows", type=int, default=528, help="cached positions read by decode attention")
     ap.add_argument("--seq", type=int, default=512)
+    ap.add_argument("--topk", type=int, default=0, help="attn_decode_topk: rows kept (default: ceil(rows / 10))")
     ap.add_argument("--kv", choices=["q4", "f16"], default="q4")
     ap.add_argument("--mib", type=int, default=1024, help="copy: MiB read (and as many written)")
     ap.add_argument("--iters", type=int, default=5)
@@ -74,7 +76,7 @@ def main(argv=None):
         out.update(m=a.m, n=a.n, k=a.k, wdtype=a.wdtype,
                    bytes=int(a.n * a.k * (2 if a.wdtype == "f16" else 0.625)), flops=2 * a.m * a.n * a.k)
         out["classes"] = _time_classes(lambda: B.fg_linear(mat, None, x), a.iters, a.warmup)
-    elif a.op == "attn_decode":
+    elif a.op in ("attn_decode", "attn_decode_topk"):
         h1 = a.nh * a.dh
         cfg = B.Cfg(h1, a.nh, 4 * h1, 50272, 4096)
         q4 = a.kv == "q4"
@@ -88,11 +90,20 @@ def main(argv=None):
             kv.k_codes.normal_()
             kv.v_codes.normal_()
         qkv = torch.randn(a.batch, 3 * h1, device=dev, dtype=torch.float16)
-        out.update(batch=a.batch, nh=a.nh, dh=a.dh, rows=a.rows, kv=a.kv,
-                   bytes=int(2 * a.batch * a.nh * a.rows * a.dh * (0.625 if q4 else 2)),
-                   flops=4 * a.batch * a.nh * a.rows * a.dh)
-        out["classes"] = _time_classes(lambda: B.fg_decode_attention(cfg, qkv, 3 * h1, a.batch, a.rows, kv, 0),
-                                       a.iters, a.warmup)
+        if a.op == "attn_decode_topk":
+            topk = a.topk or -(-a.rows // 10)
+            # K stream in full, topk rows of V
+            out.update(batch=a.batch, nh=a.nh, dh=a.dh, rows=a.rows, topk=topk, kv=a.kv,
+                       bytes=int(a.batch * a.nh * (a.rows + topk) * a.dh * 0.625),
+                       flops=2 * a.batch * a.nh * (a.rows + topk) * a.dh)
+            out["classes"] = _time_classes(
+                lambda: B.fg_decode_attention_topk(cfg, qkv, 3 * h1, a.batch, a.rows, topk, kv, 0), a.iters, a.warmup)
+        else:
+            out.update(batch=a.batch, nh=a.nh, dh=a.dh, rows=a.rows, kv=a.kv,
+                       bytes=int(2 * a.batch * a.nh * a.rows * a.dh * (0.625 if q4 else 2)),
+                       flops=4 * a.batch * a.nh * a.rows * a.dh)
+            out["classes"] = _time_classes(lambda: B.fg_decode_attention(cfg, qkv, 3 * h1, a.batch, a.rows, kv, 0),
+                                           a.iters, a.warmup)
     elif a.op == "attn_prefill":
         h1 = a.nh * a.dh
         cfg = B.Cfg(h1, a.nh, 4 * h1, 50272, 4096)

@@ -102,6 +102,24 @@ def test_layer_argument_errors_need_no_gpu():
     assert gen(0, 9, 1, 4) == B.FG_ERR_SHAPE
 
 
+def test_topk_attention_argument_errors_need_no_gpu():
+    L = B.lib()
+    cfg = _cfg()
+    a = 4096
+    kv = B.fg_kv_cache(a, a, a, a, B.FG_Q4G64, 4, 40, 0)
+    call = lambda rows, topk, kv_=kv, b=4: L.fg_decode_attention_topk(C.byref(cfg), a, 2304, b, rows, topk,
+                                                                      C.byref(kv_), 0, a, None, None)
+    assert call(30, 0) == B.FG_ERR_SHAPE           # keep at least one row
+    assert call(30, 31) == B.FG_ERR_SHAPE          # ... and at most all of them
+    assert call(41, 4) == B.FG_ERR_SHAPE           # more rows than the cache holds
+    assert call(30, 3, b=5) == B.FG_ERR_SHAPE
+    f16 = B.fg_kv_cache(a, None, a, None, B.FG_F16, 4, 40, 0)
+    assert call(30, 3, f16) == B.FG_ERR_UNSUPPORTED
+    big = B.fg_kv_cache(a, a, a, a, B.FG_Q4G64, 4, 40000, 0)
+    assert call(36800, 100, big) == B.FG_ERR_UNSUPPORTED   # scores of one head no longer fit on chip
+    assert call(30, 3, b=0) == B.FG_OK
+
+
 def test_workspace_queries_are_pure_host_functions():
     L = B.lib()
     cfg = _cfg()

@@ -257,6 +257,79 @@ def test_decode_attention_peaked_softmax(quant):
     assert_close(got, ref, "peaked softmax")
 
 
+# ------------------------------------------------------------------ Top-K sparse decode attention
+def _topk_case(nh, dh, rows, topk, seed, b=3, batch=4, boff=1, dup_rows=False):
+    h1 = nh * dh
+    cfg = B.Cfg(h1, nh, 4 * h1, 1000, 4096)
+    cap = rows + 3
+    k16 = _rand16((batch, rows, h1), 1.0, seed)
+    if dup_rows:   # every cached key row identical: all scores tie exactly
+        k16[:] = k16[:, :1]
+    v16 = _rand16((batch, rows, h1), 1.0, seed + 1)
+    q16 = _rand16((b, 3 * h1), 1.0, seed + 2)
+    okv = O.KVCache.empty(batch, nh, cap, dh, True)
+    okv.store(0, 0, k16, v16)
+    kv = B.KVCache(cfg, batch, cap, True)
+    kv.k_codes.copy_(dev(okv.k_codes)); kv.v_codes.copy_(dev(okv.v_codes))
+    kv.k_meta.copy_(dev(okv.k_meta)); kv.v_meta.copy_(dev(okv.v_meta))
+    out, kept = B.fg_decode_attention_topk(cfg, dev(q16), 3 * h1, b, rows, topk, kv, boff, want_rows=True)
+    torch.cuda.synchronize()
+    out, kept = host(out), host(kept)
+    ref = np.empty((b, nh, dh))
+    exact = 0
+    for i in range(b):
+        for h in range(nh):
+            kh, vh = okv.load(boff + i, h, rows)
+            qv = q16[i, h * dh:(h + 1) * dh].astype(np.float64)
+            sc = O.attn_decode_scores(qv, kh)
+            got = kept[i, h]
+            # a valid index set: ascending, distinct, in range
+            assert np.all(np.diff(got) > 0) and got[0] >= 0 and got[-1] < rows
+            # ... that is a top-k set of the oracle's scores up to the kernel's FP32 score error
+            srt = np.sort(sc)[::-1]
+            thr = srt[topk - 1]
+            eps = 2e-5 * (1.0 + np.abs(sc).max())
+            mask = np.zeros(rows, bool)
+            mask[got] = True
+            assert sc[mask].min() >= thr - eps and (topk == rows or sc[~mask].max() <= thr + eps)
+            # where the k-th and (k+1)-th scores are clearly apart the set is THE top-k set
+            if topk == rows or srt[topk - 1] - srt[topk] > 2 * eps:
+                assert np.array_equal(got, O.topk_indices(sc, topk))
+                exact += 1
+            ref[i, h] = O.attn_decode_subset(qv, kh, vh, got.astype(np.int64))
+    return out, O.round_f16(ref.reshape(b, h1)), kept, exact
+
+
+@pytest.mark.parametrize("nh,dh", [(2, 128), (3, 64)])
+@pytest.mark.parametrize("rows,topk", [(1, 1), (5, 2), (64, 7), (65, 65), (129, 13), (200, 20), (528, 53),
+                                       (528, 1), (1100, 110), (2100, 210)])
+def test_decode_attention_topk(rows, topk, nh, dh):
+    out, ref, _, exact = _topk_case(nh, dh, rows, topk, seed=rows + topk)
+    assert exact > 0   # random scores: at least one head must have had an unambiguous boundary
+    assert_close(out, ref, "top-k attention rows=%d k=%d dh=%d" % (rows, topk, dh))
+
+
+@pytest.mark.parametrize("nh,dh", [(2, 128), (3, 64)])
+def test_decode_attention_topk_ties_keep_lowest_rows(nh, dh):
+    out, ref, kept, _ = _topk_case(nh, dh, 300, 37, seed=5, dup_rows=True)
+    assert np.array_equal(kept, np.broadcast_to(np.arange(37, dtype=np.int32), kept.shape))
+    assert_close(out, ref, "top-k attention, all scores tied")
+
+
+def test_decode_attention_topk_full_k_equals_dense():
+    """Keeping every row must reproduce the dense kernel's result (same cache, same query)."""
+    nh, dh, rows = 2, 128, 333
+    h1 = nh * dh
+    cfg = B.Cfg(h1, nh, 4 * h1, 1000, 4096)
+    kv = B.KVCache(cfg, 2, rows + 1, True)
+    k16 = dev(_rand16((2 * rows, h1), 1.0, 1)); v16 = dev(_rand16((2 * rows, h1), 1.0, 2))
+    B.fg_kv_append(cfg, k16, v16, h1, 2, rows, kv, 0, 0)
+    q = dev(_rand16((2, 3 * h1), 1.0, 3))
+    dense = host(B.fg_decode_attention(cfg, q, 3 * h1, 2, rows, kv, 0))
+    sparse = host(B.fg_decode_attention_topk(cfg, q, 3 * h1, 2, rows, rows, kv, 0))
+    assert_close(sparse, dense.astype(np.float64), "top-k with k = rows vs dense", rel=1e-3, mabs=2e-3)
+
+
 # ------------------------------------------------------------------ prefill attention
 @pytest.mark.parametrize("nh,dh", [(2, 128), (3, 64)])
 @pytest.mark.parametrize("b,s", [(1, 1), (2, 7), (1, 64), (2, 65), (1, 100), (1, 200), (3, 32)])
