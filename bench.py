@@ -28,6 +28,9 @@ MFMA_F16_PEAK = 2.5e15     # flop/s, dense FP16 MFMA
 WORKLOADS = {
     # name: (shape name, quantized weights, quantized kv, num_gpu_batches, gpu_batch_size, s, n)
     "opt175b_q4": ("OPT_175B", True, True, 4, 36, 512, 32),
+    # schedule ablation (Section 4.2): ONE GPU batch of the 175B block per pass over the layers, i.e. what
+    # the row-by-row order costs: every 36 sequences stream all weights again
+    "opt175b_q4_1x36": ("OPT_175B", True, True, 1, 36, 512, 32),
     "opt30b_q4": ("OPT_30B", True, True, 8, 32, 512, 32),
     "opt6.7b_f16": ("OPT_6_7B", False, False, 4, 32, 512, 32),
     "opt125m_layer_q4": ("OPT_125M_LAYER", True, True, 1, 4, 32, 9),
