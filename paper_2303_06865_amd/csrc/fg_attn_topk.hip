@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
   __shared__ __attribute__((aligned(16))) half_t sm_q[DH];
   __shared__ int s_hist[256];
   __shared__ int s_wave[4];
-  __shared__ float s_red[4];
+  __shared__ float s_red[8];
   __shared__ uint32_t s_prefix;
   __shared__ int s_need;
   __shared__ float s_o[4 * DH];
@@ -116,10 +116,21 @@ __global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
   QueryOps<DH> Q;
   query_setup<DH>(sm_q, lane, Q);
 
-  // ---- phase 1: scores of all rows -> LDS (rows past the end hold -inf)
+  // ---- phase 1: scores of all rows -> LDS (rows past the end hold -inf), with each wave's running
+  // maximum and sum of exponentials (merged below into the softmax denominator)
+  float m_run = -INFINITY, l_run = 0.f;
   auto scores = [&](const Buf& b, int chunk) {
     float sc[NS];
     chunk_scores<DH>(b.kq, b.km0, b.km1, Q, a.scale, G, chunk << 7, lane, sc);
+    float cmax = sc[0];
+    if (NS == 2) cmax = fmaxf(cmax, sc[NS - 1]);
+    cmax = wave_max(cmax);              // a processed chunk has at least one valid row
+    if (cmax > m_run) {                 // wave-uniform
+      l_run *= fast_exp2((m_run - cmax) * kLog2e);
+      m_run = cmax;
+    }
+    l_run += fast_exp2((sc[0] - m_run) * kLog2e);
+    if (NS == 2) l_run += fast_exp2((sc[NS - 1] - m_run) * kLog2e);
     if (DH == 128) {
       s_sc[chunk * RPC + lane] = sc[0];
     } else {
@@ -138,22 +149,19 @@ __global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
       scores(b1, chunk + 4);
     }
   }
-  __syncthreads();
-
-  // ---- maximum and softmax denominator over all rows
-  float mx = -INFINITY;
-  for (int i = tid; i < n; i += 256) mx = fmaxf(mx, s_sc[i]);
-  mx = wave_max(mx);
-  if (lane == 0) s_red[wave] = mx;
+  // ---- maximum and softmax denominator over all rows: log-sum-exp merge of the four waves
+  l_run = wave_sum(l_run);
+  if (lane == 0) {
+    s_red[wave] = m_run;
+    s_red[4 + wave] = l_run;
+  }
   __syncthreads();
   const float M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
   float den = 0.f;
-  for (int i = tid; i < n; i += 256) den += fast_exp2((s_sc[i] - M) * kLog2e);
-  den = wave_sum(den);
-  __syncthreads();
-  if (lane == 0) s_red[wave] = den;
-  __syncthreads();
-  const float inv_den = 1.0f / (s_red[0] + s_red[1] + s_red[2] + s_red[3]);
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+    if (s_red[w] != -INFINITY) den += s_red[4 + w] * fast_exp2((s_red[w] - M) * kLog2e);
+  const float inv_den = 1.0f / den;
 
   // ---- phase 2: radix select of the topk-th largest key, most significant byte first
   if (tid == 0) {
