@@ -142,9 +142,12 @@ int fg_layernorm(const void* x_f16, const void* gamma_f16, const void* beta_f16,
 
 /* out[m, w.rows] = act(x[m, w.cols] . W^T + bias) + residual   (Section 3: x . w)
  * x, residual (nullable), out are FP16 row-major; bias FP16 (nullable); relu != 0 applies
- * max(.,0) before the residual is added.  FG_Q4G64 weights are dequantized inside the kernel
- * (never materialised in HBM).  w.cols % 64 == 0; w.rows % 8 == 0; m >= 0.
- * ws must hold fg_linear_workspace_bytes(&w, m) bytes (may be 0 => ws may be NULL). */
+ * max(.,0) before the residual is added.  4-bit weights (FG_Q4G64, FG_Q4G64_TILED) are dequantized
+ * inside the kernel (never materialised in HBM); the tiled form is the fast one.
+ * w.cols % 64 == 0; w.rows % 8 == 0 (% 32 for the tiled form); m >= 0.
+ * ws must hold fg_linear_workspace_bytes(&w, m) bytes (may be 0 => ws may be NULL): the kernels
+ * that split the contraction over workgroups keep their partial sums there and add them in a
+ * fixed order, so results do not depend on scheduling.  One ws serves one call at a time. */
 int fg_linear(const fg_mat* w, const void* bias_f16, const void* x_f16, int64_t m,
               const void* residual_f16, int relu, void* out_f16, void* ws, size_t ws_bytes,
               void* stream);
@@ -233,7 +236,11 @@ size_t fg_workspace_bytes(const fg_model_cfg* cfg, const fg_layer_weights* layer
 /* ---- Per-kernel timing (HIP events on the caller's stream) -----------------------------
  * Between fg_profile_begin and fg_profile_end every kernel launch of the library is bracketed
  * by two events.  fg_profile_end synchronises and accumulates, per kernel class, the summed
- * GPU time and the number of launches; fg_profile_read returns them.  Global, not thread-safe. */
+ * GPU time and the number of launches; fg_profile_read returns them.  Global, not thread-safe.
+ * Classes: GEMM_SMALL_M = projections in the decode shape (up to 320 rows on tiled 4-bit or FP16
+ * weights, up to 512 otherwise) and GEMM_SMALL_M_FINISH their partial-sum reduction pass;
+ * GEMM_LARGE_M = projections in the prefill shape (reduction pass included);
+ * ATTN_DECODE covers the dense and the Top-K decode attention. */
 typedef enum {
   FG_K_QUANTIZE = 0, FG_K_DEQUANTIZE, FG_K_LAYERNORM, FG_K_GEMM_SMALL_M, FG_K_GEMM_SMALL_M_FINISH,
   FG_K_GEMM_LARGE_M, FG_K_KV_APPEND, FG_K_ATTN_DECODE, FG_K_ATTN_PREFILL, FG_K_EMBED, FG_K_ARGMAX,

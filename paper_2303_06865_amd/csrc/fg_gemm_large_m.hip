@@ -1,5 +1,6 @@
 // Fused dequant + MFMA GEMM for the prefill-phase projections (Section 3, prefill: x.wQ, x.wK,
-// x.wV, .wO, .w1, .w2 over b*s rows, weights stored as in Section 5).
+// x.wV, .wO, .w1, .w2 over b*s rows, weights stored as in Section 5), for FP16 weights and for 4-bit
+// weights in the canonical row-major format.  Tiled 4-bit weights take fg_gemm_stream.hip instead.
 //
 // out[M, N] = act(x[M, K] . W[N, K]^T + bias) + residual,  M large (thousands of rows)
 //

@@ -1,6 +1,9 @@
 // Fused dequant + GEMM for the decode-phase projections (Section 3: t.wQ, t.wK, t.wV, .wO, .w1, .w2
 // with the weights stored as in Section 5), for a small number of activation rows M (the block
-// of sequences in a decode step).
+// of sequences in a decode step), on weights in the CANONICAL row-major 4-bit format, and on FP16
+// weights whose shape the streaming kernels do not take (N % 32 != 0, or 320 < M <= 512).  Tiled
+// 4-bit weights and the common FP16 cases go through fg_gemm_stream.hip, which is faster: in the
+// canonical format the 32 bytes a lane pair needs per K step lie K/2 bytes apart from row to row.
 //
 // out[M, N] = act(x[M, K] . W[N, K]^T + bias) + residual
 //
