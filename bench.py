@@ -31,6 +31,10 @@ WORKLOADS = {
     # schedule ablation (Section 4.2): ONE GPU batch of the 175B block per pass over the layers, i.e. what
     # the row-by-row order costs: every 36 sequences stream all weights again
     "opt175b_q4_1x36": ("OPT_175B", True, True, 1, 36, 512, 32),
+    # other prompt/generation lengths of the paper's evaluation (Section 6 and its appendix tables)
+    "opt175b_q4_1024_32": ("OPT_175B", True, True, 4, 20, 1024, 32),
+    "opt175b_q4_128_128": ("OPT_175B", True, True, 4, 36, 128, 128),
+    "opt175b_q4_512_8": ("OPT_175B", True, True, 4, 36, 512, 8),
     "opt30b_q4": ("OPT_30B", True, True, 8, 32, 512, 32),
     "opt6.7b_f16": ("OPT_6_7B", False, False, 4, 32, 512, 32),
     "opt125m_layer_q4": ("OPT_125M_LAYER", True, True, 1, 4, 32, 9),
