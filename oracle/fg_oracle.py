@@ -80,6 +80,46 @@ def quantize_groupwise(x16: np.ndarray, group: int = GROUP, bits: int = BITS):
     return pack_codes(codes.reshape(rows, cols)), meta
 
 
+def quantize_groupwise_h16(x16: np.ndarray, group: int = GROUP, bits: int = BITS):
+    """The 4.5-bit variant of Section 5's format: the pair (min, scale) is stored as two FP16 numbers
+    (4 bytes per group of 64 instead of 8).
+
+    Reading taken (the paper does not describe a storage precision for the pair): the inputs are
+    FP16, so min is stored exactly; scale is the SMALLEST FP16 number >= (max-min)/15 (binary32
+    quotient rounded up), so that every code round((x-min)/scale) still lies in [0, 15] without
+    clamping and every element is within scale/2 of its reconstruction; the maximum no longer
+    round-trips exactly.  Codes are computed in binary32 with that stored scale.
+
+    Returns (codes uint8 [rows, cols/2], meta float16 [rows, cols/group, 2])."""
+    if group != GROUP or bits != BITS:
+        raise ValueError("only group=64, bits=4 is defined")
+    x16 = np.asarray(x16)
+    if x16.dtype != np.float16 or x16.ndim != 2:
+        raise ValueError("expects a 2-D float16 array")
+    rows, cols = x16.shape
+    if cols % group != 0:
+        raise ValueError("cols must be a multiple of the group size")
+    if not np.all(np.isfinite(x16)):
+        raise ValueError("non-finite input")
+    ng = cols // group
+    x = x16.astype(np.float32).reshape(rows, ng, group)
+    mn = x.min(axis=2)
+    mx = x.max(axis=2)
+    q = ((mx - mn).astype(np.float32) / np.float32(QMAX)).astype(np.float32)
+    s16 = q.astype(np.float16)                                  # nearest FP16 ...
+    low = s16.astype(np.float32) < q                            # ... stepped up where it fell below
+    s16 = np.where(low, np.nextafter(s16, np.float16(np.inf)), s16).astype(np.float16)
+    scale = s16.astype(np.float32)
+    codes = np.zeros((rows, ng, group), dtype=np.uint8)
+    nz = scale > 0
+    if np.any(nz):
+        num = (x[nz] - mn[nz][:, None]).astype(np.float32)
+        t = (num / scale[nz][:, None]).astype(np.float32)
+        codes[nz] = np.clip(np.rint(t), 0, QMAX).astype(np.uint8)
+    meta = np.stack([mn.astype(np.float16), s16], axis=-1)
+    return pack_codes(codes.reshape(rows, cols)), meta
+
+
 def pack_codes(c: np.ndarray) -> np.ndarray:
     """Two 4-bit codes per byte, even element in the low nibble."""
     c = np.asarray(c, dtype=np.uint8)
@@ -281,6 +321,7 @@ class KVCache:
     cap: int
     dh: int
     quantized: bool
+    meta_f16: bool = False      # quantized only: (min, scale) stored as FP16 (quantize_groupwise_h16)
     k_codes: np.ndarray = field(default=None)
     k_meta: np.ndarray = field(default=None)
     v_codes: np.ndarray = field(default=None)
@@ -289,14 +330,15 @@ class KVCache:
     v_f16: np.ndarray = field(default=None)
 
     @staticmethod
-    def empty(batch: int, nh: int, cap: int, dh: int, quantized: bool) -> "KVCache":
-        c = KVCache(batch, nh, cap, dh, quantized)
+    def empty(batch: int, nh: int, cap: int, dh: int, quantized: bool, meta_f16: bool = False) -> "KVCache":
+        c = KVCache(batch, nh, cap, dh, quantized, meta_f16 and quantized)
         if quantized:
             assert dh % GROUP == 0
+            mt = np.float16 if meta_f16 else np.float32
             c.k_codes = np.zeros((batch, nh, cap, dh // 2), np.uint8)
             c.v_codes = np.zeros((batch, nh, cap, dh // 2), np.uint8)
-            c.k_meta = np.zeros((batch, nh, cap, dh // GROUP, 2), np.float32)
-            c.v_meta = np.zeros((batch, nh, cap, dh // GROUP, 2), np.float32)
+            c.k_meta = np.zeros((batch, nh, cap, dh // GROUP, 2), mt)
+            c.v_meta = np.zeros((batch, nh, cap, dh // GROUP, 2), mt)
         else:
             c.k_f16 = np.zeros((batch, nh, cap, dh), np.float16)
             c.v_f16 = np.zeros((batch, nh, cap, dh), np.float16)
@@ -311,7 +353,8 @@ class KVCache:
         for name, x16 in (("k", k16), ("v", v16)):
             x16 = np.ascontiguousarray(x16, np.float16)
             if self.quantized:
-                codes, meta = quantize_groupwise(x16.reshape(nb * npos, h1))
+                quant = quantize_groupwise_h16 if self.meta_f16 else quantize_groupwise
+                codes, meta = quant(x16.reshape(nb * npos, h1))
                 codes = codes.reshape(nb, npos, self.nh, self.dh // 2).transpose(0, 2, 1, 3)
                 meta = meta.reshape(nb, npos, self.nh, self.dh // GROUP, 2).transpose(0, 2, 1, 3, 4)
                 getattr(self, name + "_codes")[b0:b0 + nb, :, pos0:pos0 + npos] = codes

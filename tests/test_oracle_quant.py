@@ -216,3 +216,68 @@ def test_tiled_order_is_the_documented_permutation():
                 dst = (tile * 64 + 32 * h + row % 32) * 16
                 assert np.array_equal(flat[dst:dst + 16], src)
     assert sorted(flat.tolist()) == sorted(codes.reshape(-1).tolist())
+
+
+# ---------------------------------------------------------------- FP16 (min, scale) variant
+@pytest.mark.parametrize("std,seed", [(1.0, 1), (0.02, 2), (30.0, 3), (1e-4, 4)])
+def test_h16_variant_invariants(std, seed):
+    """4.5-bit variant: min is stored exactly, scale is the smallest FP16 not below (max-min)/15, codes
+    need no clamping, and every element stays within half a (stored) step of its reconstruction."""
+    x = _rand16((37, 256), std, seed)
+    codes, meta = O.quantize_groupwise_h16(x)
+    assert meta.dtype == np.float16 and meta.shape == (37, 4, 2)
+    xg = x.astype(np.float64).reshape(37, 4, 64)
+    mn, sc = meta[..., 0].astype(np.float64), meta[..., 1].astype(np.float64)
+    assert np.array_equal(mn, xg.min(axis=2))                       # FP16 inputs: min round-trips exactly
+    want = (xg.max(axis=2).astype(np.float32) - xg.min(axis=2).astype(np.float32)) / np.float32(15)
+    assert np.all(sc >= want)                                       # ... scale is rounded UP
+    below = np.nextafter(meta[..., 1], np.float16(-np.inf)).astype(np.float64)
+    assert np.all((below < want) | (sc == 0))                       # ... and is the smallest such FP16
+    c = O.unpack_codes(codes).reshape(37, 4, 64).astype(np.float64)
+    assert c.min() >= 0 and c.max() <= 15
+    # unclamped rounding already lands in [0, 15]: nothing was clipped
+    t = (xg - mn[..., None]) / np.where(sc > 0, sc, 1.0)[..., None]
+    assert np.all(np.rint(t) <= 15)
+    xh = O.dequantize_groupwise(codes, meta).astype(np.float64).reshape(37, 4, 64)
+    assert np.all(np.abs(xh - xg) <= sc[..., None] * (0.5 + 1e-6) + 1e-12)
+    # the group's minimum element reconstructs exactly, the maximum within half a step
+    assert np.all(np.take_along_axis(xh, xg.argmin(axis=2)[..., None], 2)[..., 0] == xg.min(axis=2))
+
+
+def test_h16_variant_agrees_with_the_binary32_format_when_scale_is_representable():
+    """Ranges 15 * 2^k make (max-min)/15 an FP16 number: both formats then store the same codes."""
+    rng = np.random.default_rng(9)
+    x = rng.integers(0, 16, size=(6, 128)).astype(np.float16) * np.float16(0.25) - np.float16(1.5)
+    x[:, 0] = -1.5
+    x[:, 1] = 2.25            # range 3.75 = 15 * 0.25 in both groups?  (second group gets its own extremes)
+    x[:, 64] = -1.5
+    x[:, 65] = 2.25
+    c32, m32 = O.quantize_groupwise(x)
+    c16, m16 = O.quantize_groupwise_h16(x)
+    assert np.array_equal(c32, c16)
+    assert np.array_equal(m32, m16.astype(np.float32))
+    assert np.array_equal(O.dequantize_groupwise(c16, m16), x.astype(np.float32))
+
+
+def test_h16_variant_bruteforce_and_constant_group():
+    x = _rand16((3, 64), 1.0, 12)
+    codes, meta = O.quantize_groupwise_h16(x)
+    c = O.unpack_codes(codes)
+    for r in range(3):
+        mn, sc = float(meta[r, 0, 0]), float(meta[r, 0, 1])
+        for j in range(64):
+            errs = [abs(mn + k * sc - float(x[r, j])) for k in range(16)]
+            assert errs[c[r, j]] <= min(errs) + 1e-7     # the chosen level is a nearest one
+    z = np.full((2, 64), 0.75, np.float16)
+    cz, mz = O.quantize_groupwise_h16(z)
+    assert not cz.any() and np.all(mz[..., 0] == np.float16(0.75)) and not mz[..., 1].any()
+
+
+def test_kv_cache_h16_variant_stores_half_size_pairs():
+    x = _rand16((2, 3, 128), 1.0, 5)
+    a = O.KVCache.empty(2, 2, 4, 64, True, meta_f16=True)
+    a.store(0, 1, x, x)
+    assert a.k_meta.dtype == np.float16 and a.k_meta.nbytes * 2 == O.KVCache.empty(2, 2, 4, 64, True).k_meta.nbytes
+    kh, _ = a.load(1, 1, 4)
+    c, m = O.quantize_groupwise_h16(x[1, :, 64:128])
+    assert np.array_equal(kh[1:4], O.dequantize_groupwise(c, m).astype(np.float64))
