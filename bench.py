@@ -35,6 +35,9 @@ WORKLOADS = {
     "opt175b_q4_1024_32": ("OPT_175B", True, True, 4, 20, 1024, 32),
     "opt175b_q4_128_128": ("OPT_175B", True, True, 4, 36, 128, 128),
     "opt175b_q4_512_8": ("OPT_175B", True, True, 4, 36, 512, 8),
+    # the 4.5-bit cache variant: FP16 {min, scale} pairs (10 % fewer KV bytes per step)
+    "opt175b_q4_h16kv": ("OPT_175B", True, "h16", 4, 36, 512, 32),
+    "kv_stress_175b_layer_h16kv": ("OPT_175B", True, "h16", 1, 512, 2048, 64),
     "opt30b_q4": ("OPT_30B", True, True, 8, 32, 512, 32),
     "opt6.7b_f16": ("OPT_6_7B", False, False, 4, 32, 512, 32),
     "opt125m_layer_q4": ("OPT_125M_LAYER", True, True, 1, 4, 32, 9),
@@ -45,7 +48,8 @@ WORKLOADS = {
 
 
 def bpe(q):
-    return 0.625 if q else 2.0
+    """Stored bytes per element: FP16, 4-bit with binary32 pairs, or ("h16") 4-bit with FP16 pairs."""
+    return 0.5625 if q == "h16" else (0.625 if q else 2.0)
 
 
 def build_model(sh, wq, seed, torch, B, embeddings=True):
@@ -93,7 +97,7 @@ def cpu_baseline(sh, wq, kvq, s, n, budget_s=25.0):
     f16 = lambda shape, std: (rng.standard_normal(shape, dtype=np.float32) * np.float32(std)).astype(np.float16)
     slabs = {"wqkv": (3 * h1, h1), "wo": (h1, h1), "w1": (h2, h1), "w2": (h1, h2)}
     mats = {k: O.Mat.from_f16(f16((min(slab, r), c), 0.02), wq) for k, (r, c) in slabs.items()}
-    kv = O.KVCache.empty(b, nh, rows + 1, dh, kvq)
+    kv = O.KVCache.empty(b, nh, rows + 1, dh, bool(kvq), kvq == "h16")
     kv.store(0, 0, f16((b, rows, h1), 1.0), f16((b, rows, h1), 1.0))
     x = f16((b, h1), 1.0)
     a = f16((b, h2), 1.0)
@@ -138,7 +142,7 @@ def run_kv_stress(args, torch, B, synth):
     cfg = B.Cfg(sh.h1, sh.nh, sh.h2, sh.vocab, max(sh.max_pos, ctx + n), sh.ln_eps)
     layers, _, _, _, _ = build_model(sh, wq, args.seed, torch, B, embeddings=False)
     w = layers[0]
-    kv = B.KVCache(cfg, b, ctx + n, kvq, zero=False)
+    kv = B.KVCache(cfg, b, ctx + n, bool(kvq), zero=False, meta_f16=kvq == "h16")
     g = torch.Generator(device="cuda")
     g.manual_seed(args.seed * 1000003 + 77)
     chunk = 256   # rows per fill call: 512 x 256 x 12288 FP16 = 3.2 GB of K and of V at a time
@@ -191,7 +195,7 @@ def run_kv_stress(args, torch, B, synth):
         "ms_per_step": 1e3 * elapsed / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": args.workload, "shape": {"l": 1, "h1": sh.h1, "nh": sh.nh, "h2": sh.h2},
-                   "weights": "q4g64", "kv_cache": "q4g64", "block": "1x%d" % b, "context": ctx, "decode_steps": n},
+                   "weights": "q4g64", "kv_cache": "q4g64_h16" if kvq == "h16" else "q4g64", "block": "1x%d" % b, "context": ctx, "decode_steps": n},
         "decode": {"ms_per_layer_step": 1e3 * elapsed / K / n,
                    "hbm_frac_avg": (kv_bytes + n * P * bpe(wq)) / (elapsed / K) / HBM_PEAK},
         "roofline": dict(rl[dominant], kernel=dominant), "roofline_kernels": rl,
@@ -236,7 +240,7 @@ def main():
     t_setup = time.time()
     layers, emb, pos, lnf_g, lnf_b = build_model(sh, wq, args.seed, torch, B)
     cap = s + n
-    kv = [B.KVCache(cfg, bls, cap, kvq, zero=False) for _ in range(sh.l)]
+    kv = [B.KVCache(cfg, bls, cap, bool(kvq), zero=False, meta_f16=kvq == "h16") for _ in range(sh.l)]
     ws = torch.empty(B.fg_workspace_bytes(cfg, layers[0], gbs, ngb, s), dtype=torch.uint8, device="cuda")
     out_ids = torch.zeros((bls, n), dtype=torch.int32, device="cuda")
     prompt = torch.from_numpy(synth.prompt_ids(bls, s, sh.vocab, args.seed)).cuda()
@@ -334,7 +338,7 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": args.workload + ("" if not args.layers else "_%dlayers" % args.layers),
                    "shape": {"l": sh.l, "h1": sh.h1, "nh": sh.nh, "h2": sh.h2, "vocab": sh.vocab},
-                   "weights": "q4g64" if wq else "f16", "kv_cache": "q4g64" if kvq else "f16",
+                   "weights": "q4g64" if wq else "f16", "kv_cache": "q4g64_h16" if kvq == "h16" else ("q4g64" if kvq else "f16"),
                    "block": "%dx%d" % (ngb, gbs), "prompt_len": s, "gen_len": n,
                    "resident_gb": resident / 1e9, "setup_s": t_setup},
         "prefill_s": prefill_s, "decode_s": decode_s, "decode": decode,

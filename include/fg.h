@@ -33,6 +33,12 @@
  *             per (row r, half h of the group) at offset 16*(32*h + r); tiles of one row block
  *             follow each other along the input dimension, row blocks follow each other; meta has
  *             32 pairs per tile in the same tile order.  Same size as FG_Q4G64.
+ *   FG_Q4G64_H16  (KV caches only) the 4.5-bit variant: as FG_Q4G64, but the pair is stored as two
+ *             FP16 numbers {min, scale}, 4 bytes per group.  min is stored exactly (the inputs are
+ *             FP16); scale is the smallest FP16 number >= (max-min)/15, and the codes are computed
+ *             with that stored scale, so they lie in [0, 15] without clamping and every element is
+ *             within scale/2 of min + code*scale; the maximum no longer round-trips exactly.
+ *             0.5625 bytes per element.
  */
 #ifndef FG_H
 #define FG_H
@@ -53,7 +59,7 @@ typedef enum {
   FG_ERR_DEVICE = -5       /* a HIP runtime call failed (see fg_last_device_error) */
 } fg_status;
 
-typedef enum { FG_F16 = 0, FG_Q4G64 = 1, FG_Q4G64_TILED = 2 } fg_dtype;
+typedef enum { FG_F16 = 0, FG_Q4G64 = 1, FG_Q4G64_TILED = 2, FG_Q4G64_H16 = 3 } fg_dtype;
 
 /* A weight matrix [rows = output features, cols = input features], row-major.
  * FG_F16:   data = FP16 values, meta = NULL.
@@ -89,6 +95,7 @@ typedef struct {
  * FG_Q4G64: k_codes/v_codes hold dh/2 bytes per (sequence, head, row); k_meta/v_meta hold
  *           dh/64 {min,scale} pairs per (sequence, head, row).  Groups run along the hidden
  *           dimension of a token row (Section 5), so no group straddles a head.
+ * FG_Q4G64_H16: the same with 4-byte FP16 pairs in k_meta/v_meta.
  * FG_F16:   k_codes/v_codes hold dh FP16 values per (sequence, head, row); metas are NULL. */
 typedef struct {
   void *k_codes, *k_meta, *v_codes, *v_meta;
@@ -123,6 +130,10 @@ int fg_version(void);
  * binary32 arithmetic, IEEE division, no fused multiply-add. */
 int fg_quantize_groupwise(const void* x_f16, int64_t rows, int64_t cols, int group, int bits,
                           void* codes_out, void* meta_out, void* stream);
+/* The same quantizer for the FG_Q4G64_H16 variant (see "Storage formats"): meta_out_f16 receives
+ * rows*cols/64 pairs of FP16 {min, scale}. */
+int fg_quantize_groupwise_h16(const void* x_f16, int64_t rows, int64_t cols, int group, int bits,
+                              void* codes_out, void* meta_out_f16, void* stream);
 
 /* Reorder a canonical FG_Q4G64 matrix into FG_Q4G64_TILED (same byte counts: rows*cols/2 and
  * rows*cols/64*8).  src->rows % 32 == 0.  Done once per weight matrix, e.g. at load time. */
@@ -132,6 +143,8 @@ int fg_pack_weights(const fg_mat* src, void* data_out, void* meta_out, void* str
  * min + code*scale rounded once to binary32 (a fused multiply-add). */
 int fg_dequantize_groupwise(const void* codes, const void* meta, int64_t rows, int64_t cols,
                             void* out_f32, void* stream);
+int fg_dequantize_groupwise_h16(const void* codes, const void* meta_f16, int64_t rows, int64_t cols,
+                                void* out_f32, void* stream);
 
 /* ---- Section 3 pieces, exported so each can be checked on its own ---------------------- */
 
@@ -156,8 +169,8 @@ size_t fg_linear_workspace_bytes(const fg_mat* w, int64_t m);
 /* Store K and V token rows into a layer's cache (Section 3 "Concat", Section 5 storage):
  * k, v are FP16 [b, s, h1] views whose consecutive rows are row_stride elements apart
  * (so they may be column slices of a [b*s, 3*h1] QKV buffer).  Rows land at cache rows
- * pos0 .. pos0+s-1 of sequences batch_offset .. batch_offset+b-1; with FG_Q4G64 every
- * 64-element group of a row is quantized exactly as fg_quantize_groupwise does. */
+ * pos0 .. pos0+s-1 of sequences batch_offset .. batch_offset+b-1; with FG_Q4G64 (FG_Q4G64_H16) every
+ * 64-element group of a row is quantized exactly as fg_quantize_groupwise (_h16) does. */
 int fg_kv_append(const fg_model_cfg* cfg, const void* k_f16, const void* v_f16, int64_t row_stride,
                  int32_t b, int32_t s, const fg_kv_cache* kv, int32_t batch_offset, int32_t pos0,
                  void* stream);
@@ -170,7 +183,7 @@ int fg_decode_attention(const fg_model_cfg* cfg, const void* q_f16, int64_t q_ro
                         int32_t rows, const fg_kv_cache* kv, int32_t batch_offset, void* out_f16,
                         void* stream);
 
-/* Top-K sparse variant of fg_decode_attention (Section 5, sparse attention), FG_Q4G64 caches only
+/* Top-K sparse variant of fg_decode_attention (Section 5, sparse attention), 4-bit caches only
  * (FG_ERR_UNSUPPORTED otherwise): the attention weights are those of the full softmax over rows
  * 0 .. rows-1; only the topk highest-weighted rows of V are read and summed with those weights (no
  * renormalisation); among equal scores the lowest row index is kept.  1 <= topk <= rows

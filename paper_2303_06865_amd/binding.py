@@ -14,7 +14,7 @@ import torch
 
 FG_OK = 0
 FG_ERR_NULL, FG_ERR_SHAPE, FG_ERR_UNSUPPORTED, FG_ERR_WORKSPACE, FG_ERR_DEVICE = -1, -2, -3, -4, -5
-FG_F16, FG_Q4G64, FG_Q4G64_TILED = 0, 1, 2
+FG_F16, FG_Q4G64, FG_Q4G64_TILED, FG_Q4G64_H16 = 0, 1, 2, 3
 KERNEL_CLASSES = ["quantize", "dequantize", "layernorm", "gemm_small_m", "gemm_small_m_finish", "gemm_large_m",
                   "kv_append", "attn_decode", "attn_prefill", "embed", "argmax"]
 
@@ -55,8 +55,11 @@ EXPORTS = {
     "fg_version": (C.c_int, []),
     "fg_quantize_groupwise": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                         C.c_void_p]),
+    "fg_quantize_groupwise_h16": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_void_p,
+                                            C.c_void_p, C.c_void_p]),
     "fg_pack_weights": (C.c_int, [C.POINTER(fg_mat), C.c_void_p, C.c_void_p, C.c_void_p]),
     "fg_dequantize_groupwise": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
+    "fg_dequantize_groupwise_h16": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p]),
     "fg_layernorm": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_float, C.c_void_p,
                                C.c_void_p]),
     "fg_linear": (C.c_int, [C.POINTER(fg_mat), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_void_p,
@@ -205,26 +208,30 @@ class LayerWeights:
 class KVCache:
     """One layer's cache, logical layout [batch, nh, cap, dh]."""
 
-    def __init__(self, cfg: Cfg, batch: int, cap: int, quantized: bool, device="cuda", zero: bool = True):
+    def __init__(self, cfg: Cfg, batch: int, cap: int, quantized: bool, device="cuda", zero: bool = True,
+                 meta_f16: bool = False):
+        """quantized: 4-bit storage; meta_f16 (quantized only): FP16 {min, scale} pairs (FG_Q4G64_H16)."""
         self.batch, self.cap, self.quantized = batch, cap, quantized
+        self.meta_f16 = bool(meta_f16 and quantized)
         mk = torch.zeros if zero else torch.empty
         nh, dh = cfg.nh, cfg.dh
         if quantized:
             self.k_codes = mk((batch, nh, cap, dh // 2), dtype=torch.uint8, device=device)
             self.v_codes = mk((batch, nh, cap, dh // 2), dtype=torch.uint8, device=device)
-            self.k_meta = mk((batch, nh, cap, dh // 64, 2), dtype=torch.float32, device=device)
-            self.v_meta = mk((batch, nh, cap, dh // 64, 2), dtype=torch.float32, device=device)
+            mt = torch.float16 if self.meta_f16 else torch.float32
+            self.k_meta = mk((batch, nh, cap, dh // 64, 2), dtype=mt, device=device)
+            self.v_meta = mk((batch, nh, cap, dh // 64, 2), dtype=mt, device=device)
         else:
             self.k_codes = mk((batch, nh, cap, dh), dtype=torch.float16, device=device)
             self.v_codes = mk((batch, nh, cap, dh), dtype=torch.float16, device=device)
             self.k_meta = self.v_meta = None
         self.c = fg_kv_cache(_p(self.k_codes), _p(self.k_meta), _p(self.v_codes), _p(self.v_meta),
-                             FG_Q4G64 if quantized else FG_F16, batch, cap, 0)
+                             (FG_Q4G64_H16 if self.meta_f16 else FG_Q4G64) if quantized else FG_F16, batch, cap, 0)
 
     def nbytes(self) -> int:
         n = 2 * self.k_codes.numel() * self.k_codes.element_size()
         if self.k_meta is not None:
-            n += 2 * self.k_meta.numel() * 4
+            n += 2 * self.k_meta.numel() * self.k_meta.element_size()
         return n
 
 
@@ -237,21 +244,22 @@ def fg_version() -> int:
     return lib().fg_version()
 
 
-def fg_quantize_groupwise(x: torch.Tensor, group: int = 64, bits: int = 4):
+def fg_quantize_groupwise(x: torch.Tensor, group: int = 64, bits: int = 4, meta_f16: bool = False):
+    """meta_f16: the 4.5-bit variant with FP16 {min, scale} pairs (fg_quantize_groupwise_h16)."""
     x = _f16(x)
     rows, cols = x.shape
     codes = torch.empty((rows, cols // 2), dtype=torch.uint8, device=x.device)
-    meta = torch.empty((rows, cols // 64, 2), dtype=torch.float32, device=x.device)
-    _check(lib().fg_quantize_groupwise(_p(x), rows, cols, group, bits, _p(codes), _p(meta), _stream()),
-           "fg_quantize_groupwise")
+    meta = torch.empty((rows, cols // 64, 2), dtype=torch.float16 if meta_f16 else torch.float32, device=x.device)
+    fn = lib().fg_quantize_groupwise_h16 if meta_f16 else lib().fg_quantize_groupwise
+    _check(fn(_p(x), rows, cols, group, bits, _p(codes), _p(meta), _stream()), "fg_quantize_groupwise")
     return codes, meta
 
 
 def fg_dequantize_groupwise(codes: torch.Tensor, meta: torch.Tensor) -> torch.Tensor:
     rows, half = codes.shape
     out = torch.empty((rows, half * 2), dtype=torch.float32, device=codes.device)
-    _check(lib().fg_dequantize_groupwise(_p(codes), _p(meta), rows, half * 2, _p(out), _stream()),
-           "fg_dequantize_groupwise")
+    fn = lib().fg_dequantize_groupwise_h16 if meta.dtype == torch.float16 else lib().fg_dequantize_groupwise
+    _check(fn(_p(codes), _p(meta), rows, half * 2, _p(out), _stream()), "fg_dequantize_groupwise")
     return out
 
 

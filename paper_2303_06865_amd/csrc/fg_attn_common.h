@@ -16,6 +16,20 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// {min, scale} of one group as stored: two binary32 (FG_Q4G64) or two FP16 (FG_Q4G64_H16).  Kept raw
+// in the prefetch buffers and converted only when the chunk is processed, so that a conversion
+// never waits for a load that has just been issued.
+template <bool H16>
+struct MetaRaw {
+  using type = float2;
+};
+template <>
+struct MetaRaw<true> {
+  using type = h2_t;
+};
+__device__ __forceinline__ float2 meta_f32(float2 m) { return m; }
+__device__ __forceinline__ float2 meta_f32(h2_t m) { return make_float2((float)m.x, (float)m.y); }
+
 template <int DH>
 struct QueryOps {
   float Qs[2], Os[2];   // per-group sums of q and of bias * q

@@ -32,8 +32,8 @@ struct AttnArgs {
   int64_t q_stride;
   const uint8_t* k_codes;
   const uint8_t* v_codes;
-  const float2* k_meta;
-  const float2* v_meta;
+  const void* k_meta;   // float2 or (H16) FP16 pairs
+  const void* v_meta;
   half_t* out;       // [b, nh*dh]
   int nh, cap, rows, batch_offset;
   int n_heads;       // b * nh
@@ -65,8 +65,9 @@ __device__ __forceinline__ void merge_and_store(const float* sm_m, const float* 
   }
 }
 
-template <int DH, int WPH>
+template <int DH, int WPH, bool H16>
 __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
+  using meta_t = typename MetaRaw<H16>::type;
   constexpr int GPR = DH / 64;       // quantization groups per row of this head
   constexpr int NS = 2 / GPR;        // scores per lane per chunk (lane owns groups 2L, 2L+1)
   constexpr int HPB = 4 / WPH;       // heads per workgroup
@@ -86,15 +87,15 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
   const int64_t hrow = ((int64_t)(a.batch_offset + seq) * a.nh + head) * a.cap;   // first cache row
   const uint8_t* kc = a.k_codes + hrow * (DH / 2);
   const uint8_t* vc = a.v_codes + hrow * (DH / 2);
-  const float2* km = a.k_meta + hrow * GPR;
-  const float2* vm = a.v_meta + hrow * GPR;
+  const meta_t* km = reinterpret_cast<const meta_t*>(a.k_meta) + hrow * GPR;
+  const meta_t* vm = reinterpret_cast<const meta_t*>(a.v_meta) + hrow * GPR;
   const int G = a.rows * GPR;                  // groups in the stream
   const int n_chunks = (G + 127) >> 7;
 
   // one chunk's worth of registers: 4 + 4 code loads of 16 bytes and the meta of the lane's two groups
   struct Buf {
     u4_t kq[4], vq[4];
-    float2 km0, km1, vm0, vm1;
+    meta_t km0, km1, vm0, vm1;
   };
   // all addresses clamped into the stream; rows past the end are masked when the chunk is processed
   auto load = [&](Buf& b, int chunk) {
@@ -137,7 +138,7 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
     const int ni = (G - gbase + 31) >> 5;   // 32-group loads of this chunk that hold valid rows
     // ---- scores on the matrix cores
     float sc[NS];
-    chunk_scores<DH>(b.kq, b.km0, b.km1, Q, a.scale, G, gbase, lane, sc);
+    chunk_scores<DH>(b.kq, meta_f32(b.km0), meta_f32(b.km1), Q, a.scale, G, gbase, lane, sc);
     // ---- online softmax (every processed chunk has at least one valid row)
     float cmax = sc[0];
     if (NS == 2) cmax = fmaxf(cmax, sc[NS - 1]);
@@ -157,9 +158,10 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
     p[1] = NS == 2 ? fast_exp2((sc[NS - 1] - m_run) * kLog2e) : p[0];
     l_run += NS == 2 ? p[0] + p[1] : p[0];
     // weights of the V codes of the two groups this lane owns, and their constant terms
-    const float wv0 = p[0] * b.vm0.y, wv1 = p[1] * b.vm1.y;
-    mterm[0] += p[0] * b.vm0.x;
-    mterm[1] += p[1] * b.vm1.x;
+    const float2 vm0 = meta_f32(b.vm0), vm1 = meta_f32(b.vm1);
+    const float wv0 = p[0] * vm0.y, wv1 = p[1] * vm1.y;
+    mterm[0] += p[0] * vm0.x;
+    mterm[1] += p[1] * vm1.x;
 
     // ---- output accumulation: lane (r, q4) handles group 32 i + 2 r + h of each load, half `half`.
     // A nibble masked in place is the FP16 subnormal c * 2^-24 (low nibble of a half) or c * 2^-20;
@@ -383,8 +385,8 @@ int decode_attention_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_
   a.q_stride = q_stride;
   a.k_codes = reinterpret_cast<const uint8_t*>(kv.k_codes);
   a.v_codes = reinterpret_cast<const uint8_t*>(kv.v_codes);
-  a.k_meta = reinterpret_cast<const float2*>(kv.k_meta);
-  a.v_meta = reinterpret_cast<const float2*>(kv.v_meta);
+  a.k_meta = kv.k_meta;
+  a.v_meta = kv.v_meta;
   a.out = out;
   a.nh = cfg.nh;
   a.cap = kv.cap;
@@ -397,27 +399,39 @@ int decode_attention_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_
   const int64_t heads = (int64_t)b * cfg.nh;
   const int wph = heads >= 2048 ? 1 : (heads >= 1024 ? 2 : 4);
   const dim3 grid((unsigned)ceil_div(heads * wph, 4));
-  const bool q4 = kv.dtype == FG_Q4G64;
+  const bool q4 = kv.dtype == FG_Q4G64 || kv.dtype == FG_Q4G64_H16;
+  const bool h16 = kv.dtype == FG_Q4G64_H16;
   ProfScope prof(FG_K_ATTN_DECODE, stream);
-#define FG_ATTN_LAUNCH(KERNEL, DH_)                                                                   \
+#define FG_ATTN_LAUNCH(DH_, ...)                                                                      \
   do {                                                                                                \
     if (wph == 1)                                                                                     \
-      hipLaunchKernelGGL((KERNEL<DH_, 1>), grid, dim3(256), 0, stream, a);                            \
+      hipLaunchKernelGGL((__VA_ARGS__<DH_, 1 FG_ATTN_EXTRA>), grid, dim3(256), 0, stream, a);         \
     else if (wph == 2)                                                                                \
-      hipLaunchKernelGGL((KERNEL<DH_, 2>), grid, dim3(256), 0, stream, a);                            \
+      hipLaunchKernelGGL((__VA_ARGS__<DH_, 2 FG_ATTN_EXTRA>), grid, dim3(256), 0, stream, a);         \
     else                                                                                              \
-      hipLaunchKernelGGL((KERNEL<DH_, 4>), grid, dim3(256), 0, stream, a);                            \
+      hipLaunchKernelGGL((__VA_ARGS__<DH_, 4 FG_ATTN_EXTRA>), grid, dim3(256), 0, stream, a);         \
   } while (0)
-  if (q4) {
+  if (q4 && h16) {
+#define FG_ATTN_EXTRA , true
     if (dh == 128)
-      FG_ATTN_LAUNCH(attn_decode_q4_kernel, 128);
+      FG_ATTN_LAUNCH(128, attn_decode_q4_kernel);
     else
-      FG_ATTN_LAUNCH(attn_decode_q4_kernel, 64);
+      FG_ATTN_LAUNCH(64, attn_decode_q4_kernel);
+#undef FG_ATTN_EXTRA
+  } else if (q4) {
+#define FG_ATTN_EXTRA , false
+    if (dh == 128)
+      FG_ATTN_LAUNCH(128, attn_decode_q4_kernel);
+    else
+      FG_ATTN_LAUNCH(64, attn_decode_q4_kernel);
+#undef FG_ATTN_EXTRA
   } else {
+#define FG_ATTN_EXTRA
     if (dh == 128)
-      FG_ATTN_LAUNCH(attn_decode_f16_kernel, 128);
+      FG_ATTN_LAUNCH(128, attn_decode_f16_kernel);
     else
-      FG_ATTN_LAUNCH(attn_decode_f16_kernel, 64);
+      FG_ATTN_LAUNCH(64, attn_decode_f16_kernel);
+#undef FG_ATTN_EXTRA
   }
 #undef FG_ATTN_LAUNCH
   FG_LAUNCH_CHECK();

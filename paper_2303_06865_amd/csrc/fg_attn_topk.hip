@@ -23,8 +23,8 @@ struct TopkArgs {
   int64_t q_stride;
   const uint8_t* k_codes;
   const uint8_t* v_codes;
-  const float2* k_meta;
-  const float2* v_meta;
+  const void* k_meta;   // float2 or (H16) FP16 pairs
+  const void* v_meta;
   half_t* out;       // [b, nh*dh]
   int32_t* sel_out;  // [b, nh, topk] kept row indices, ascending, or NULL
   int nh, cap, rows, topk, batch_offset;
@@ -57,8 +57,9 @@ __device__ __forceinline__ int block_excl_scan(int v, int* s_wave, int* total) {
   return base + incl - v;
 }
 
-template <int DH>
+template <int DH, bool H16>
 __global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
+  using meta_t = typename MetaRaw<H16>::type;
   constexpr int GPR = DH / 64;       // quantization groups per row
   constexpr int NS = 2 / GPR;        // scores per lane per chunk
   constexpr int RPC = 128 / GPR;     // rows per chunk
@@ -85,14 +86,14 @@ __global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
   const int64_t hrow = ((int64_t)(a.batch_offset + seq) * a.nh + head) * a.cap;   // first cache row
   const uint8_t* kc = a.k_codes + hrow * (DH / 2);
   const uint8_t* vc = a.v_codes + hrow * (DH / 2);
-  const float2* km = a.k_meta + hrow * GPR;
-  const float2* vm = a.v_meta + hrow * GPR;
+  const meta_t* km = reinterpret_cast<const meta_t*>(a.k_meta) + hrow * GPR;
+  const meta_t* vm = reinterpret_cast<const meta_t*>(a.v_meta) + hrow * GPR;
   const int G = n * GPR;
   const int n_chunks = (G + 127) >> 7;
 
   struct Buf {
     u4_t kq[4];
-    float2 km0, km1;
+    meta_t km0, km1;
   };
   auto load = [&](Buf& b, int chunk) {
     const int gbase = chunk << 7;
@@ -121,7 +122,7 @@ __global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
   float m_run = -INFINITY, l_run = 0.f;
   auto scores = [&](const Buf& b, int chunk) {
     float sc[NS];
-    chunk_scores<DH>(b.kq, b.km0, b.km1, Q, a.scale, G, chunk << 7, lane, sc);
+    chunk_scores<DH>(b.kq, meta_f32(b.km0), meta_f32(b.km1), Q, a.scale, G, chunk << 7, lane, sc);
     float cmax = sc[0];
     if (NS == 2) cmax = fmaxf(cmax, sc[NS - 1]);
     cmax = wave_max(cmax);              // a processed chunk has at least one valid row
@@ -252,7 +253,7 @@ __global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
     const int row = s_sel[valid ? e : a.topk - 1];
     const float p = valid ? fast_exp2((s_sc[row] - M) * kLog2e) * inv_den : 0.f;
     const uint2 cw = *reinterpret_cast<const uint2*>(vc + (int64_t)row * (DH / 2) + pc * 8);
-    const float2 mt = vm[(int64_t)row * GPR + (pc >> 2)];
+    const float2 mt = meta_f32(vm[(int64_t)row * GPR + (pc >> 2)]);
     const float w = p * mt.y;
     const float w24 = w * 16777216.0f, w20 = w * 1048576.0f;   // nibbles are read as FP16 subnormals
     mterm += p * mt.x;
@@ -306,8 +307,8 @@ int decode_attention_topk_launch(const fg_model_cfg& cfg, const half_t* q, int64
   a.q_stride = q_stride;
   a.k_codes = reinterpret_cast<const uint8_t*>(kv.k_codes);
   a.v_codes = reinterpret_cast<const uint8_t*>(kv.v_codes);
-  a.k_meta = reinterpret_cast<const float2*>(kv.k_meta);
-  a.v_meta = reinterpret_cast<const float2*>(kv.v_meta);
+  a.k_meta = kv.k_meta;
+  a.v_meta = kv.v_meta;
   a.out = out;
   a.sel_out = sel_out;
   a.nh = cfg.nh;
@@ -320,17 +321,19 @@ int decode_attention_topk_launch(const fg_model_cfg& cfg, const half_t* q, int64
   if ((int64_t)a.rows_pad + topk > kMaxLdsWords) return FG_ERR_UNSUPPORTED;
   const size_t smem = ((size_t)a.rows_pad + topk) * 4;
   const dim3 grid((unsigned)(b * cfg.nh));
-  static bool attr_done[2] = {false, false};
-  const void* fn = dh == 128 ? (const void*)&attn_decode_topk_q4_kernel<128> : (const void*)&attn_decode_topk_q4_kernel<64>;
-  if (!attr_done[dh == 128]) {
-    FG_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsWords * 4));
-    attr_done[dh == 128] = true;
+  const bool h16 = kv.dtype == FG_Q4G64_H16;
+  const int variant = (dh == 128 ? 2 : 0) + (h16 ? 1 : 0);
+  typedef void (*kernel_t)(TopkArgs);
+  static const kernel_t kernels[4] = {attn_decode_topk_q4_kernel<64, false>, attn_decode_topk_q4_kernel<64, true>,
+                                      attn_decode_topk_q4_kernel<128, false>, attn_decode_topk_q4_kernel<128, true>};
+  static bool attr_done[4] = {false, false, false, false};
+  if (!attr_done[variant]) {
+    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernels[variant]),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsWords * 4));
+    attr_done[variant] = true;
   }
   ProfScope prof(FG_K_ATTN_DECODE, stream);
-  if (dh == 128)
-    hipLaunchKernelGGL(attn_decode_topk_q4_kernel<128>, grid, dim3(256), smem, stream, a);
-  else
-    hipLaunchKernelGGL(attn_decode_topk_q4_kernel<64>, grid, dim3(256), smem, stream, a);
+  hipLaunchKernelGGL(kernels[variant], grid, dim3(256), smem, stream, a);
   FG_LAUNCH_CHECK();
   return FG_OK;
 }
@@ -347,7 +350,7 @@ extern "C" int fg_decode_attention_topk(const fg_model_cfg* cfg, const void* q_f
   if (rc) return rc;
   rc = check_kv(cfg, kv);
   if (rc) return rc;
-  if (kv->dtype != FG_Q4G64) return FG_ERR_UNSUPPORTED;
+  if (kv->dtype != FG_Q4G64 && kv->dtype != FG_Q4G64_H16) return FG_ERR_UNSUPPORTED;
   if (b < 0 || rows < 1 || rows > kv->cap || batch_offset < 0 || (int64_t)batch_offset + b > kv->batch)
     return FG_ERR_SHAPE;
   if (topk < 1 || topk > rows) return FG_ERR_SHAPE;

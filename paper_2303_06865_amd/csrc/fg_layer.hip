@@ -73,12 +73,13 @@ int check_mat(const fg_mat* w) {
 
 int check_kv(const fg_model_cfg* cfg, const fg_kv_cache* kv) {
   (void)cfg;
-  if (kv->dtype != FG_F16 && kv->dtype != FG_Q4G64) return FG_ERR_UNSUPPORTED;
+  const bool q4 = kv->dtype == FG_Q4G64 || kv->dtype == FG_Q4G64_H16;
+  if (kv->dtype != FG_F16 && !q4) return FG_ERR_UNSUPPORTED;
   if (kv->batch <= 0 || kv->cap <= 0) return FG_ERR_SHAPE;
   if (!kv->k_codes || !kv->v_codes) return FG_ERR_NULL;
-  if (kv->dtype == FG_Q4G64 && (!kv->k_meta || !kv->v_meta)) return FG_ERR_NULL;
+  if (q4 && (!kv->k_meta || !kv->v_meta)) return FG_ERR_NULL;
   if (!aligned16(kv->k_codes) || !aligned16(kv->v_codes)) return FG_ERR_SHAPE;
-  if (kv->dtype == FG_Q4G64 && (!aligned16(kv->k_meta) || !aligned16(kv->v_meta))) return FG_ERR_SHAPE;
+  if (q4 && (!aligned16(kv->k_meta) || !aligned16(kv->v_meta))) return FG_ERR_SHAPE;
   return FG_OK;
 }
 
@@ -581,7 +582,9 @@ extern "C" int fg_generate(const fg_model_cfg* cfg, int32_t l, const fg_layer_we
     stats->weight_bytes_per_step = wb;
     const int64_t rows_last = (int64_t)s + n - 1;
     const int64_t el = 2 * (int64_t)bls * l * h1 * (n > 1 ? rows_last : 0);
-    stats->kv_bytes_last_step = kv[0].dtype == FG_Q4G64 ? el / 2 + el / kGroup * 8 : el * 2;
+    stats->kv_bytes_last_step = kv[0].dtype == FG_Q4G64       ? el / 2 + el / kGroup * 8
+                                : kv[0].dtype == FG_Q4G64_H16 ? el / 2 + el / kGroup * 4
+                                                              : el * 2;
     cleanup();
   }
   return FG_OK;

@@ -9,6 +9,10 @@ namespace fg {
 
 // Eight lanes cooperate on one group of 64 FP16 values (16 bytes per lane), so a wavefront
 // covers eight groups per pass: 1 KiB of coalesced input, 256 B of codes, 64 B of meta.
+// H16: the 4.5-bit variant whose {min, scale} pair is stored as two FP16 numbers.  min is an FP16
+// input value and needs no rounding; scale becomes the smallest FP16 number >= (max-min)/15, and it
+// is that stored scale the codes are computed with (so they still lie in [0, 15] unclamped).
+template <bool H16>
 __device__ __forceinline__ void quantize_group_8lanes(const h8_t v, int sub, uint32_t& packed,
                                                       float& mn_out, float& scale_out) {
   float x[8];
@@ -26,7 +30,15 @@ __device__ __forceinline__ void quantize_group_8lanes(const h8_t v, int sub, uin
     mx = fmaxf(mx, __shfl_xor(mx, o, 64));
   }
   const float range = mx - mn;
-  const float scale = range / 15.0f;  // IEEE-rounded division (see build flags)
+  float scale = range / 15.0f;  // IEEE-rounded division (see build flags)
+  if (H16) {
+    half_t hs = (half_t)scale;                         // round to nearest ...
+    if ((float)hs < scale) {                           // ... then up, if that fell below
+      const uint16_t b = __builtin_bit_cast(uint16_t, hs);
+      hs = __builtin_bit_cast(half_t, (uint16_t)(b + 1));
+    }
+    scale = (float)hs;
+  }
   uint32_t p = 0;
   if (scale > 0.0f) {
 #pragma unroll
@@ -44,10 +56,11 @@ __device__ __forceinline__ void quantize_group_8lanes(const h8_t v, int sub, uin
 }
 
 // Plain layout: x [rows, cols] contiguous -> codes [rows, cols/2], meta [rows, cols/64].
+template <bool H16>
 __global__ __launch_bounds__(256) void quantize_rows_kernel(const half_t* __restrict__ x,
                                                             int64_t n_groups,
                                                             uint32_t* __restrict__ codes,
-                                                            float2* __restrict__ meta) {
+                                                            void* __restrict__ meta) {
   const int sub = threadIdx.x & 7;
   int64_t g = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 3;
   const int64_t stride = ((int64_t)gridDim.x * blockDim.x) >> 3;
@@ -55,21 +68,33 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const half_t* __rest
     const h8_t v = *reinterpret_cast<const h8_t*>(x + g * kGroup + sub * 8);
     uint32_t p;
     float mn, sc;
-    quantize_group_8lanes(v, sub, p, mn, sc);
+    quantize_group_8lanes<H16>(v, sub, p, mn, sc);
     codes[g * 8 + sub] = p;
-    if (sub == 0) meta[g] = make_float2(mn, sc);
+    if (sub == 0) {
+      if (H16)
+        reinterpret_cast<h2_t*>(meta)[g] = (h2_t){(half_t)mn, (half_t)sc};
+      else
+        reinterpret_cast<float2*>(meta)[g] = make_float2(mn, sc);
+    }
   }
 }
 
+template <bool H16>
 __global__ __launch_bounds__(256) void dequantize_rows_kernel(const uint32_t* __restrict__ codes,
-                                                              const float2* __restrict__ meta,
+                                                              const void* __restrict__ meta,
                                                               int64_t n_words,
                                                               float* __restrict__ out) {
   int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   for (; w < n_words; w += stride) {
     const uint32_t p = codes[w];
-    const float2 m = meta[w >> 3];
+    float2 m;
+    if (H16) {
+      const h2_t hm = reinterpret_cast<const h2_t*>(meta)[w >> 3];
+      m = make_float2((float)hm.x, (float)hm.y);
+    } else {
+      m = reinterpret_cast<const float2*>(meta)[w >> 3];
+    }
     float4 lo, hi;
     float* o = reinterpret_cast<float*>(&lo);
     float* o2 = reinterpret_cast<float*>(&hi);
@@ -93,11 +118,12 @@ struct KvAppendArgs {
   int32_t b, s, nh, dh, cap, batch_offset, pos0;
 };
 
+template <bool H16>
 __global__ __launch_bounds__(256) void kv_append_q4_kernel(KvAppendArgs a) {
   const int which = blockIdx.y;
   const half_t* __restrict__ x = a.src[which];
   uint32_t* __restrict__ codes = reinterpret_cast<uint32_t*>(a.codes[which]);
-  float2* __restrict__ meta = reinterpret_cast<float2*>(a.meta[which]);
+  void* __restrict__ meta = a.meta[which];
   const int gph = a.dh / kGroup;              // groups per head
   const int gpr = a.nh * gph;                 // groups per token row
   const int64_t n_groups = (int64_t)a.b * a.s * gpr;
@@ -113,10 +139,15 @@ __global__ __launch_bounds__(256) void kv_append_q4_kernel(KvAppendArgs a) {
     const h8_t v = *reinterpret_cast<const h8_t*>(x + row * a.ld + (int64_t)gi * kGroup + sub * 8);
     uint32_t p;
     float mn, sc;
-    quantize_group_8lanes(v, sub, p, mn, sc);
+    quantize_group_8lanes<H16>(v, sub, p, mn, sc);
     const int64_t crow = (((int64_t)(a.batch_offset + bi) * a.nh + head) * a.cap + pos);
     codes[(crow * gph + gh) * 8 + sub] = p;
-    if (sub == 0) meta[crow * gph + gh] = make_float2(mn, sc);
+    if (sub == 0) {
+      if (H16)
+        reinterpret_cast<h2_t*>(meta)[crow * gph + gh] = (h2_t){(half_t)mn, (half_t)sc};
+      else
+        reinterpret_cast<float2*>(meta)[crow * gph + gh] = make_float2(mn, sc);
+    }
   }
 }
 
@@ -169,10 +200,13 @@ int kv_append_launch(const fg_model_cfg& cfg, const half_t* k, const half_t* v, 
   a.batch_offset = batch_offset;
   a.pos0 = pos0;
   ProfScope prof(FG_K_KV_APPEND, stream);
-  if (kv.dtype == FG_Q4G64) {
+  if (kv.dtype == FG_Q4G64 || kv.dtype == FG_Q4G64_H16) {
     const int64_t groups = (int64_t)b * s * cfg.h1 / kGroup;
     dim3 grid(grid_for(groups, 32), 2);
-    hipLaunchKernelGGL(kv_append_q4_kernel, grid, dim3(256), 0, stream, a);
+    if (kv.dtype == FG_Q4G64_H16)
+      hipLaunchKernelGGL(kv_append_q4_kernel<true>, grid, dim3(256), 0, stream, a);
+    else
+      hipLaunchKernelGGL(kv_append_q4_kernel<false>, grid, dim3(256), 0, stream, a);
   } else {
     const int64_t chunks = (int64_t)b * s * cfg.h1 / 8;
     dim3 grid(grid_for(chunks, 256), 2);
@@ -186,8 +220,8 @@ int kv_append_launch(const fg_model_cfg& cfg, const half_t* k, const half_t* v, 
 
 using namespace fg;
 
-extern "C" int fg_quantize_groupwise(const void* x_f16, int64_t rows, int64_t cols, int group, int bits,
-                                     void* codes_out, void* meta_out, void* stream) {
+static int quantize_entry(bool h16, const void* x_f16, int64_t rows, int64_t cols, int group, int bits,
+                          void* codes_out, void* meta_out, void* stream) {
   if (group != kGroup || bits != 4) return FG_ERR_UNSUPPORTED;
   if (rows < 0 || cols <= 0 || cols % kGroup != 0) return FG_ERR_SHAPE;
   if (rows == 0) return FG_OK;
@@ -195,26 +229,52 @@ extern "C" int fg_quantize_groupwise(const void* x_f16, int64_t rows, int64_t co
   const int64_t groups = rows * (cols / kGroup);
   hipStream_t st = as_stream(stream);
   ProfScope prof(FG_K_QUANTIZE, st);
-  hipLaunchKernelGGL(quantize_rows_kernel, dim3(grid_for(groups, 32)), dim3(256), 0, st,
-                     reinterpret_cast<const half_t*>(x_f16), groups,
-                     reinterpret_cast<uint32_t*>(codes_out), reinterpret_cast<float2*>(meta_out));
+  if (h16)
+    hipLaunchKernelGGL(quantize_rows_kernel<true>, dim3(grid_for(groups, 32)), dim3(256), 0, st,
+                       reinterpret_cast<const half_t*>(x_f16), groups, reinterpret_cast<uint32_t*>(codes_out), meta_out);
+  else
+    hipLaunchKernelGGL(quantize_rows_kernel<false>, dim3(grid_for(groups, 32)), dim3(256), 0, st,
+                       reinterpret_cast<const half_t*>(x_f16), groups, reinterpret_cast<uint32_t*>(codes_out), meta_out);
   FG_LAUNCH_CHECK();
   return FG_OK;
 }
 
-extern "C" int fg_dequantize_groupwise(const void* codes, const void* meta, int64_t rows, int64_t cols,
-                                       void* out_f32, void* stream) {
+extern "C" int fg_quantize_groupwise(const void* x_f16, int64_t rows, int64_t cols, int group, int bits,
+                                     void* codes_out, void* meta_out, void* stream) {
+  return quantize_entry(false, x_f16, rows, cols, group, bits, codes_out, meta_out, stream);
+}
+
+extern "C" int fg_quantize_groupwise_h16(const void* x_f16, int64_t rows, int64_t cols, int group, int bits,
+                                         void* codes_out, void* meta_out_f16, void* stream) {
+  return quantize_entry(true, x_f16, rows, cols, group, bits, codes_out, meta_out_f16, stream);
+}
+
+static int dequantize_entry(bool h16, const void* codes, const void* meta, int64_t rows, int64_t cols, void* out_f32,
+                            void* stream) {
   if (rows < 0 || cols <= 0 || cols % kGroup != 0) return FG_ERR_SHAPE;
   if (rows == 0) return FG_OK;
   if (!codes || !meta || !out_f32) return FG_ERR_NULL;
   const int64_t words = rows * cols / 8;
   hipStream_t st = as_stream(stream);
   ProfScope prof(FG_K_DEQUANTIZE, st);
-  hipLaunchKernelGGL(dequantize_rows_kernel, dim3(grid_for(words, 256)), dim3(256), 0, st,
-                     reinterpret_cast<const uint32_t*>(codes), reinterpret_cast<const float2*>(meta), words,
-                     reinterpret_cast<float*>(out_f32));
+  if (h16)
+    hipLaunchKernelGGL(dequantize_rows_kernel<true>, dim3(grid_for(words, 256)), dim3(256), 0, st,
+                       reinterpret_cast<const uint32_t*>(codes), meta, words, reinterpret_cast<float*>(out_f32));
+  else
+    hipLaunchKernelGGL(dequantize_rows_kernel<false>, dim3(grid_for(words, 256)), dim3(256), 0, st,
+                       reinterpret_cast<const uint32_t*>(codes), meta, words, reinterpret_cast<float*>(out_f32));
   FG_LAUNCH_CHECK();
   return FG_OK;
+}
+
+extern "C" int fg_dequantize_groupwise(const void* codes, const void* meta, int64_t rows, int64_t cols,
+                                       void* out_f32, void* stream) {
+  return dequantize_entry(false, codes, meta, rows, cols, out_f32, stream);
+}
+
+extern "C" int fg_dequantize_groupwise_h16(const void* codes, const void* meta_f16, int64_t rows, int64_t cols,
+                                           void* out_f32, void* stream) {
+  return dequantize_entry(true, codes, meta_f16, rows, cols, out_f32, stream);
 }
 
 extern "C" int fg_kv_append(const fg_model_cfg* cfg, const void* k_f16, const void* v_f16,

@@ -59,7 +59,7 @@ def main(argv=None):
     ap.add_argument("--rows", type=int, default=528, help="cached positions read by decode attention")
     ap.add_argument("--seq", type=int, default=512)
     ap.add_argument("--topk", type=int, default=0, help="attn_decode_topk: rows kept (default: ceil(rows / 10))")
-    ap.add_argument("--kv", choices=["q4", "f16"], default="q4")
+    ap.add_argument("--kv", choices=["q4", "q4h", "f16"], default="q4", help="cache storage: 4-bit, 4-bit with FP16 pairs, FP16")
     ap.add_argument("--mib", type=int, default=1024, help="copy: MiB read (and as many written)")
     ap.add_argument("--iters", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
@@ -79,13 +79,14 @@ def main(argv=None):
     elif a.op in ("attn_decode", "attn_decode_topk"):
         h1 = a.nh * a.dh
         cfg = B.Cfg(h1, a.nh, 4 * h1, 50272, 4096)
-        q4 = a.kv == "q4"
-        kv = B.KVCache(cfg, a.batch, a.rows + 64, q4, zero=False)
+        q4 = a.kv != "f16"
+        kvb = {"q4": 0.625, "q4h": 0.5625, "f16": 2.0}[a.kv]
+        kv = B.KVCache(cfg, a.batch, a.rows + 64, q4, zero=False, meta_f16=a.kv == "q4h")
         if q4:
             kv.k_codes.random_(0, 256)
             kv.v_codes.random_(0, 256)
-            kv.k_meta.normal_().abs_().mul_(0.3)
-            kv.v_meta.normal_().abs_().mul_(0.3)
+            kv.k_meta.copy_(torch.randn(kv.k_meta.shape, device=dev).abs_().mul_(0.3))
+            kv.v_meta.copy_(torch.randn(kv.v_meta.shape, device=dev).abs_().mul_(0.3))
         else:
             kv.k_codes.normal_()
             kv.v_codes.normal_()
@@ -94,13 +95,13 @@ def main(argv=None):
             topk = a.topk or -(-a.rows // 10)
             # K stream in full, topk rows of V
             out.update(batch=a.batch, nh=a.nh, dh=a.dh, rows=a.rows, topk=topk, kv=a.kv,
-                       bytes=int(a.batch * a.nh * (a.rows + topk) * a.dh * 0.625),
+                       bytes=int(a.batch * a.nh * (a.rows + topk) * a.dh * kvb),
                        flops=2 * a.batch * a.nh * (a.rows + topk) * a.dh)
             out["classes"] = _time_classes(
                 lambda: B.fg_decode_attention_topk(cfg, qkv, 3 * h1, a.batch, a.rows, topk, kv, 0), a.iters, a.warmup)
         else:
             out.update(batch=a.batch, nh=a.nh, dh=a.dh, rows=a.rows, kv=a.kv,
-                       bytes=int(2 * a.batch * a.nh * a.rows * a.dh * (0.625 if q4 else 2)),
+                       bytes=int(2 * a.batch * a.nh * a.rows * a.dh * kvb),
                        flops=4 * a.batch * a.nh * a.rows * a.dh)
             out["classes"] = _time_classes(lambda: B.fg_decode_attention(cfg, qkv, 3 * h1, a.batch, a.rows, kv, 0),
                                            a.iters, a.warmup)

@@ -50,6 +50,24 @@ def test_quantize_edge_groups_bit_exact():
     assert list(O.unpack_codes(host(codes))[1, 2:6]) == [0, 2, 2, 4]
 
 
+@pytest.mark.parametrize("rows,cols,std", [(1, 64, 1.0), (37, 576, 0.02), (257, 12288, 0.02), (7, 64 * 5, 30.0),
+                                           (9, 256, 1e-4), (5, 128, 3000.0)])
+def test_quantize_h16_variant_bit_exact(rows, cols, std):
+    """FP16 {min, scale} pairs: same bit-exactness bar, including scales in the FP16 subnormal range."""
+    x = _rand16((rows, cols), std, rows * 11 + cols)
+    x[0, :64] = x[0, 0]                                  # a constant group
+    codes_ref, meta_ref = O.quantize_groupwise_h16(x)
+    codes, meta = B.fg_quantize_groupwise(dev(x), meta_f16=True)
+    torch.cuda.synchronize()
+    assert meta.dtype == torch.float16
+    assert np.array_equal(host(meta).view(np.uint16), meta_ref.view(np.uint16))
+    assert np.array_equal(host(codes), codes_ref)
+    out = B.fg_dequantize_groupwise(dev(codes_ref), dev(meta_ref))
+    torch.cuda.synchronize()
+    ref = O.dequantize_groupwise(codes_ref, meta_ref)
+    assert np.array_equal(host(out).view(np.uint32), ref.view(np.uint32))
+
+
 def test_quantize_empty_input_is_a_noop():
     x = torch.empty((0, 128), dtype=torch.float16, device="cuda")
     codes, meta = B.fg_quantize_groupwise(x)
@@ -182,36 +200,39 @@ def test_linear_identity_and_onehot():
 
 
 # ------------------------------------------------------------------ KV append
-@pytest.mark.parametrize("quant", [True, False])
+@pytest.mark.parametrize("quant", [True, False, "h16"])
 @pytest.mark.parametrize("nh,dh", [(3, 128), (12, 64)])
 def test_kv_append_bit_exact(nh, dh, quant):
     h1 = nh * dh
     cfg = B.Cfg(h1, nh, 4 * h1, 1000, 64)
     b, s, cap, boff, pos0 = 3, 5, 16, 1, 4
     qkv = _rand16((b * s, 3 * h1), 1.0, nh + dh)
-    okv = O.KVCache.empty(5, nh, cap, dh, quant)
+    h16 = quant == "h16"
+    quant = bool(quant)
+    okv = O.KVCache.empty(5, nh, cap, dh, quant, h16)
     okv.store(boff, pos0, qkv[:, h1:2 * h1].reshape(b, s, h1), qkv[:, 2 * h1:].reshape(b, s, h1))
-    kv = B.KVCache(cfg, 5, cap, quant)
+    kv = B.KVCache(cfg, 5, cap, quant, meta_f16=h16)
     dq = dev(qkv)
     B.fg_kv_append(cfg, dq[:, h1:], dq[:, 2 * h1:], 3 * h1, b, s, kv, boff, pos0)
     torch.cuda.synchronize()
     if quant:
         assert np.array_equal(host(kv.k_codes), okv.k_codes) and np.array_equal(host(kv.v_codes), okv.v_codes)
-        assert np.array_equal(host(kv.k_meta).view(np.uint32), okv.k_meta.view(np.uint32))
-        assert np.array_equal(host(kv.v_meta).view(np.uint32), okv.v_meta.view(np.uint32))
+        bits = np.uint16 if h16 else np.uint32
+        assert np.array_equal(host(kv.k_meta).view(bits), okv.k_meta.view(bits))
+        assert np.array_equal(host(kv.v_meta).view(bits), okv.v_meta.view(bits))
     else:
         assert np.array_equal(host(kv.k_codes), okv.k_f16) and np.array_equal(host(kv.v_codes), okv.v_f16)
 
 
 # ------------------------------------------------------------------ decode attention
-def _decode_attn_case(nh, dh, quant, rows, b=3, batch=4, boff=1, seed=0, kstd=1.0):
+def _decode_attn_case(nh, dh, quant, rows, b=3, batch=4, boff=1, seed=0, kstd=1.0, meta_f16=False):
     h1 = nh * dh
     cfg = B.Cfg(h1, nh, 4 * h1, 1000, 4096)
     cap = rows + 3
     k16 = _rand16((batch, rows, h1), kstd, seed)
     v16 = _rand16((batch, rows, h1), 1.0, seed + 1)
     q16 = _rand16((b, 3 * h1), 1.0, seed + 2)
-    okv = O.KVCache.empty(batch, nh, cap, dh, quant)
+    okv = O.KVCache.empty(batch, nh, cap, dh, quant, meta_f16)
     okv.store(0, 0, k16, v16)
     ref = np.empty((b, nh, dh))
     for i in range(b):
@@ -219,7 +240,7 @@ def _decode_attn_case(nh, dh, quant, rows, b=3, batch=4, boff=1, seed=0, kstd=1.
             kh, vh = okv.load(boff + i, h, rows)
             ref[i, h] = O.attn_decode(q16[i, h * dh:(h + 1) * dh].astype(np.float64), kh, vh)
     ref = O.round_f16(ref.reshape(b, h1))
-    kv = B.KVCache(cfg, batch, cap, quant)
+    kv = B.KVCache(cfg, batch, cap, quant, meta_f16=meta_f16)
     if quant:   # upload the oracle's cache bytes: this test isolates the attention kernel
         kv.k_codes.copy_(dev(okv.k_codes)); kv.v_codes.copy_(dev(okv.v_codes))
         kv.k_meta.copy_(dev(okv.k_meta)); kv.v_meta.copy_(dev(okv.v_meta))
@@ -236,6 +257,18 @@ def _decode_attn_case(nh, dh, quant, rows, b=3, batch=4, boff=1, seed=0, kstd=1.
 def test_decode_attention(rows, nh, dh, quant):
     got, ref = _decode_attn_case(nh, dh, quant, rows, seed=rows)
     assert_close(got, ref, "decode attention rows=%d dh=%d q=%s" % (rows, dh, quant))
+
+
+@pytest.mark.parametrize("nh,dh", [(2, 128), (3, 64)])
+@pytest.mark.parametrize("rows", [1, 63, 65, 129, 257, 600])
+def test_decode_attention_fp16_pair_cache(rows, nh, dh):
+    got, ref = _decode_attn_case(nh, dh, True, rows, seed=rows + 1, meta_f16=True)
+    assert_close(got, ref, "decode attention, FP16 pairs, rows=%d dh=%d" % (rows, dh))
+
+
+def test_decode_attention_fp16_pair_cache_many_heads():
+    got, ref = _decode_attn_case(51, 128, True, 150, b=41, batch=42, boff=1, seed=8, meta_f16=True)
+    assert_close(got, ref, "decode attention, FP16 pairs, one wave per head")
 
 
 @pytest.mark.parametrize("quant", [True, False])
@@ -258,7 +291,7 @@ def test_decode_attention_peaked_softmax(quant):
 
 
 # ------------------------------------------------------------------ Top-K sparse decode attention
-def _topk_case(nh, dh, rows, topk, seed, b=3, batch=4, boff=1, dup_rows=False):
+def _topk_case(nh, dh, rows, topk, seed, b=3, batch=4, boff=1, dup_rows=False, meta_f16=False):
     h1 = nh * dh
     cfg = B.Cfg(h1, nh, 4 * h1, 1000, 4096)
     cap = rows + 3
@@ -267,9 +300,9 @@ def _topk_case(nh, dh, rows, topk, seed, b=3, batch=4, boff=1, dup_rows=False):
         k16[:] = k16[:, :1]
     v16 = _rand16((batch, rows, h1), 1.0, seed + 1)
     q16 = _rand16((b, 3 * h1), 1.0, seed + 2)
-    okv = O.KVCache.empty(batch, nh, cap, dh, True)
+    okv = O.KVCache.empty(batch, nh, cap, dh, True, meta_f16)
     okv.store(0, 0, k16, v16)
-    kv = B.KVCache(cfg, batch, cap, True)
+    kv = B.KVCache(cfg, batch, cap, True, meta_f16=meta_f16)
     kv.k_codes.copy_(dev(okv.k_codes)); kv.v_codes.copy_(dev(okv.v_codes))
     kv.k_meta.copy_(dev(okv.k_meta)); kv.v_meta.copy_(dev(okv.v_meta))
     out, kept = B.fg_decode_attention_topk(cfg, dev(q16), 3 * h1, b, rows, topk, kv, boff, want_rows=True)
@@ -307,6 +340,13 @@ def test_decode_attention_topk(rows, topk, nh, dh):
     out, ref, _, exact = _topk_case(nh, dh, rows, topk, seed=rows + topk)
     assert exact > 0   # random scores: at least one head must have had an unambiguous boundary
     assert_close(out, ref, "top-k attention rows=%d k=%d dh=%d" % (rows, topk, dh))
+
+
+@pytest.mark.parametrize("nh,dh", [(2, 128), (3, 64)])
+def test_decode_attention_topk_fp16_pair_cache(nh, dh):
+    out, ref, _, exact = _topk_case(nh, dh, 300, 30, seed=21, meta_f16=True)
+    assert exact > 0
+    assert_close(out, ref, "top-k attention, FP16 pairs, dh=%d" % dh)
 
 
 @pytest.mark.parametrize("nh,dh", [(2, 128), (3, 64)])

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 
 def _run_layer_sequence(sh, quant_w, quant_kv, b, s, steps, seed, biases, random_ln, x_std=0.05, batch=None,
-                        boff=0, tiled=False):
+                        boff=0, tiled=False, meta_f16=False):
     """Prefill then `steps` decode steps on both sides, the decode inputs being fresh seeded
     activations (the same on both sides).  Before every decode step the device cache is overwritten
     with the oracle's bytes, so each step is compared on identical inputs: the two caches otherwise
@@ -26,8 +26,8 @@ def _run_layer_sequence(sh, quant_w, quant_kv, b, s, steps, seed, biases, random
     w = B.LayerWeights.from_numpy(t, quant_w, tiled=tiled)
     batch = batch or b
     cap = s + steps
-    okv = O.KVCache.empty(batch, sh.nh, cap, sh.dh, quant_kv)
-    kv = B.KVCache(cfg, batch, cap, quant_kv)
+    okv = O.KVCache.empty(batch, sh.nh, cap, sh.dh, quant_kv, meta_f16)
+    kv = B.KVCache(cfg, batch, cap, quant_kv, meta_f16=meta_f16)
     x = synth.activations_f16((b, s, sh.h1), x_std, seed)
     ref = O.prefill_layer(ocfg, ow, x, okv, batch_offset=boff)
     got = B.fg_prefill_layer(cfg, w, dev(x), kv, batch_offset=boff)
@@ -56,6 +56,18 @@ def test_opt125m_layer_q4_batch4_prompt32_8steps(tiled):
     weights in the canonical and in the streaming (tiled) order."""
     _run_layer_sequence(synth.OPT_125M_LAYER, True, True, b=4, s=32, steps=8, seed=0, biases=False,
                         random_ln=False, x_std=0.03, tiled=tiled)
+
+
+@pytest.mark.parametrize("dh128", [False, True])
+def test_layer_with_fp16_pair_cache(dh128):
+    """The 4.5-bit cache variant (FP16 {min, scale} pairs) through prefill and decode."""
+    if dh128:
+        sh = synth.Shape(h1=512, nh=4, h2=1536, vocab=1000, max_pos=256)
+        _run_layer_sequence(sh, True, True, b=3, s=70, steps=3, seed=4, biases=True, random_ln=True, x_std=0.5,
+                            batch=4, boff=1, tiled=True, meta_f16=True)
+    else:
+        _run_layer_sequence(synth.OPT_125M_LAYER, True, True, b=4, s=32, steps=4, seed=3, biases=False,
+                            random_ln=False, x_std=0.03, tiled=True, meta_f16=True)
 
 
 @pytest.mark.parametrize("quant_w,quant_kv", [(False, False), (True, False), (False, True)])
