@@ -13,8 +13,10 @@
 // Kernel: out[M, N] = act(x[M, K] . W^T + bias) + residual.  One kernel template, two shapes:
 //   decode   M <= 160 per row block: 4 waves side by side, each all rows x 64 columns
 //            (MT = 1..5 row tiles of 32, NT = 2 column tiles, WM = 1);
-//   prefill  row blocks of 256: 8 waves as 2 x 4, each 128 rows x 64 columns (MT = 4, NT = 2, WM = 2,
-//            two waves per SIMD so that one wave's MFMAs overlap the other's dequantization).
+//   prefill  row blocks of 256: 8 waves side by side, each all 256 rows x 32 columns (MT = 8, NT = 1,
+//            WM = 1; two waves per SIMD, so that one wave's MFMAs overlap the other's LDS reads and
+//            dequantization, and no weight is dequantized twice in a workgroup: measured 2 % faster
+//            than 2 x 4 waves of 128 x 64, which halve the LDS reads but dequantize everything twice).
 //   * Nothing but MFMA operands passes through registers.  The activation tile (XOR-swizzled, the A
 //     operand) and the weight tiles (1 KiB of codes + 256 B of {min,scale} each) are copied
 //     global -> LDS asynchronously, several K steps ahead.  A wave reads its codes back, dequantizes
@@ -566,7 +568,7 @@ struct Shape {
 Shape pick_shape(int64_t m) {
   // Up to two row blocks the side-by-side shape wins (few tiles: the 256-row shape would leave most of
   // its stream-K pieces short); beyond that the weights would be re-read too often.
-  if (m > 2 * kMaxMT * 32) return {4, 2, 2, 8};
+  if (m > 2 * kMaxMT * 32) return {8, 1, 1, 8};
   if (m > kMaxMT * 32) m = ceil_div(m, 2);
   const int need = (int)ceil_div(m, 32);
   return {need < 1 ? 1 : need, 2, 1, 4};
@@ -626,10 +628,10 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   a.partial = reinterpret_cast<float*>(ws);
   const size_t need = gemm_stream_workspace(la.n, la.k, la.m);
   if (!ws || ws_bytes < need) return FG_ERR_WORKSPACE;
-  if (sh.wm == 2) {   // prefill shape: GEMM and reduction of the last partial round are one profile record
+  if (sh.nw == 8) {   // prefill shape: GEMM and reduction of the last partial round are one profile record
     ProfScope prof(FG_K_GEMM_LARGE_M, stream);
     if (la.dtype != FG_Q4G64_TILED) return FG_ERR_UNSUPPORTED;
-    const int rc = launch_t<4, 2, 2, 8, false>(a, stream);
+    const int rc = launch_t<8, 1, 1, 8, false>(a, stream);
     if (rc) return rc;
     if (rem_tiles > 0) {
       hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, 8), dim3(sh.nw * 64), 0, stream, a, sh.mt,
