@@ -39,6 +39,7 @@ constexpr int kBStageF16 = kBN * kKS * 2;     // FP16 weights: 256 rows of 128 b
 constexpr int kMaxMT = 5;     // decode shape: up to 5 row tiles of 32 (160 rows)
 constexpr int kGroupM = 8;    // row blocks per group in the tile walk
 constexpr int kLdsBytes = 160 * 1024;
+constexpr int kFinishItems = 8;   // float4 items per thread of the reduction pass
 
 struct StreamArgs {
   const uint8_t* w;     // tiled codes
@@ -503,29 +504,45 @@ __global__ __launch_bounds__(512) void gemm_stream_finish_kernel(StreamArgs a, i
   const int64_t slot = (int64_t)rows_t * kBN;
   const int tid = threadIdx.x, wave = tid >> 6, l32 = tid & 31, kb = (tid >> 5) & 1;
   const int wm = wave / wn_n, wn = wave - wm * wn_n;
-  for (int e = blockIdx.y; e < mt * nt * 4; e += gridDim.y) {   // e = (m*nt + j)*4 + q
+  // this thread's float4 items e = blockIdx.y + i * gridDim.y, e = (m*nt + j)*4 + q; the launch keeps
+  // their number within kFinishItems.  Contributors outermost, so that the loads of one contributor
+  // for all items are in flight together; the sum still runs in ascending K order per item.
+  const int n_items = mt * nt * 4;
+  float4 v[kFinishItems];
+#pragma unroll
+  for (int i = 0; i < kFinishItems; ++i) v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int p = p_lo; p <= p_hi; ++p) {
+    const int64_t pb = work_begin(a.rem_work, a.grid, p);
+    if (work_begin(a.rem_work, a.grid, p + 1) == pb) continue;
+    const int s = pb >= w0 ? 0 : 1;
+    const float4* src = reinterpret_cast<const float4*>(a.partial + ((int64_t)p * 2 + s) * slot) + tid;
+#pragma unroll
+    for (int i = 0; i < kFinishItems; ++i) {
+      const int e = blockIdx.y + i * gridDim.y;
+      if (e < n_items) {
+        const float4 x = src[(int64_t)e * nthr];
+        v[i].x += x.x;
+        v[i].y += x.y;
+        v[i].z += x.z;
+        v[i].w += x.w;
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < kFinishItems; ++i) {
+    const int e = blockIdx.y + i * gridDim.y;
+    if (e >= n_items) break;
     const int q = e & 3, mj = e >> 2, m = mj / nt, j = mj - m * nt;
     const int row0 = m0 + (wm * mt + m) * 32 + q * 8 + kb * 4;
     const int col = n_tile * kBN + (wn * nt + j) * 32 + l32;
     if (row0 >= a.M || col >= a.N) continue;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int p = p_lo; p <= p_hi; ++p) {
-      const int64_t pb = work_begin(a.rem_work, a.grid, p);
-      if (work_begin(a.rem_work, a.grid, p + 1) == pb) continue;
-      const int s = pb >= w0 ? 0 : 1;
-      const float4 x = reinterpret_cast<const float4*>(a.partial + ((int64_t)p * 2 + s) * slot)[e * nthr + tid];
-      v.x += x.x;
-      v.y += x.y;
-      v.z += x.z;
-      v.w += x.w;
-    }
-    const float o[4] = {v.x, v.y, v.z, v.w};
+    const float o[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
     const float bvv = a.bias ? (float)a.bias[col] : 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = row0 + i;
+    for (int r = 0; r < 4; ++r) {
+      const int row = row0 + r;
       if (row >= a.M) break;
-      float x = o[i] + bvv;
+      float x = o[r] + bvv;
       if (a.relu) x = fmaxf(x, 0.f);
       if (a.residual) x += (float)a.residual[(int64_t)row * a.ldr + col];
       if (a.out32)
@@ -657,7 +674,7 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   }
   if (rem_tiles > 0) {
     ProfScope prof(FG_K_GEMM_SMALL_M_FINISH, stream);
-    hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, sh.mt * sh.nt >= 6 ? 8 : 4),
+    hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, sh.mt * sh.nt >= 4 ? 8 : 4),
                        dim3(sh.nw * 64), 0, stream, a, sh.mt, sh.nt, sh.wm);
     FG_LAUNCH_CHECK();
   }
