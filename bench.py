@@ -37,6 +37,8 @@ WORKLOADS = {
     "opt175b_q4_512_8": ("OPT_175B", True, True, 4, 36, 512, 8),
     # the 4.5-bit cache variant: FP16 {min, scale} pairs (10 % fewer KV bytes per step)
     "opt175b_q4_h16kv": ("OPT_175B", True, "h16", 4, 36, 512, 32),
+    # ... and with the weights' pairs in FP16 as well: 4.5 bits per stored element everywhere
+    "opt175b_q4_h16": ("OPT_175B", "h16", "h16", 4, 36, 512, 32),
     "kv_stress_175b_layer_h16kv": ("OPT_175B", True, "h16", 1, 512, 2048, 64),
     "opt30b_q4": ("OPT_30B", True, True, 8, 32, 512, 32),
     "opt6.7b_f16": ("OPT_6_7B", False, False, 4, 32, 512, 32),
@@ -64,7 +66,7 @@ def build_model(sh, wq, seed, torch, B, embeddings=True):
         w = torch.empty((rows, cols), dtype=torch.float16, device="cuda")
         w.normal_(0.0, 0.02, generator=g)
         # 4-bit matrices go into the tiled streaming layout (same bytes, repacked once at load time)
-        m = B.Mat.from_f16(w, wq, tiled=wq)
+        m = B.Mat.from_f16(w, bool(wq), tiled=bool(wq), meta_f16=wq == "h16")
         return m
 
     for j in range(sh.l):
@@ -96,7 +98,7 @@ def cpu_baseline(sh, wq, kvq, s, n, budget_s=25.0):
     rng = np.random.default_rng(0)
     f16 = lambda shape, std: (rng.standard_normal(shape, dtype=np.float32) * np.float32(std)).astype(np.float16)
     slabs = {"wqkv": (3 * h1, h1), "wo": (h1, h1), "w1": (h2, h1), "w2": (h1, h2)}
-    mats = {k: O.Mat.from_f16(f16((min(slab, r), c), 0.02), wq) for k, (r, c) in slabs.items()}
+    mats = {k: O.Mat.from_f16(f16((min(slab, r), c), 0.02), bool(wq), wq == "h16") for k, (r, c) in slabs.items()}
     kv = O.KVCache.empty(b, nh, rows + 1, dh, bool(kvq), kvq == "h16")
     kv.store(0, 0, f16((b, rows, h1), 1.0), f16((b, rows, h1), 1.0))
     x = f16((b, h1), 1.0)
@@ -338,7 +340,7 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": args.workload + ("" if not args.layers else "_%dlayers" % args.layers),
                    "shape": {"l": sh.l, "h1": sh.h1, "nh": sh.nh, "h2": sh.h2, "vocab": sh.vocab},
-                   "weights": "q4g64" if wq else "f16", "kv_cache": "q4g64_h16" if kvq == "h16" else ("q4g64" if kvq else "f16"),
+                   "weights": "q4g64_h16" if wq == "h16" else ("q4g64" if wq else "f16"), "kv_cache": "q4g64_h16" if kvq == "h16" else ("q4g64" if kvq else "f16"),
                    "block": "%dx%d" % (ngb, gbs), "prompt_len": s, "gen_len": n,
                    "resident_gb": resident / 1e9, "setup_s": t_setup},
         "prefill_s": prefill_s, "decode_s": decode_s, "decode": decode,

@@ -33,12 +33,16 @@
  *             per (row r, half h of the group) at offset 16*(32*h + r); tiles of one row block
  *             follow each other along the input dimension, row blocks follow each other; meta has
  *             32 pairs per tile in the same tile order.  Same size as FG_Q4G64.
- *   FG_Q4G64_H16  (KV caches only) the 4.5-bit variant: as FG_Q4G64, but the pair is stored as two
+ *   FG_Q4G64_H16  the 4.5-bit variant (KV caches; weights only as the input of fg_pack_weights): as
+ *             FG_Q4G64, but the pair is stored as two
  *             FP16 numbers {min, scale}, 4 bytes per group.  min is stored exactly (the inputs are
  *             FP16); scale is the smallest FP16 number >= (max-min)/15, and the codes are computed
  *             with that stored scale, so they lie in [0, 15] without clamping and every element is
  *             within scale/2 of min + code*scale; the maximum no longer round-trips exactly.
  *             0.5625 bytes per element.
+ *   FG_Q4G64_H16_TILED  FG_Q4G64_H16 weights in the tile order of FG_Q4G64_TILED (32 pairs of 4 bytes
+ *             per tile); made by fg_pack_weights.  Dequantized like FG_Q4G64 weights: the FP16 number
+ *             nearest to min + code*scale with the stored FP16 min and scale.
  */
 #ifndef FG_H
 #define FG_H
@@ -59,13 +63,15 @@ typedef enum {
   FG_ERR_DEVICE = -5       /* a HIP runtime call failed (see fg_last_device_error) */
 } fg_status;
 
-typedef enum { FG_F16 = 0, FG_Q4G64 = 1, FG_Q4G64_TILED = 2, FG_Q4G64_H16 = 3 } fg_dtype;
+typedef enum { FG_F16 = 0, FG_Q4G64 = 1, FG_Q4G64_TILED = 2, FG_Q4G64_H16 = 3, FG_Q4G64_H16_TILED = 4 } fg_dtype;
 
 /* A weight matrix [rows = output features, cols = input features], row-major.
  * FG_F16:   data = FP16 values, meta = NULL.
  * FG_Q4G64: data = packed codes (rows*cols/2 bytes), meta = rows*cols/64 {min,scale} pairs;
  *           groups run along cols (the contraction dimension); cols % 64 == 0.
- * FG_Q4G64_TILED: the same bytes in the streaming order described above. */
+ * FG_Q4G64_TILED: the same bytes in the streaming order described above.
+ * FG_Q4G64_H16_TILED: likewise with rows*cols/64 FP16 pairs (4 bytes each).  A canonical FG_Q4G64_H16
+ *           matrix (codes as FG_Q4G64, FP16 pairs) is accepted by fg_pack_weights only. */
 typedef struct {
   const void* data;
   const void* meta;
@@ -135,8 +141,9 @@ int fg_quantize_groupwise(const void* x_f16, int64_t rows, int64_t cols, int gro
 int fg_quantize_groupwise_h16(const void* x_f16, int64_t rows, int64_t cols, int group, int bits,
                               void* codes_out, void* meta_out_f16, void* stream);
 
-/* Reorder a canonical FG_Q4G64 matrix into FG_Q4G64_TILED (same byte counts: rows*cols/2 and
- * rows*cols/64*8).  src->rows % 32 == 0.  Done once per weight matrix, e.g. at load time. */
+/* Reorder a canonical FG_Q4G64 matrix into FG_Q4G64_TILED, or a canonical FG_Q4G64_H16 one into
+ * FG_Q4G64_H16_TILED (same byte counts as the source: rows*cols/2 codes and rows*cols/64 pairs of 8
+ * or 4 bytes).  src->rows % 32 == 0.  Done once per weight matrix, e.g. at load time. */
 int fg_pack_weights(const fg_mat* src, void* data_out, void* meta_out, void* stream);
 
 /* Inverse map of Section 5 (stored 4-bit -> values before computation): out_f32[r][c] =

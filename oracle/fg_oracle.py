@@ -198,14 +198,14 @@ class Mat:
     cols: int
     f16: Optional[np.ndarray] = None      # [rows, cols] float16
     codes: Optional[np.ndarray] = None    # [rows, cols/2] uint8
-    meta: Optional[np.ndarray] = None     # [rows, cols/64, 2] float32
+    meta: Optional[np.ndarray] = None     # [rows, cols/64, 2] float32 (float16: the FP16-pair variant)
 
     @staticmethod
-    def from_f16(w16: np.ndarray, quantized: bool) -> "Mat":
+    def from_f16(w16: np.ndarray, quantized: bool, meta_f16: bool = False) -> "Mat":
         w16 = np.ascontiguousarray(w16, dtype=np.float16)
         r, c = w16.shape
         if quantized:
-            codes, meta = quantize_groupwise(w16)
+            codes, meta = quantize_groupwise_h16(w16) if meta_f16 else quantize_groupwise(w16)
             return Mat(r, c, codes=codes, meta=meta)
         return Mat(r, c, f16=w16)
 

@@ -14,7 +14,7 @@ import torch
 
 FG_OK = 0
 FG_ERR_NULL, FG_ERR_SHAPE, FG_ERR_UNSUPPORTED, FG_ERR_WORKSPACE, FG_ERR_DEVICE = -1, -2, -3, -4, -5
-FG_F16, FG_Q4G64, FG_Q4G64_TILED, FG_Q4G64_H16 = 0, 1, 2, 3
+FG_F16, FG_Q4G64, FG_Q4G64_TILED, FG_Q4G64_H16, FG_Q4G64_H16_TILED = 0, 1, 2, 3, 4
 KERNEL_CLASSES = ["quantize", "dequantize", "layernorm", "gemm_small_m", "gemm_small_m_finish", "gemm_large_m",
                   "kv_append", "attn_decode", "attn_prefill", "embed", "argmax"]
 
@@ -155,26 +155,27 @@ class Mat:
         self.c = fg_mat(_p(data), _p(meta), dtype, 0, rows, cols)
 
     @staticmethod
-    def from_f16(w: torch.Tensor, quantize: bool, tiled: bool = False) -> "Mat":
+    def from_f16(w: torch.Tensor, quantize: bool, tiled: bool = False, meta_f16: bool = False) -> "Mat":
         """quantize: store as 4-bit groups of 64 (quantized on the GPU); tiled: additionally reorder
-        into the streaming layout with fg_pack_weights (rows must be a multiple of 32)."""
+        into the streaming layout with fg_pack_weights (rows must be a multiple of 32); meta_f16: the
+        {min, scale} pairs are FP16 (only the tiled form of such a matrix can be multiplied)."""
         w = _f16(w)
         r, c = w.shape
         if quantize:
-            codes, meta = fg_quantize_groupwise(w)
-            m = Mat(r, c, FG_Q4G64, codes, meta)
+            codes, meta = fg_quantize_groupwise(w, meta_f16=meta_f16)
+            m = Mat(r, c, FG_Q4G64_H16 if meta_f16 else FG_Q4G64, codes, meta)
             return m.tiled() if tiled else m
         return Mat(r, c, FG_F16, w, None)
 
     def tiled(self) -> "Mat":
-        assert self.dtype == FG_Q4G64
+        assert self.dtype in (FG_Q4G64, FG_Q4G64_H16)
         data = torch.empty_like(self.data)
         meta = torch.empty_like(self.meta)
         _check(lib().fg_pack_weights(C.byref(self.c), _p(data), _p(meta), _stream()), "fg_pack_weights")
-        return Mat(self.rows, self.cols, FG_Q4G64_TILED, data, meta)
+        return Mat(self.rows, self.cols, FG_Q4G64_TILED if self.dtype == FG_Q4G64 else FG_Q4G64_H16_TILED, data, meta)
 
     def nbytes(self) -> int:
-        return self.data.numel() * self.data.element_size() + (0 if self.meta is None else self.meta.numel() * 4)
+        return self.data.numel() * self.data.element_size() + (0 if self.meta is None else self.meta.numel() * self.meta.element_size())
 
 
 class Cfg:
@@ -193,10 +194,10 @@ class LayerWeights:
                                   _p(ln2_g), _p(ln2_b))
 
     @staticmethod
-    def from_numpy(t: Dict, quantize: bool, device="cuda", tiled: bool = False) -> "LayerWeights":
+    def from_numpy(t: Dict, quantize: bool, device="cuda", tiled: bool = False, meta_f16: bool = False) -> "LayerWeights":
         """t: FP16 numpy tensors as made by synth.layer_tensors; weights are quantized on the GPU."""
         d = lambda a: None if a is None else torch.from_numpy(a).to(device)
-        mk = lambda a: Mat.from_f16(d(a), quantize, tiled)
+        mk = lambda a: Mat.from_f16(d(a), quantize, tiled, meta_f16 and quantize)
         return LayerWeights(mk(t["wqkv"]), mk(t["wo"]), mk(t["w1"]), mk(t["w2"]),
                             d(t["ln1_g"]), d(t["ln1_b"]), d(t["ln2_g"]), d(t["ln2_b"]),
                             d(t.get("bqkv")), d(t.get("bo")), d(t.get("b1")), d(t.get("b2")))

@@ -83,7 +83,7 @@ int gemm_large_m_launch(const LinearArgs& a, hipStream_t stream);
 // tiled 4-bit weights: weight-streaming kernel for few rows, and the repacking kernel
 size_t gemm_stream_workspace(int64_t n, int64_t k, int64_t m);
 int gemm_stream_launch(const LinearArgs& a, void* ws, size_t ws_bytes, hipStream_t stream);
-int pack_weights_launch(const void* codes, const void* meta, int64_t n, int64_t k, void* codes_out, void* meta_out,
+int pack_weights_launch(const void* codes, const void* meta, bool meta_f16, int64_t n, int64_t k, void* codes_out, void* meta_out,
                         hipStream_t stream);
 
 int layernorm_launch(const half_t* x, int64_t ldx, const half_t* g, const half_t* b, int64_t rows,
@@ -104,7 +104,7 @@ int prefill_attention_launch(const fg_model_cfg& cfg, const half_t* qkv, int32_t
 
 // validation helpers (host only)
 int check_cfg(const fg_model_cfg* cfg);
-int check_mat(const fg_mat* w);
+int check_mat(const fg_mat* w, bool for_pack = false);
 int check_kv(const fg_model_cfg* cfg, const fg_kv_cache* kv);
 
 // ---- device helpers -------------------------------------------------------------------------

@@ -95,6 +95,12 @@ __device__ __forceinline__ float2 lds_read64(uint32_t addr) {
   __asm__ volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
   return r;
 }
+template <int OFF>
+__device__ __forceinline__ uint32_t lds_read32(uint32_t addr) {
+  uint32_t r;
+  __asm__ volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+  return r;
+}
 // all ds_reads issued so far have landed
 __device__ __forceinline__ void lds_wait() { __asm__ volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 // makes later uses of v depend on a point after the preceding lds_wait()
@@ -133,7 +139,10 @@ struct StreamCfg {
   static_assert(kNST >= 3, "needs three stages");
 };
 
-template <int MT, int NT, int WM, int NW, bool F16W>
+// H16M: the {min, scale} pairs of the tiled 4-bit weights are two FP16 numbers (4 bytes) instead of two
+// binary32 numbers; a tile's 32 pairs then fill half of its 256-byte slot of the stage (the copy stays
+// wave-wide: lanes 32..63 fetch the same pairs again into the other half).
+template <int MT, int NT, int WM, int NW, bool F16W, bool H16M = false>
 __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
   using C = StreamCfg<MT, NT, WM, NW, F16W>;
   constexpr int kWN = C::kWN, kAStage = C::kAStage, kStageBytes = C::kStageBytes, kNST = C::kNST;
@@ -162,7 +171,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
   for (int kk = 0; kk < 4; ++kk) a_off[kk] = ((wm * MT * 32 + l32) * kKS + swz(l32, 4 * kb + kk) * 8) * 2;
   // this wave's weight tiles inside a stage
   const int bq_off = kAStage + wn * NT * 1024 + lane * 16;           // + j * 1024
-  const int bm_off = kAStage + 8 * 1024 + wn * NT * 256 + l32 * 8;   // + j * 256
+  const int bm_off = kAStage + 8 * 1024 + wn * NT * 256 + l32 * (H16M ? 4 : 8);   // + j * 256
   // FP16 weights: operand offsets like a_off, for this wave's first column tile
   int b_off[4];
 #pragma unroll
@@ -223,7 +232,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
         int nt = n_tile * 8 + wave * kBT + j;
         nt = nt < a.n32 ? nt : a.n32 - 1;   // ragged last column block: load valid data, never store it
         w_src[j] = a.w + (int64_t)nt * a.ksteps * 1024 + lane * 16;
-        m_src[j] = reinterpret_cast<const float*>(a.meta) + (int64_t)nt * a.ksteps * 64 + lane;
+        m_src[j] = reinterpret_cast<const float*>(a.meta) + (H16M ? (int64_t)nt * a.ksteps * 32 + l32
+                                                                  : (int64_t)nt * a.ksteps * 64 + lane);
       }
     }
 
@@ -245,18 +255,19 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
           __builtin_amdgcn_global_load_lds((gptr_t)(w_src[j] + (int64_t)kc * 1024),
                                            (lptr_t)(st + kAStage + (wave * kBT + j) * 1024), 16, 0, 0);
         else
-          __builtin_amdgcn_global_load_lds((gptr_t)(m_src[j] + (int64_t)kc * 64),
+          __builtin_amdgcn_global_load_lds((gptr_t)(m_src[j] + (int64_t)kc * (H16M ? 32 : 64)),
                                            (lptr_t)(st + kAStage + 8 * 1024 + (wave * kBT + j) * 256), 4, 0, 0);
       }
     };
     u4_t cq[NT];
     float2 cm[NT];
+    uint32_t cmh[NT];   // H16M: the pair as stored
     auto read_b = [&](int stage) {
       const uint32_t st = lds0 + stage * kStageBytes;
       static_for<0, NT>([&](auto J) __attribute__((always_inline)) {
         constexpr int j = decltype(J)::value;
         cq[j] = lds_read128<j * 1024>(st + bq_off);
-        cm[j] = lds_read64<j * 256>(st + bm_off);
+        if constexpr (H16M) cmh[j] = lds_read32<j * 256>(st + bm_off); else cm[j] = lds_read64<j * 256>(st + bm_off);
       });
     };
     // operand slice kk of this wave's MT row tiles of a stage
@@ -308,6 +319,11 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
     auto set_meta = [&]() {
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
+        if constexpr (H16M) {
+          const h2_t pr = __builtin_bit_cast(h2_t, cmh[j]);
+          cm[j].x = (float)pr.x;
+          cm[j].y = (float)pr.y;
+        }
         s24[j] = cm[j].y * 16777216.0f;
         s20[j] = cm[j].y * 1048576.0f;
         mn[j] = cm[j].x;
@@ -317,7 +333,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         lds_landed(cq[j]);
-        lds_landed(cm[j]);
+        if constexpr (H16M) lds_landed(cmh[j]); else lds_landed(cm[j]);
       }
     };
 
@@ -554,10 +570,11 @@ __global__ __launch_bounds__(512) void gemm_stream_finish_kernel(StreamArgs a, i
 }
 
 // canonical [N][K/2] codes + [N][K/64] meta  ->  tiled: one thread per 16-byte piece
+template <class PairT>   // float2, or uint32_t for a pair of FP16 numbers
 __global__ __launch_bounds__(256) void pack_weights_kernel(const uint8_t* __restrict__ codes,
-                                                           const float2* __restrict__ meta, int N, int K,
+                                                           const PairT* __restrict__ meta, int N, int K,
                                                            uint8_t* __restrict__ codes_out,
-                                                           float2* __restrict__ meta_out) {
+                                                           PairT* __restrict__ meta_out) {
   const int ksteps = K >> 6;
   const int64_t pieces = (int64_t)N * ksteps * 2;   // 16-byte pieces
   int64_t id = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -591,17 +608,17 @@ Shape pick_shape(int64_t m) {
   return {need < 1 ? 1 : need, 2, 1, 4};
 }
 
-template <int MT, int NT, int WM, int NW, bool F16W>
+template <int MT, int NT, int WM, int NW, bool F16W, bool H16M = false>
 int launch_t(const StreamArgs& a, hipStream_t stream) {
   using C = StreamCfg<MT, NT, WM, NW, F16W>;
   const size_t smem = (size_t)C::kNST * C::kStageBytes;
   static bool attr_done = false;
   if (!attr_done) {
-    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MT, NT, WM, NW, F16W>),
+    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_stream_kernel<MT, NT, WM, NW, F16W, H16M>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     attr_done = true;
   }
-  hipLaunchKernelGGL((gemm_stream_kernel<MT, NT, WM, NW, F16W>), dim3(a.grid), dim3(NW * 64), smem, stream, a);
+  hipLaunchKernelGGL((gemm_stream_kernel<MT, NT, WM, NW, F16W, H16M>), dim3(a.grid), dim3(NW * 64), smem, stream, a);
   FG_LAUNCH_CHECK();
   return FG_OK;
 }
@@ -647,8 +664,9 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   if (!ws || ws_bytes < need) return FG_ERR_WORKSPACE;
   if (sh.nw == 8) {   // prefill shape: GEMM and reduction of the last partial round are one profile record
     ProfScope prof(FG_K_GEMM_LARGE_M, stream);
-    if (la.dtype != FG_Q4G64_TILED) return FG_ERR_UNSUPPORTED;
-    const int rc = launch_t<8, 1, 1, 8, false>(a, stream);
+    if (la.dtype != FG_Q4G64_TILED && la.dtype != FG_Q4G64_H16_TILED) return FG_ERR_UNSUPPORTED;
+    const int rc = la.dtype == FG_Q4G64_H16_TILED ? launch_t<8, 1, 1, 8, false, true>(a, stream)
+                                                  : launch_t<8, 1, 1, 8, false>(a, stream);
     if (rc) return rc;
     if (rem_tiles > 0) {
       hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, 8), dim3(sh.nw * 64), 0, stream, a, sh.mt,
@@ -660,16 +678,21 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   {
     ProfScope prof(FG_K_GEMM_SMALL_M, stream);
     int rc = FG_ERR_UNSUPPORTED;
-    const bool f16w = la.dtype == FG_F16;
-    {
-      switch (sh.mt) {
-        case 1: rc = f16w ? launch_t<1, 2, 1, 4, true>(a, stream) : launch_t<1, 2, 1, 4, false>(a, stream); break;
-        case 2: rc = f16w ? launch_t<2, 2, 1, 4, true>(a, stream) : launch_t<2, 2, 1, 4, false>(a, stream); break;
-        case 3: rc = f16w ? launch_t<3, 2, 1, 4, true>(a, stream) : launch_t<3, 2, 1, 4, false>(a, stream); break;
-        case 4: rc = f16w ? launch_t<4, 2, 1, 4, true>(a, stream) : launch_t<4, 2, 1, 4, false>(a, stream); break;
-        case 5: rc = f16w ? launch_t<5, 2, 1, 4, true>(a, stream) : launch_t<5, 2, 1, 4, false>(a, stream); break;
-      }
+    const bool f16w = la.dtype == FG_F16, h16m = la.dtype == FG_Q4G64_H16_TILED;
+#define FG_STREAM_CASE(MT)                                                     \
+  case MT:                                                                     \
+    rc = f16w   ? launch_t<MT, 2, 1, 4, true>(a, stream)                       \
+         : h16m ? launch_t<MT, 2, 1, 4, false, true>(a, stream)                \
+                : launch_t<MT, 2, 1, 4, false>(a, stream);                     \
+    break;
+    switch (sh.mt) {
+      FG_STREAM_CASE(1)
+      FG_STREAM_CASE(2)
+      FG_STREAM_CASE(3)
+      FG_STREAM_CASE(4)
+      FG_STREAM_CASE(5)
     }
+#undef FG_STREAM_CASE
     if (rc) return rc;
   }
   if (rem_tiles > 0) {
@@ -681,15 +704,20 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   return FG_OK;
 }
 
-int pack_weights_launch(const void* codes, const void* meta, int64_t n, int64_t k, void* codes_out, void* meta_out,
-                        hipStream_t stream) {
+int pack_weights_launch(const void* codes, const void* meta, bool meta_f16, int64_t n, int64_t k, void* codes_out,
+                        void* meta_out, hipStream_t stream) {
   const int64_t pieces = n * (k / 64) * 2;
   int64_t blocks = ceil_div(pieces, 256);
   if (blocks > 256 * 64) blocks = 256 * 64;
   ProfScope prof(FG_K_QUANTIZE, stream);
-  hipLaunchKernelGGL(pack_weights_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
-                     reinterpret_cast<const uint8_t*>(codes), reinterpret_cast<const float2*>(meta), (int)n, (int)k,
-                     reinterpret_cast<uint8_t*>(codes_out), reinterpret_cast<float2*>(meta_out));
+  if (meta_f16)
+    hipLaunchKernelGGL(pack_weights_kernel<uint32_t>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       reinterpret_cast<const uint8_t*>(codes), reinterpret_cast<const uint32_t*>(meta), (int)n, (int)k,
+                       reinterpret_cast<uint8_t*>(codes_out), reinterpret_cast<uint32_t*>(meta_out));
+  else
+    hipLaunchKernelGGL(pack_weights_kernel<float2>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                       reinterpret_cast<const uint8_t*>(codes), reinterpret_cast<const float2*>(meta), (int)n, (int)k,
+                       reinterpret_cast<uint8_t*>(codes_out), reinterpret_cast<float2*>(meta_out));
   FG_LAUNCH_CHECK();
   return FG_OK;
 }

@@ -60,10 +60,13 @@ int check_cfg(const fg_model_cfg* c) {
   return FG_OK;
 }
 
-int check_mat(const fg_mat* w) {
-  if (w->dtype != FG_F16 && w->dtype != FG_Q4G64 && w->dtype != FG_Q4G64_TILED) return FG_ERR_UNSUPPORTED;
+// for_pack: also accept the canonical FP16-pair form, which only fg_pack_weights consumes
+int check_mat(const fg_mat* w, bool for_pack) {
+  const bool tiled = w->dtype == FG_Q4G64_TILED || w->dtype == FG_Q4G64_H16_TILED;
+  if (w->dtype != FG_F16 && w->dtype != FG_Q4G64 && !tiled && !(for_pack && w->dtype == FG_Q4G64_H16))
+    return FG_ERR_UNSUPPORTED;
   if (w->rows <= 0 || w->cols <= 0 || w->cols % kGroup != 0 || w->rows % 8 != 0) return FG_ERR_SHAPE;
-  if (w->dtype == FG_Q4G64_TILED && w->rows % 32 != 0) return FG_ERR_SHAPE;
+  if (tiled && w->rows % 32 != 0) return FG_ERR_SHAPE;
   if (w->rows > 0x7fffffff || w->cols > 0x7fffffff) return FG_ERR_SHAPE;
   if (!w->data) return FG_ERR_NULL;
   if (w->dtype != FG_F16 && !w->meta) return FG_ERR_NULL;
@@ -102,7 +105,7 @@ static const int64_t kSmallMLimit = 512;   // rows up to which the weight-stream
 // Tiled 4-bit weights always take the stream kernels; row-major FP16 weights take them for up to two
 // row blocks (the decode phase and the LM head), where the kernel is a pure weight streamer.
 static bool use_stream(int dtype, int64_t n, int64_t m) {
-  if (dtype == FG_Q4G64_TILED) return true;
+  if (dtype == FG_Q4G64_TILED || dtype == FG_Q4G64_H16_TILED) return true;
   return dtype == FG_F16 && m <= 320 && n % 32 == 0;
 }
 
@@ -324,13 +327,14 @@ extern "C" int fg_profile_read(int k, double* total_ms, int64_t* launches) {
 
 extern "C" int fg_pack_weights(const fg_mat* src, void* data_out, void* meta_out, void* stream) {
   if (!src) return FG_ERR_NULL;
-  int rc = check_mat(src);
+  int rc = check_mat(src, true);
   if (rc) return rc;
-  if (src->dtype != FG_Q4G64) return FG_ERR_UNSUPPORTED;
+  if (src->dtype != FG_Q4G64 && src->dtype != FG_Q4G64_H16) return FG_ERR_UNSUPPORTED;
   if (src->rows % 32 != 0) return FG_ERR_SHAPE;
   if (!data_out || !meta_out) return FG_ERR_NULL;
   if (!aligned16(data_out) || !aligned16(meta_out)) return FG_ERR_SHAPE;
-  return pack_weights_launch(src->data, src->meta, src->rows, src->cols, data_out, meta_out, as_stream(stream));
+  return pack_weights_launch(src->data, src->meta, src->dtype == FG_Q4G64_H16, src->rows, src->cols, data_out,
+                             meta_out, as_stream(stream));
 }
 
 extern "C" size_t fg_linear_workspace_bytes(const fg_mat* w, int64_t m) {
@@ -574,7 +578,8 @@ extern "C" int fg_generate(const fg_model_cfg* cfg, int32_t l, const fg_layer_we
     stats->tokens = (int64_t)bls * n;
     auto mat_bytes = [](const fg_mat& m) -> int64_t {
       const int64_t e = m.rows * m.cols;
-      return m.dtype != FG_F16 ? e / 2 + e / kGroup * 8 : e * 2;
+      if (m.dtype == FG_F16) return e * 2;
+      return e / 2 + e / kGroup * (m.dtype == FG_Q4G64_H16_TILED ? 4 : 8);
     };
     int64_t wb = 0;
     for (int j = 0; j < l; ++j)

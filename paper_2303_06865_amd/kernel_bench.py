@@ -51,8 +51,8 @@ def main(argv=None):
     ap.add_argument("--m", type=int, default=144)
     ap.add_argument("--n", type=int, default=36864)
     ap.add_argument("--k", type=int, default=12288)
-    ap.add_argument("--wdtype", choices=["f16", "q4", "q4t"], default="q4t",
-                    help="weight storage: FP16, 4-bit canonical, 4-bit tiled")
+    ap.add_argument("--wdtype", choices=["f16", "q4", "q4t", "q4th"], default="q4t",
+                    help="weight storage: FP16, 4-bit canonical, 4-bit tiled, 4-bit tiled with FP16 pairs")
     ap.add_argument("--batch", type=int, default=144)
     ap.add_argument("--nh", type=int, default=96)
     ap.add_argument("--dh", type=int, default=128)
@@ -70,11 +70,11 @@ def main(argv=None):
     out = {"op": a.op}
     if a.op == "linear":
         w = torch.randn(a.n, a.k, device=dev, dtype=torch.float16) * 0.02
-        mat = B.Mat.from_f16(w, a.wdtype != "f16", tiled=a.wdtype == "q4t")
+        mat = B.Mat.from_f16(w, a.wdtype != "f16", tiled=a.wdtype in ("q4t", "q4th"), meta_f16=a.wdtype == "q4th")
         del w
         x = torch.randn(a.m, a.k, device=dev, dtype=torch.float16)
         out.update(m=a.m, n=a.n, k=a.k, wdtype=a.wdtype,
-                   bytes=int(a.n * a.k * (2 if a.wdtype == "f16" else 0.625)), flops=2 * a.m * a.n * a.k)
+                   bytes=int(a.n * a.k * {"f16": 2, "q4th": 0.5625}.get(a.wdtype, 0.625)), flops=2 * a.m * a.n * a.k)
         out["classes"] = _time_classes(lambda: B.fg_linear(mat, None, x), a.iters, a.warmup)
     elif a.op in ("attn_decode", "attn_decode_topk"):
         h1 = a.nh * a.dh

@@ -43,6 +43,8 @@ FULL_LINEAR = [
     (18432, 36864, 12288, True),
     (18432, 12288, 49152, True),
     (144, 50272, 12288, False),
+    (144, 36864, 12288, "h16"),      # 4-bit weights with FP16 {min, scale} pairs
+    (18432, 12288, 49152, "h16"),
 ]
 
 
@@ -52,18 +54,21 @@ def test_linear_full_size_sampled(m, n, k, quant):
     x = _gen((m, k), 1.0, 2000 + m)
     res = _gen((m, n), 1.0, 3000 + m)
     bias = _gen((n,), 0.5, 4000)
-    wm = B.Mat.from_f16(w, quant, tiled=quant)
+    h16 = quant == "h16"
+    quant = bool(quant)
+    wm = B.Mat.from_f16(w, quant, tiled=quant, meta_f16=h16)
     out = B.fg_linear(wm, bias, x, res, False)
     torch.cuda.synchronize()
 
     cols = _sample(n, [255, 256, 32 * 1151, n - 256, n // 2], 24, n + k)
     rows = _sample(m, [31, 32, 159, 160, 255, 256, m // 2, m - 33], 24, m + k) if m > 160 else np.arange(m)
     w_rows = host(w[torch.from_numpy(cols).cuda()])
-    om = O.Mat.from_f16(w_rows, quant)
+    om = O.Mat.from_f16(w_rows, quant, h16)
     if quant:   # the device quantized the very same rows to the very same bytes (checked on the canonical form)
-        canon = B.Mat.from_f16(w[torch.from_numpy(cols).cuda()].contiguous(), True)
+        canon = B.Mat.from_f16(w[torch.from_numpy(cols).cuda()].contiguous(), True, meta_f16=h16)
+        bits = np.uint16 if h16 else np.uint32
         assert np.array_equal(host(canon.data), om.codes)
-        assert np.array_equal(host(canon.meta).view(np.uint32), om.meta.view(np.uint32))
+        assert np.array_equal(host(canon.meta).view(bits), om.meta.view(bits))
     ti = torch.from_numpy(rows).cuda()
     tj = torch.from_numpy(cols).cuda()
     x_s = host(x[ti]).astype(np.float64)

@@ -96,25 +96,26 @@ def test_layernorm(rows, cols):
 
 
 # ------------------------------------------------------------------ fused dequant + GEMM
-def _linear_case(m, n, k, quant, bias, relu, residual, seed, std_w=0.02, std_x=1.0, tiled=False):
+def _linear_case(m, n, k, quant, bias, relu, residual, seed, std_w=0.02, std_x=1.0, tiled=False, meta_f16=False):
     w16 = _rand16((n, k), std_w, seed)
     x16 = _rand16((m, k), std_x, seed + 1)
     b16 = _rand16(n, 0.5, seed + 2) if bias else None
     r16 = _rand16((m, n), 1.0, seed + 3) if residual else None
-    om = O.Mat.from_f16(w16, quant)
+    om = O.Mat.from_f16(w16, quant, meta_f16)
     y = O.linear(x16.astype(np.float64), om, b16)
     if relu:
         y = np.maximum(y, 0.0)
     if residual:
         y = y + r16.astype(np.float64)
     ref = O.round_f16(y)
-    wm = B.Mat.from_f16(dev(w16), quant)
+    wm = B.Mat.from_f16(dev(w16), quant, meta_f16=meta_f16)
+    bits = np.uint16 if meta_f16 else np.uint32
     if quant:   # the device-made weights are the oracle's bits
-        assert np.array_equal(host(wm.data), om.codes) and np.array_equal(host(wm.meta), om.meta)
+        assert np.array_equal(host(wm.data), om.codes) and np.array_equal(host(wm.meta).view(bits), om.meta.view(bits))
     if tiled:
         wm = wm.tiled()
         tc, tmeta = O.tile_weights(om.codes, om.meta)
-        assert np.array_equal(host(wm.data), tc) and np.array_equal(host(wm.meta), tmeta)
+        assert np.array_equal(host(wm.data), tc) and np.array_equal(host(wm.meta).view(bits), tmeta.view(bits))
     out = B.fg_linear(wm, dev(b16), dev(x16), dev(r16), relu)
     torch.cuda.synchronize()
     return host(out), ref
@@ -181,6 +182,20 @@ TILED_CASES = [
 def test_linear_tiled_weights(m, n, k, bias, relu, residual):
     got, ref = _linear_case(m, n, k, True, bias, relu, residual, seed=m + n + k, tiled=True)
     assert_close(got, ref, "tiled linear m=%d n=%d k=%d" % (m, n, k))
+
+
+@pytest.mark.parametrize("m,n,k,bias,relu,residual", TILED_CASES)
+def test_linear_tiled_weights_fp16_pairs(m, n, k, bias, relu, residual):
+    """Tiled 4-bit weights whose {min, scale} pairs are FP16 (0.5625 bytes per weight)."""
+    got, ref = _linear_case(m, n, k, True, bias, relu, residual, seed=m + n + k + 7, tiled=True, meta_f16=True)
+    assert_close(got, ref, "tiled FP16-pair linear m=%d n=%d k=%d" % (m, n, k))
+
+
+def test_linear_rejects_canonical_fp16_pair_weights():
+    """Only the tiled form of an FP16-pair matrix can be multiplied."""
+    wq = B.Mat.from_f16(dev(_rand16((64, 128), 0.02, 5)), True, meta_f16=True)
+    with pytest.raises(RuntimeError):
+        B.fg_linear(wq, None, dev(_rand16((4, 128), 1.0, 6)))
 
 
 def test_linear_identity_and_onehot():

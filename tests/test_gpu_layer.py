@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 
 def _run_layer_sequence(sh, quant_w, quant_kv, b, s, steps, seed, biases, random_ln, x_std=0.05, batch=None,
-                        boff=0, tiled=False, meta_f16=False):
+                        boff=0, tiled=False, meta_f16=False, w_meta_f16=False):
     """Prefill then `steps` decode steps on both sides, the decode inputs being fresh seeded
     activations (the same on both sides).  Before every decode step the device cache is overwritten
     with the oracle's bytes, so each step is compared on identical inputs: the two caches otherwise
@@ -22,8 +22,8 @@ def _run_layer_sequence(sh, quant_w, quant_kv, b, s, steps, seed, biases, random
     crosses a rounding boundary, which says nothing about the kernels."""
     ocfg, cfg = cfg_pair(sh)
     t = synth.layer_tensors(sh, seed, 0, std=0.02, biases=biases, random_ln=random_ln)
-    ow = oracle_layer(t, quant_w)
-    w = B.LayerWeights.from_numpy(t, quant_w, tiled=tiled)
+    ow = oracle_layer(t, quant_w, w_meta_f16)
+    w = B.LayerWeights.from_numpy(t, quant_w, tiled=tiled, meta_f16=w_meta_f16)
     batch = batch or b
     cap = s + steps
     okv = O.KVCache.empty(batch, sh.nh, cap, sh.dh, quant_kv, meta_f16)
@@ -68,6 +68,17 @@ def test_layer_with_fp16_pair_cache(dh128):
     else:
         _run_layer_sequence(synth.OPT_125M_LAYER, True, True, b=4, s=32, steps=4, seed=3, biases=False,
                             random_ln=False, x_std=0.03, tiled=True, meta_f16=True)
+
+
+@pytest.mark.parametrize("prefill_rows", [False, True])
+def test_layer_with_fp16_pair_weights_and_cache(prefill_rows):
+    """Weights AND cache in the 4.5-bit form (FP16 pairs), decode-shape and prefill-shape GEMM launches."""
+    if prefill_rows:   # 4 x 96 = 384 rows: the 256-row prefill tile
+        _run_layer_sequence(synth.OPT_125M_LAYER, True, True, b=4, s=96, steps=2, seed=6, biases=True,
+                            random_ln=True, x_std=0.1, tiled=True, meta_f16=True, w_meta_f16=True)
+    else:
+        _run_layer_sequence(synth.OPT_125M_LAYER, True, True, b=4, s=32, steps=4, seed=5, biases=False,
+                            random_ln=False, x_std=0.03, tiled=True, meta_f16=True, w_meta_f16=True)
 
 
 @pytest.mark.parametrize("quant_w,quant_kv", [(False, False), (True, False), (False, True)])

@@ -281,3 +281,29 @@ def test_kv_cache_h16_variant_stores_half_size_pairs():
     kh, _ = a.load(1, 1, 4)
     c, m = O.quantize_groupwise_h16(x[1, :, 64:128])
     assert np.array_equal(kh[1:4], O.dequantize_groupwise(c, m).astype(np.float64))
+
+
+def test_h16_weight_form_is_single_rounding_and_tiles_like_the_binary32_form():
+    """Weights with FP16 pairs: Mat.dense() is the FP16 number nearest to min + code*scale evaluated
+    exactly (Python fractions) from the STORED FP16 pair; the tiled order permutes 4-byte pairs the
+    same way it permutes 8-byte ones; and y = x W^T against that dense matrix is what linear() gives."""
+    from fractions import Fraction
+    w = _rand16((32, 128), 0.02, 33)
+    m = O.Mat.from_f16(w, True, meta_f16=True)
+    assert m.meta.dtype == np.float16 and m.meta.shape == (32, 2, 2)
+    c = O.unpack_codes(m.codes)
+    d = m.dense()
+    for r in range(0, 32, 5):
+        for k in range(0, 128, 3):
+            exact = Fraction(float(m.meta[r, k // 64, 0])) + int(c[r, k]) * Fraction(float(m.meta[r, k // 64, 1]))
+            assert d[r, k] == float(np.float16(float(exact)))
+    # within half a step of the original weight
+    sc = np.repeat(m.meta[..., 1].astype(np.float64), 64, axis=1)
+    assert np.all(np.abs(d - w.astype(np.float64)) <= sc / 2 + 2.0 ** -11 * np.abs(d) + 1e-12)
+    tc, tm = O.tile_weights(m.codes, m.meta)
+    tc32, tm32 = O.tile_weights(m.codes, m.meta.astype(np.float32))
+    assert tm.dtype == np.float16 and np.array_equal(tc, tc32) and np.array_equal(tm.astype(np.float32), tm32)
+    x = _rand16((3, 128), 1.0, 34).astype(np.float64)
+    y = O.linear(x, m, None)
+    ref = np.array([[sum(x[i, k] * d[j, k] for k in range(128)) for j in range(32)] for i in range(3)])
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-12)

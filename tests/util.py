@@ -41,10 +41,10 @@ def assert_close(got, ref, what="", rel=REL_L2, mabs=MAX_ABS):
     return r, m
 
 
-def oracle_layer(t, quant):
+def oracle_layer(t, quant, meta_f16=False):
+    mk = lambda a: O.Mat.from_f16(a, quant, meta_f16 and quant)
     return O.LayerWeights(
-        wqkv=O.Mat.from_f16(t["wqkv"], quant), wo=O.Mat.from_f16(t["wo"], quant),
-        w1=O.Mat.from_f16(t["w1"], quant), w2=O.Mat.from_f16(t["w2"], quant),
+        wqkv=mk(t["wqkv"]), wo=mk(t["wo"]), w1=mk(t["w1"]), w2=mk(t["w2"]),
         ln1_g=t["ln1_g"], ln1_b=t["ln1_b"], ln2_g=t["ln2_g"], ln2_b=t["ln2_b"],
         bqkv=t["bqkv"], bo=t["bo"], b1=t["b1"], b2=t["b2"])
 
