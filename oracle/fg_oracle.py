@@ -21,9 +21,10 @@ Precision policy
 
 Parity pins: every function here is pinned by tests/test_oracle_*.py against
 invariants, closed forms, brute force or a library routine, except
-`generate`, whose output values for random weights are fixed by nothing the
-paper prints: full-model token ids are "parity unpinned" and are pinned only
-transitively (layer pins + schedule invariants).
+`generate` (and `generate_diagonal`, pinned to it: same ids in another order), whose
+output values for random weights are fixed by nothing the paper prints:
+full-model token ids are "parity unpinned" and are pinned only transitively
+(layer pins + schedule invariants).
 """
 from __future__ import annotations
 
@@ -498,6 +499,165 @@ def generate(cfg: ModelCfg, layers: List[LayerWeights], emb16, pos16, lnf_g, lnf
             trace.append(logits)
     if return_trace:
         return ids, np.stack(trace), caches
+    return ids
+
+
+# --------------------------------------------------------------------------
+# Appendix, "Diagonal block schedule": non-contiguous cache, sequences at different steps
+# --------------------------------------------------------------------------
+PAGE_ROWS = 64
+
+
+@dataclass
+class PagedKVCache:
+    """One layer's compressed K/V cache in non-contiguous memory (the appendix names attention over
+    non-contiguous memory as what the diagonal block schedule needs in order to save memory).
+
+    A pool of pages; a page holds PAGE_ROWS = 64 consecutive positions of ONE sequence, for all heads:
+    codes [n_pages, nh, 64, dh/2], meta [n_pages, nh, 64, dh/64, 2].  table[seq] lists the pages of
+    sequence `seq` in position order (position p lives in page table[seq][p // 64], row p % 64).
+    Every row is quantized exactly as in KVCache (Section 5, along the hidden dimension of the token
+    row): this class only changes where a row is kept.  It has KVCache's store/load interface, the
+    sequence id taking the place of the batch index."""
+    nh: int
+    dh: int
+    n_pages: int
+    table: np.ndarray                      # int32 [n_seqs, max_pages_per_seq]; -1 = no page
+    meta_f16: bool = False
+    k_codes: np.ndarray = field(default=None)
+    k_meta: np.ndarray = field(default=None)
+    v_codes: np.ndarray = field(default=None)
+    v_meta: np.ndarray = field(default=None)
+
+    @staticmethod
+    def empty(nh: int, dh: int, n_pages: int, table: np.ndarray, meta_f16: bool = False) -> "PagedKVCache":
+        assert dh % GROUP == 0
+        c = PagedKVCache(nh, dh, n_pages, np.asarray(table, np.int32), meta_f16)
+        mt = np.float16 if meta_f16 else np.float32
+        c.k_codes = np.zeros((n_pages, nh, PAGE_ROWS, dh // 2), np.uint8)
+        c.v_codes = np.zeros((n_pages, nh, PAGE_ROWS, dh // 2), np.uint8)
+        c.k_meta = np.zeros((n_pages, nh, PAGE_ROWS, dh // GROUP, 2), mt)
+        c.v_meta = np.zeros((n_pages, nh, PAGE_ROWS, dh // GROUP, 2), mt)
+        return c
+
+    def _where(self, seq: int, pos: int):
+        page = int(self.table[seq, pos // PAGE_ROWS])
+        assert 0 <= page < self.n_pages, "position %d of sequence %d has no page" % (pos, seq)
+        return page, pos % PAGE_ROWS
+
+    def store(self, b0: int, pos0: int, k16: np.ndarray, v16: np.ndarray) -> None:
+        """FP16 K/V rows [nb, npos, h1] of sequences b0.. at positions pos0..: each token row is
+        quantized along its hidden dimension and written row by row through the page table."""
+        nb, npos, h1 = k16.shape
+        assert h1 == self.nh * self.dh
+        quant = quantize_groupwise_h16 if self.meta_f16 else quantize_groupwise
+        for name, x16 in (("k", k16), ("v", v16)):
+            codes, meta = quant(np.ascontiguousarray(x16, np.float16).reshape(nb * npos, h1))
+            codes = codes.reshape(nb, npos, self.nh, self.dh // 2)
+            meta = meta.reshape(nb, npos, self.nh, self.dh // GROUP, 2)
+            for i in range(nb):
+                for p in range(npos):
+                    page, r = self._where(b0 + i, pos0 + p)
+                    getattr(self, name + "_codes")[page, :, r] = codes[i, p]
+                    getattr(self, name + "_meta")[page, :, r] = meta[i, p]
+
+    def load(self, b: int, head: int, rows: int):
+        """K_hat, V_hat [rows, dh] float64 of one (sequence, head): the rows gathered through the
+        page table, converted back from the stored format."""
+        out = []
+        for name in ("k", "v"):
+            codes = np.empty((rows, self.dh // 2), np.uint8)
+            meta = np.empty((rows, self.dh // GROUP, 2), self.k_meta.dtype)
+            for p in range(rows):
+                page, r = self._where(b, p)
+                codes[p] = getattr(self, name + "_codes")[page, head, r]
+                meta[p] = getattr(self, name + "_meta")[page, head, r]
+            out.append(dequantize_groupwise(codes, meta).astype(np.float64))
+        return out[0], out[1]
+
+
+def decode_layer_ragged(cfg: ModelCfg, w: LayerWeights, x16: np.ndarray, seq_ids, pos, kv) -> np.ndarray:
+    """A decode step in which row i belongs to sequence seq_ids[i] and sits at its own position pos[i]
+    (pos[i] rows already cached), as in the diagonal block schedule, where the GPU batches of a block
+    are at different token steps.  Section 3 treats every sequence on its own, so this is decode_layer
+    applied to each row with its own t.  kv: a KVCache or a PagedKVCache.  x16 [b, h1] FP16."""
+    out = np.empty_like(np.asarray(x16, np.float16))
+    for i in range(out.shape[0]):
+        out[i] = decode_layer(cfg, w, x16[i:i + 1], int(pos[i]), kv, batch_offset=int(seq_ids[i]))[0]
+    return out
+
+
+def generate_diagonal(cfg: ModelCfg, layers: List[LayerWeights], emb16, pos16, lnf_g, lnf_b,
+                      prompt: np.ndarray, n: int, gpu_batch_size: int, meta_f16: bool = False,
+                      return_page_use: bool = False):
+    """Generation in the order of the appendix's diagonal block schedule, for a queue of
+    prompt.shape[0] sequences cut into GPU batches of gpu_batch_size: one GPU batch is admitted per
+    iteration, so in iteration `it` batch g is at token step it - g; an iteration runs, layer by layer,
+    the prefill of the newly admitted batch and one decode step of every batch still generating (the
+    squares of one diagonal), then emits one token for each of them.  A batch is retired after its
+    n-th token and its cache pages return to the pool; pages are taken one at a time as a sequence
+    grows.  The compressed cache is paged (PagedKVCache), one pool per layer.
+
+    The schedule only reorders independent work, so the ids equal generate()'s row for row.
+    Returns ids int32 [n_seqs, n] (and, on request, the largest number of pages in use at once)."""
+    n_seqs, s = prompt.shape
+    assert n_seqs % gpu_batch_size == 0 and n >= 1 and s + n - 1 <= cfg.max_pos
+    ng = n_seqs // gpu_batch_size
+    l = len(layers)
+    max_pages = -(-(s + n) // PAGE_ROWS)
+    in_flight = min(ng, n)
+    pool_pages = in_flight * gpu_batch_size * max_pages          # an upper bound; page_use reports the need
+    table = np.full((n_seqs, max_pages), -1, np.int32)
+    caches = [PagedKVCache.empty(cfg.nh, cfg.dh, pool_pages, table, meta_f16) for _ in range(l)]
+    for c in caches:
+        c.table = table                                          # one table, shared by the layers
+    free = list(range(pool_pages - 1, -1, -1))
+    ids = np.zeros((n_seqs, n), np.int32)
+    peak = 0
+
+    def ensure(seq: int, rows: int):
+        for slot in range(-(-rows // PAGE_ROWS)):
+            if table[seq, slot] < 0:
+                table[seq, slot] = free.pop()
+
+    for it in range(ng + n - 1):
+        groups = [g for g in range(ng) if 0 <= it - g < n]
+        # this iteration's rows: the admitted batch's prompt, and one token of every older batch
+        new = [g for g in groups if it - g == 0]
+        old = [g for g in groups if it - g > 0]
+        old_seqs = np.array([q for g in old for q in range(g * gpu_batch_size, (g + 1) * gpu_batch_size)], np.int64)
+        old_pos = np.array([s + (it - q // gpu_batch_size) - 1 for q in old_seqs], np.int64)
+        for q, p in zip(old_seqs, old_pos):
+            ensure(int(q), int(p) + 1)
+        x_new = None
+        if new:
+            sl = slice(new[0] * gpu_batch_size, (new[0] + 1) * gpu_batch_size)
+            for q in range(sl.start, sl.stop):
+                ensure(q, s)
+            x_new = embed(prompt[sl], np.broadcast_to(np.arange(s), (gpu_batch_size, s)), emb16, pos16)
+        peak = max(peak, pool_pages - len(free))
+        x_old = None
+        if len(old_seqs):
+            step = np.array([it - q // gpu_batch_size for q in old_seqs])
+            x_old = embed(ids[old_seqs, step - 1], old_pos, emb16, pos16)
+        for j in range(l):
+            if x_new is not None:
+                x_new = prefill_layer(cfg, layers[j], x_new, caches[j], batch_offset=new[0] * gpu_batch_size)
+            if x_old is not None:
+                x_old = decode_layer_ragged(cfg, layers[j], x_old, old_seqs, old_pos, caches[j])
+        if x_new is not None:
+            ids[sl, 0] = greedy(lm_head_logits(cfg, x_new[:, -1, :], lnf_g, lnf_b, emb16))
+        if x_old is not None:
+            ids[old_seqs, step] = greedy(lm_head_logits(cfg, x_old, lnf_g, lnf_b, emb16))
+        for g in groups:
+            if it - g == n - 1:                                   # retired: its pages go back
+                for q in range(g * gpu_batch_size, (g + 1) * gpu_batch_size):
+                    for slot in range(max_pages):
+                        if table[q, slot] >= 0:
+                            free.append(int(table[q, slot]))
+                            table[q, slot] = -1
+    if return_page_use:
+        return ids, peak
     return ids
 
 
