@@ -111,6 +111,38 @@ typedef struct {
   int32_t reserved;
 } fg_kv_cache;
 
+/* One layer's compressed cache in NON-CONTIGUOUS memory (appendix, "Diagonal block schedule": the
+ * schedule saves memory only with attention over a cache that is not one pre-allocated buffer per
+ * sequence).  A pool of n_pages pages; a page holds FG_PAGE_ROWS = 64 consecutive positions of ONE
+ * sequence for all heads:
+ *   k_codes/v_codes [n_pages][nh][64][dh/2] bytes, k_meta/v_meta [n_pages][nh][64][dh/64] pairs
+ * (8-byte pairs for FG_Q4G64, 4-byte FP16 pairs for FG_Q4G64_H16; FG_F16 is not supported in pages).
+ * Rows are quantized exactly as in fg_kv_cache; only their place differs. */
+#define FG_PAGE_ROWS 64
+typedef struct {
+  void *k_codes, *k_meta, *v_codes, *v_meta; /* device */
+  int32_t dtype;                             /* FG_Q4G64 or FG_Q4G64_H16 */
+  int32_t n_pages;
+} fg_kv_pages;
+
+/* Who the rows of a ragged step are and where their sequences live.  All arrays are DEVICE int32.
+ * page_table [n_seqs][table_stride]: entry [q][j] is the page holding positions 64j .. 64j+63 of
+ *   sequence q (only entries below the sequence's length are read; the table is shared by all layers
+ *   when every layer's pool assigns the same page numbers).
+ * seq_ids [b]: sequence of row i, or NULL for the identity (row i is sequence i).
+ * pos [b]: number of rows of row i's sequence already cached BEFORE this call (its new row goes to
+ *   position pos[i]); NULL means 0 for every row.
+ * The kernels cannot report errors: an entry that is out of range (sequence id, position beyond
+ * 64*table_stride, page number) makes them skip the store, and read page 0 or stop at the table's
+ * end in the attention, so a wrong table yields wrong values, never an access outside the pool. */
+typedef struct {
+  const int32_t* page_table;
+  const int32_t* seq_ids;
+  const int32_t* pos;
+  int32_t table_stride;
+  int32_t n_seqs;
+} fg_ragged;
+
 /* Timers and byte counts written by fg_generate (host memory). */
 typedef struct {
   double prefill_s;             /* token step 1: all layers, all GPU batches, first token */
@@ -252,6 +284,37 @@ int fg_generate(const fg_model_cfg* cfg, int32_t l, const fg_layer_weights* laye
                 fg_stats* stats);
 size_t fg_workspace_bytes(const fg_model_cfg* cfg, const fg_layer_weights* layer0, int32_t gpu_batch_size,
                           int32_t num_gpu_batches, int32_t s);
+
+/* ---- Appendix, "Diagonal block schedule": paged cache, sequences at different steps --------
+ * fg_kv_append_paged: like fg_kv_append, rows [b, s, h1]; row j of sequence i goes to position
+ * pos[i] + j of sequence seq_ids[i], through the page table. */
+int fg_kv_append_paged(const fg_model_cfg* cfg, const void* k_f16, const void* v_f16, int64_t row_stride,
+                       int32_t b, int32_t s, const fg_kv_pages* pages, const fg_ragged* seqs, void* stream);
+
+/* Decode attention over a paged cache with a length per sequence: row i attends positions
+ * 0 .. pos[i] + rows_bias - 1 of sequence seq_ids[i] (rows_bias = 1 right after its new row was
+ * appended at pos[i]; 0 if pos already counts every row to attend).  A row with no position to
+ * attend gets zeros.  seqs->pos may not be NULL.  Same arithmetic as fg_decode_attention. */
+int fg_decode_attention_paged(const fg_model_cfg* cfg, const void* q_f16, int64_t q_row_stride, int32_t b,
+                              const fg_kv_pages* pages, const fg_ragged* seqs, int32_t rows_bias,
+                              void* out_f16, void* stream);
+
+/* fg_decode_layer for rows at different steps over a paged cache: row i belongs to sequence
+ * seq_ids[i], appends its K/V row at position pos[i] and attends positions 0 .. pos[i].
+ * ws >= fg_layer_workspace_bytes(cfg, wts, b). */
+int fg_decode_layer_paged(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in, int32_t b,
+                          const fg_kv_pages* pages, const fg_ragged* seqs, void* x_out, void* ws,
+                          size_t ws_bytes, void* stream);
+
+/* fg_prefill_layer storing the s K/V rows of sequence seq_ids[i] at positions 0 .. s-1 of its pages
+ * (seqs->pos is ignored).  ws >= fg_layer_workspace_bytes(cfg, wts, b*s). */
+int fg_prefill_layer_paged(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in, int32_t b,
+                           int32_t s, const fg_kv_pages* pages, const fg_ragged* seqs, void* x_out, void* ws,
+                           size_t ws_bytes, void* stream);
+
+/* x0 = E[id] + P[position] with a position per row: ids, positions device int32 [rows]. */
+int fg_embed_ragged(const fg_model_cfg* cfg, const void* embed_f16, const void* pos_f16, const int32_t* ids,
+                    const int32_t* positions, int64_t rows, void* out_f16, void* stream);
 
 /* ---- Per-kernel timing (HIP events on the caller's stream) -----------------------------
  * Between fg_profile_begin and fg_profile_end every kernel launch of the library is bracketed

@@ -43,6 +43,16 @@ class fg_kv_cache(C.Structure):
                 ("dtype", C.c_int32), ("batch", C.c_int32), ("cap", C.c_int32), ("reserved", C.c_int32)]
 
 
+class fg_kv_pages(C.Structure):
+    _fields_ = [("k_codes", C.c_void_p), ("k_meta", C.c_void_p), ("v_codes", C.c_void_p), ("v_meta", C.c_void_p),
+                ("dtype", C.c_int32), ("n_pages", C.c_int32)]
+
+
+class fg_ragged(C.Structure):
+    _fields_ = [("page_table", C.c_void_p), ("seq_ids", C.c_void_p), ("pos", C.c_void_p),
+                ("table_stride", C.c_int32), ("n_seqs", C.c_int32)]
+
+
 class fg_stats(C.Structure):
     _fields_ = [("prefill_s", C.c_double), ("decode_s", C.c_double), ("tokens", C.c_int64),
                 ("weight_bytes_per_step", C.c_int64), ("kv_bytes_last_step", C.c_int64),
@@ -93,6 +103,19 @@ EXPORTS = {
                               C.POINTER(fg_stats)]),
     "fg_workspace_bytes": (C.c_size_t, [C.POINTER(fg_model_cfg), C.POINTER(fg_layer_weights), C.c_int32,
                                         C.c_int32, C.c_int32]),
+    "fg_kv_append_paged": (C.c_int, [C.POINTER(fg_model_cfg), C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
+                                     C.POINTER(fg_kv_pages), C.POINTER(fg_ragged), C.c_void_p]),
+    "fg_decode_attention_paged": (C.c_int, [C.POINTER(fg_model_cfg), C.c_void_p, C.c_int64, C.c_int32,
+                                            C.POINTER(fg_kv_pages), C.POINTER(fg_ragged), C.c_int32, C.c_void_p,
+                                            C.c_void_p]),
+    "fg_decode_layer_paged": (C.c_int, [C.POINTER(fg_model_cfg), C.POINTER(fg_layer_weights), C.c_void_p, C.c_int32,
+                                        C.POINTER(fg_kv_pages), C.POINTER(fg_ragged), C.c_void_p, C.c_void_p,
+                                        C.c_size_t, C.c_void_p]),
+    "fg_prefill_layer_paged": (C.c_int, [C.POINTER(fg_model_cfg), C.POINTER(fg_layer_weights), C.c_void_p, C.c_int32,
+                                         C.c_int32, C.POINTER(fg_kv_pages), C.POINTER(fg_ragged), C.c_void_p,
+                                         C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fg_embed_ragged": (C.c_int, [C.POINTER(fg_model_cfg), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                  C.c_void_p, C.c_void_p]),
     "fg_profile_begin": (C.c_int, []),
     "fg_profile_end": (C.c_int, []),
     "fg_profile_read": (C.c_int, [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
@@ -236,6 +259,41 @@ class KVCache:
         return n
 
 
+PAGE_ROWS = 64
+
+
+class KVPages:
+    """One layer's 4-bit cache as a pool of pages of 64 positions: [n_pages, nh, 64, dh/2] codes and
+    [n_pages, nh, 64, dh/64, 2] {min, scale} pairs (binary32, or FP16 with meta_f16)."""
+
+    def __init__(self, cfg: Cfg, n_pages: int, meta_f16: bool = False, device="cuda", zero: bool = True):
+        self.n_pages, self.meta_f16 = n_pages, bool(meta_f16)
+        mk = torch.zeros if zero else torch.empty
+        nh, dh = cfg.nh, cfg.dh
+        mt = torch.float16 if meta_f16 else torch.float32
+        self.k_codes = mk((n_pages, nh, PAGE_ROWS, dh // 2), dtype=torch.uint8, device=device)
+        self.v_codes = mk((n_pages, nh, PAGE_ROWS, dh // 2), dtype=torch.uint8, device=device)
+        self.k_meta = mk((n_pages, nh, PAGE_ROWS, dh // 64, 2), dtype=mt, device=device)
+        self.v_meta = mk((n_pages, nh, PAGE_ROWS, dh // 64, 2), dtype=mt, device=device)
+        self.c = fg_kv_pages(_p(self.k_codes), _p(self.k_meta), _p(self.v_codes), _p(self.v_meta),
+                             FG_Q4G64_H16 if meta_f16 else FG_Q4G64, n_pages)
+
+    def nbytes(self) -> int:
+        return 2 * (self.k_codes.numel() + self.k_meta.numel() * self.k_meta.element_size())
+
+
+class Ragged:
+    """Rows of a ragged step: page_table int32 [n_seqs, table_stride], seq_ids int32 [b] or None
+    (identity), pos int32 [b] or None (zeros); all on the device."""
+
+    def __init__(self, page_table: torch.Tensor, seq_ids: Optional[torch.Tensor] = None,
+                 pos: Optional[torch.Tensor] = None):
+        for t in (page_table, seq_ids, pos):
+            assert t is None or (t.dtype == torch.int32 and t.is_cuda and t.is_contiguous())
+        self.page_table, self.seq_ids, self.pos = page_table, seq_ids, pos
+        self.c = fg_ragged(_p(page_table), _p(seq_ids), _p(pos), page_table.shape[1], page_table.shape[0])
+
+
 def _ws(nbytes: int, device="cuda") -> Optional[torch.Tensor]:
     return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
 
@@ -360,6 +418,55 @@ def fg_decode_layer(cfg: Cfg, w: LayerWeights, x: torch.Tensor, t: int, kv: KVCa
         ws = _ws(lib().fg_layer_workspace_bytes(C.byref(cfg.c), C.byref(w.c), b))
     _check(lib().fg_decode_layer(C.byref(cfg.c), C.byref(w.c), _p(x), b, t, C.byref(kv.c), batch_offset, _p(out),
                                  _p(ws), ws.numel(), _stream()), "fg_decode_layer")
+    return out
+
+
+def fg_kv_append_paged(cfg: Cfg, k: torch.Tensor, v: torch.Tensor, row_stride: int, b: int, s: int, pages: KVPages,
+                       seqs: Ragged) -> None:
+    _check(lib().fg_kv_append_paged(C.byref(cfg.c), _p(k), _p(v), row_stride, b, s, C.byref(pages.c), C.byref(seqs.c),
+                                    _stream()), "fg_kv_append_paged")
+
+
+def fg_decode_attention_paged(cfg: Cfg, q: torch.Tensor, q_row_stride: int, b: int, pages: KVPages, seqs: Ragged,
+                              rows_bias: int = 0) -> torch.Tensor:
+    out = torch.empty((b, cfg.h1), dtype=torch.float16, device=q.device)
+    _check(lib().fg_decode_attention_paged(C.byref(cfg.c), _p(q), q_row_stride, b, C.byref(pages.c), C.byref(seqs.c),
+                                           rows_bias, _p(out), _stream()), "fg_decode_attention_paged")
+    return out
+
+
+def fg_decode_layer_paged(cfg: Cfg, w: LayerWeights, x: torch.Tensor, pages: KVPages, seqs: Ragged,
+                          ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    x = _f16(x)
+    b = x.shape[0]
+    if out is None:
+        out = torch.empty_like(x)
+    if ws is None:
+        ws = _ws(lib().fg_layer_workspace_bytes(C.byref(cfg.c), C.byref(w.c), b))
+    _check(lib().fg_decode_layer_paged(C.byref(cfg.c), C.byref(w.c), _p(x), b, C.byref(pages.c), C.byref(seqs.c),
+                                       _p(out), _p(ws), ws.numel(), _stream()), "fg_decode_layer_paged")
+    return out
+
+
+def fg_prefill_layer_paged(cfg: Cfg, w: LayerWeights, x: torch.Tensor, pages: KVPages, seqs: Ragged,
+                           ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    x = _f16(x)
+    b, s, _ = x.shape
+    if out is None:
+        out = torch.empty_like(x)
+    if ws is None:
+        ws = _ws(lib().fg_layer_workspace_bytes(C.byref(cfg.c), C.byref(w.c), b * s))
+    _check(lib().fg_prefill_layer_paged(C.byref(cfg.c), C.byref(w.c), _p(x), b, s, C.byref(pages.c), C.byref(seqs.c),
+                                        _p(out), _p(ws), ws.numel(), _stream()), "fg_prefill_layer_paged")
+    return out
+
+
+def fg_embed_ragged(cfg: Cfg, emb: torch.Tensor, pos_table: torch.Tensor, ids: torch.Tensor,
+                    positions: torch.Tensor) -> torch.Tensor:
+    rows = ids.numel()
+    out = torch.empty((rows, cfg.h1), dtype=torch.float16, device=ids.device)
+    _check(lib().fg_embed_ragged(C.byref(cfg.c), _p(emb), _p(pos_table), _p(ids), _p(positions), rows, _p(out),
+                                 _stream()), "fg_embed_ragged")
     return out
 
 

@@ -38,6 +38,11 @@ struct AttnArgs {
   int nh, cap, rows, batch_offset;
   int n_heads;       // b * nh
   float scale;       // 1/sqrt(dh)
+  // paged cache (PAGED kernels): k/v pointers are the page pools; cap, rows, batch_offset are unused
+  const int32_t* page_table;   // [n_seqs][table_stride]
+  const int32_t* seq_ids;      // [b] or nullptr
+  const int32_t* seq_rows;     // [b]: rows attended = seq_rows[i] + rows_bias
+  int table_stride, n_seqs, n_pages, rows_bias;
 };
 
 // Merge the WPH per-wave triples of each head of the block and write the outputs.  o_w already
@@ -61,11 +66,14 @@ __device__ __forceinline__ void merge_and_store(const float* sm_m, const float* 
       num += f * sm_o[(hl * WPH + w) * DH + t];
       den += f * sm_l[hl * WPH + w];
     }
-    out0[(int64_t)hl * DH + t] = (half_t)(num / den);
+    out0[(int64_t)hl * DH + t] = (half_t)(den > 0.f ? num / den : 0.f);   // no rows attended: zeros
   }
 }
 
-template <int DH, int WPH, bool H16>
+// PAGED: the head's stream is cut into pages of 64 rows (FG_PAGE_ROWS) found through the sequence's
+// row of the page table, and every sequence has its own length.  A wave keeps 64 consecutive table
+// entries in one register (one per lane) and picks the page of a chunk with a lane read.
+template <int DH, int WPH, bool H16, bool PAGED = false>
 __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
   using meta_t = typename MetaRaw<H16>::type;
   constexpr int GPR = DH / 64;       // quantization groups per row of this head
@@ -84,13 +92,49 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
   const int seq = hid / a.nh, head = hid - seq * a.nh;
   const int r = lane & 15, q4 = lane >> 4, h = q4 >> 1, half = q4 & 1;
 
-  const int64_t hrow = ((int64_t)(a.batch_offset + seq) * a.nh + head) * a.cap;   // first cache row
-  const uint8_t* kc = a.k_codes + hrow * (DH / 2);
-  const uint8_t* vc = a.v_codes + hrow * (DH / 2);
-  const meta_t* km = reinterpret_cast<const meta_t*>(a.k_meta) + hrow * GPR;
-  const meta_t* vm = reinterpret_cast<const meta_t*>(a.v_meta) + hrow * GPR;
-  const int G = a.rows * GPR;                  // groups in the stream
+  // contiguous: the stream starts at cache row hrow; paged: group indices are formed per page
+  const int64_t hrow = PAGED ? 0 : ((int64_t)(a.batch_offset + seq) * a.nh + head) * a.cap;
+  const uint8_t* kc = a.k_codes;
+  const uint8_t* vc = a.v_codes;
+  const meta_t* km = reinterpret_cast<const meta_t*>(a.k_meta);
+  const meta_t* vm = reinterpret_cast<const meta_t*>(a.v_meta);
+  int rows = a.rows;
+  const int32_t* tbl = nullptr;
+  int n_slots = 0;
+  if constexpr (PAGED) {
+    int sid = a.seq_ids ? a.seq_ids[seq] : seq;
+    sid = sid < 0 ? 0 : (sid >= a.n_seqs ? a.n_seqs - 1 : sid);
+    tbl = a.page_table + (int64_t)sid * a.table_stride;
+    rows = a.seq_rows[seq] + a.rows_bias;
+    rows = rows < 0 ? 0 : rows;
+    rows = rows > a.table_stride * FG_PAGE_ROWS ? a.table_stride * FG_PAGE_ROWS : rows;   // never read past the table
+    n_slots = (rows + FG_PAGE_ROWS - 1) / FG_PAGE_ROWS;
+  }
+  const int G = rows * GPR;                    // groups in the stream
   const int n_chunks = (G + 127) >> 7;
+  // paged: the table entries of slots 64*win .. 64*win + 63, one per lane
+  int win = -1, tbl_reg = 0;
+  auto page_of = [&](int slot) -> int {   // slot is wave-uniform and < n_slots
+    if ((slot >> 6) != win) {
+      win = slot >> 6;
+      const int sl = win * 64 + lane;
+      tbl_reg = tbl[sl < n_slots ? sl : n_slots - 1];
+    }
+    int pg = __builtin_amdgcn_readlane(tbl_reg, slot & 63);
+    return pg < 0 ? 0 : (pg >= a.n_pages ? a.n_pages - 1 : pg);   // a bad entry reads page 0 / the last page
+  };
+  // index (in quantization groups) into the code / meta arrays of group g (< G) of this head's stream;
+  // pgA, pgB: pages of the first and (head size 64 only) second slot of the chunk being loaded
+  constexpr int kGPP = FG_PAGE_ROWS * GPR;     // groups per (page, head)
+  auto gidx = [&](int g, int slot0, int pgA, int pgB) -> int64_t {
+    if constexpr (!PAGED) {
+      return hrow * GPR + g;
+    } else {
+      const int slot = g / kGPP;
+      const int pg = slot == slot0 ? pgA : pgB;
+      return ((int64_t)pg * a.nh + head) * kGPP + (g - slot * kGPP);
+    }
+  };
 
   // one chunk's worth of registers: 4 + 4 code loads of 16 bytes and the meta of the lane's two groups
   struct Buf {
@@ -100,19 +144,27 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
   // all addresses clamped into the stream; rows past the end are masked when the chunk is processed
   auto load = [&](Buf& b, int chunk) {
     const int gbase = chunk << 7;
+    int slot0 = 0, pgA = 0, pgB = 0;
+    if constexpr (PAGED) {   // a chunk of 128 groups is one page at head size 128, two at 64
+      slot0 = gbase / kGPP;
+      pgA = page_of(slot0);
+      pgB = (GPR == 1 && slot0 + 1 < n_slots) ? page_of(slot0 + 1) : pgA;
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       int g = gbase + 32 * i + 2 * r + h;
       g = g < G ? g : G - 1;
-      b.kq[i] = *reinterpret_cast<const u4_t*>(kc + (int64_t)g * 32 + half * 16);
-      b.vq[i] = *reinterpret_cast<const u4_t*>(vc + (int64_t)g * 32 + half * 16);
+      const int64_t gi = gidx(g, slot0, pgA, pgB);
+      b.kq[i] = *reinterpret_cast<const u4_t*>(kc + gi * 32 + half * 16);
+      b.vq[i] = *reinterpret_cast<const u4_t*>(vc + gi * 32 + half * 16);
     }
     const int g0 = gbase + 2 * lane, g1 = g0 + 1;
     const int c0 = g0 < G ? g0 : G - 1, c1 = g1 < G ? g1 : G - 1;
-    b.km0 = km[c0];
-    b.km1 = km[c1];
-    b.vm0 = vm[c0];
-    b.vm1 = vm[c1];
+    const int64_t i0 = gidx(c0, slot0, pgA, pgB), i1 = gidx(c1, slot0, pgA, pgB);
+    b.km0 = km[i0];
+    b.km1 = km[i1];
+    b.vm0 = vm[i0];
+    b.vm1 = vm[i1];
   };
   // the first chunk's loads go out before anything else: they overlap the query set-up below
   Buf b0, b1;
@@ -226,7 +278,7 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
   half_t* out0 = a.out + (int64_t)hid0 * DH;
   if (WPH == 1) {
     if (writer && hl < heads_valid) {
-      const float inv = 1.0f / lw;
+      const float inv = lw > 0.f ? 1.0f / lw : 0.f;   // no rows attended (paged, empty sequence): zeros
       half_t* dst = out0 + (int64_t)hl * DH + dbase;
 #pragma unroll
       for (int v8 = 0; v8 < 4; ++v8) {
@@ -394,6 +446,8 @@ int decode_attention_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_
   a.batch_offset = batch_offset;
   a.scale = 1.0f / sqrtf((float)dh);
   a.n_heads = b * cfg.nh;
+  a.page_table = a.seq_ids = a.seq_rows = nullptr;
+  a.table_stride = a.n_seqs = a.n_pages = a.rows_bias = 0;
   // Waves per head: one wave per head wastes the least (a stream of c chunks costs ceil(c / WPH) chunk
   // times), but the chip wants at least ~8 waves on each of its 256 CUs.
   const int64_t heads = (int64_t)b * cfg.nh;
@@ -438,9 +492,74 @@ int decode_attention_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_
   return FG_OK;
 }
 
+int decode_attention_paged_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_stride, int32_t b,
+                                  const fg_kv_pages& pages, const fg_ragged& seqs, int32_t rows_bias, half_t* out,
+                                  hipStream_t stream) {
+  if (b == 0) return FG_OK;
+  const int dh = cfg.h1 / cfg.nh;
+  AttnArgs a;
+  a.q = q;
+  a.q_stride = q_stride;
+  a.k_codes = reinterpret_cast<const uint8_t*>(pages.k_codes);
+  a.v_codes = reinterpret_cast<const uint8_t*>(pages.v_codes);
+  a.k_meta = pages.k_meta;
+  a.v_meta = pages.v_meta;
+  a.out = out;
+  a.nh = cfg.nh;
+  a.cap = 0;
+  a.rows = 0;
+  a.batch_offset = 0;
+  a.scale = 1.0f / sqrtf((float)dh);
+  a.n_heads = b * cfg.nh;
+  a.page_table = seqs.page_table;
+  a.seq_ids = seqs.seq_ids;
+  a.seq_rows = seqs.pos;
+  a.table_stride = seqs.table_stride;
+  a.n_seqs = seqs.n_seqs;
+  a.n_pages = pages.n_pages;
+  a.rows_bias = rows_bias;
+  const int64_t heads = (int64_t)b * cfg.nh;
+  const int wph = heads >= 2048 ? 1 : (heads >= 1024 ? 2 : 4);   // as in the contiguous launch
+  const dim3 grid((unsigned)ceil_div(heads * wph, 4));
+  const bool h16 = pages.dtype == FG_Q4G64_H16;
+  ProfScope prof(FG_K_ATTN_DECODE, stream);
+#define FG_PAGED_LAUNCH(DH_, WPH_)                                                                          \
+  do {                                                                                                      \
+    if (h16)                                                                                                \
+      hipLaunchKernelGGL((attn_decode_q4_kernel<DH_, WPH_, true, true>), grid, dim3(256), 0, stream, a);    \
+    else                                                                                                    \
+      hipLaunchKernelGGL((attn_decode_q4_kernel<DH_, WPH_, false, true>), grid, dim3(256), 0, stream, a);   \
+  } while (0)
+  if (dh == 128) {
+    if (wph == 1) FG_PAGED_LAUNCH(128, 1); else if (wph == 2) FG_PAGED_LAUNCH(128, 2); else FG_PAGED_LAUNCH(128, 4);
+  } else {
+    if (wph == 1) FG_PAGED_LAUNCH(64, 1); else if (wph == 2) FG_PAGED_LAUNCH(64, 2); else FG_PAGED_LAUNCH(64, 4);
+  }
+#undef FG_PAGED_LAUNCH
+  FG_LAUNCH_CHECK();
+  return FG_OK;
+}
+
 }  // namespace fg
 
 using namespace fg;
+
+extern "C" int fg_decode_attention_paged(const fg_model_cfg* cfg, const void* q_f16, int64_t q_row_stride, int32_t b,
+                                         const fg_kv_pages* pages, const fg_ragged* seqs, int32_t rows_bias,
+                                         void* out_f16, void* stream) {
+  if (!cfg) return FG_ERR_NULL;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  rc = check_pages(cfg, pages, seqs);
+  if (rc) return rc;
+  if (!seqs->pos) return FG_ERR_NULL;
+  if (b < 0 || rows_bias < 0) return FG_ERR_SHAPE;
+  if (q_row_stride < cfg->h1 || q_row_stride % 8 != 0) return FG_ERR_SHAPE;
+  if (b == 0) return FG_OK;
+  if (!q_f16 || !out_f16) return FG_ERR_NULL;
+  return decode_attention_paged_launch(*cfg, reinterpret_cast<const half_t*>(q_f16), q_row_stride, b, *pages, *seqs,
+                                       rows_bias, reinterpret_cast<half_t*>(out_f16), as_stream(stream));
+}
 
 extern "C" int fg_decode_attention(const fg_model_cfg* cfg, const void* q_f16, int64_t q_row_stride, int32_t b,
                                    int32_t rows, const fg_kv_cache* kv, int32_t batch_offset, void* out_f16,

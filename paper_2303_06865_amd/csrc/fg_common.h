@@ -90,6 +90,9 @@ int layernorm_launch(const half_t* x, int64_t ldx, const half_t* g, const half_t
                      int64_t cols, float eps, half_t* out, int64_t ldo, hipStream_t stream);
 int embed_launch(const half_t* emb, const half_t* pos, const int32_t* ids, int64_t ids_stride, int64_t rows,
                  int32_t s_len, int32_t pos0, int32_t h1, int32_t vocab, half_t* out, hipStream_t stream);
+int embed_ragged_launch(const half_t* emb, const half_t* pos, const int32_t* ids, const int32_t* id_index,
+                        const int32_t* positions, int64_t rows, int32_t h1, int32_t vocab, int32_t max_pos,
+                        half_t* out, hipStream_t stream);
 int argmax_launch(const float* logits, int64_t rows, int64_t cols, int32_t* out, int64_t out_stride,
                   hipStream_t stream);
 
@@ -101,6 +104,15 @@ int decode_attention_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_
                             hipStream_t stream);
 int prefill_attention_launch(const fg_model_cfg& cfg, const half_t* qkv, int32_t b, int32_t s,
                              half_t* out, hipStream_t stream);
+// paged cache (sequences at different steps): s rows per sequence from position pos[i] (nullptr: 0);
+// attention over pos[i] + rows_bias rows
+int kv_append_paged_launch(const fg_model_cfg& cfg, const half_t* k, const half_t* v, int64_t row_stride,
+                           int32_t b, int32_t s, const fg_kv_pages& pages, const fg_ragged& seqs, bool use_pos,
+                           hipStream_t stream);
+int decode_attention_paged_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_stride, int32_t b,
+                                  const fg_kv_pages& pages, const fg_ragged& seqs, int32_t rows_bias, half_t* out,
+                                  hipStream_t stream);
+int check_pages(const fg_model_cfg* cfg, const fg_kv_pages* pages, const fg_ragged* seqs);
 
 // validation helpers (host only)
 int check_cfg(const fg_model_cfg* cfg);

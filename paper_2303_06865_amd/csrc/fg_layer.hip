@@ -86,6 +86,19 @@ int check_kv(const fg_model_cfg* cfg, const fg_kv_cache* kv) {
   return FG_OK;
 }
 
+int check_pages(const fg_model_cfg* cfg, const fg_kv_pages* pages, const fg_ragged* seqs) {
+  (void)cfg;
+  if (!pages || !seqs) return FG_ERR_NULL;
+  if (pages->dtype != FG_Q4G64 && pages->dtype != FG_Q4G64_H16) return FG_ERR_UNSUPPORTED;
+  if (pages->n_pages <= 0 || seqs->table_stride <= 0 || seqs->n_seqs <= 0) return FG_ERR_SHAPE;
+  if ((int64_t)seqs->table_stride * FG_PAGE_ROWS > 0x7fffffff) return FG_ERR_SHAPE;
+  if (!pages->k_codes || !pages->v_codes || !pages->k_meta || !pages->v_meta || !seqs->page_table) return FG_ERR_NULL;
+  if (!aligned16(pages->k_codes) || !aligned16(pages->v_codes) || !aligned16(pages->k_meta) ||
+      !aligned16(pages->v_meta))
+    return FG_ERR_SHAPE;
+  return FG_OK;
+}
+
 static int check_layer(const fg_model_cfg* cfg, const fg_layer_weights* w) {
   int rc;
   if ((rc = check_mat(&w->wqkv)) || (rc = check_mat(&w->wo)) || (rc = check_mat(&w->w1)) ||
@@ -183,9 +196,14 @@ static LayerWs carve_layer_ws(const fg_model_cfg& c, const fg_layer_weights& w, 
 // Section 3 with OPT's pre-LayerNorm placement.  prefill: s > 0 rows per sequence, causal attention
 // over the fresh K/V, rows stored at 0..s-1.  decode: one row per sequence, K/V appended at row t,
 // attention over rows 0..t read back from the cache.
+// paged != nullptr: the cache is *paged / *seqs instead of kv (rows of sequences at their own positions).
+struct PagedKv {
+  const fg_kv_pages* pages;
+  const fg_ragged* seqs;
+};
 static int run_layer(const fg_model_cfg& c, const fg_layer_weights& w, const half_t* x_in, int32_t b, int32_t s,
                      bool prefill, int32_t t, const fg_kv_cache& kv, int32_t batch_offset, half_t* x_out,
-                     void* ws, hipStream_t st) {
+                     void* ws, hipStream_t st, const PagedKv* paged = nullptr) {
   const int64_t rows = (int64_t)b * (prefill ? s : 1);
   const int64_t h1 = c.h1, h2 = c.h2;
   LayerWs L = carve_layer_ws(c, w, rows, ws);
@@ -196,7 +214,20 @@ static int run_layer(const fg_model_cfg& c, const fg_layer_weights& w, const hal
   if ((rc = linear_launch(make_linear(w.wqkv, w.bqkv, L.y, h1, rows, nullptr, 0, 0, L.qkv, 3 * h1), L.gemm,
                           L.gemm_bytes, st)))
     return rc;
-  if (prefill) {
+  if (paged) {
+    if (prefill) {
+      if ((rc = prefill_attention_launch(c, L.qkv, b, s, L.o, st))) return rc;
+      if ((rc = kv_append_paged_launch(c, L.qkv + h1, L.qkv + 2 * h1, 3 * h1, b, s, *paged->pages, *paged->seqs,
+                                       false, st)))
+        return rc;
+    } else {
+      if ((rc = kv_append_paged_launch(c, L.qkv + h1, L.qkv + 2 * h1, 3 * h1, b, 1, *paged->pages, *paged->seqs,
+                                       true, st)))
+        return rc;
+      if ((rc = decode_attention_paged_launch(c, L.qkv, 3 * h1, b, *paged->pages, *paged->seqs, 1, L.o, st)))
+        return rc;
+    }
+  } else if (prefill) {
     if ((rc = prefill_attention_launch(c, L.qkv, b, s, L.o, st))) return rc;
     if ((rc = kv_append_launch(c, L.qkv + h1, L.qkv + 2 * h1, 3 * h1, b, s, kv, batch_offset, 0, st))) return rc;
   } else {
@@ -434,6 +465,41 @@ extern "C" int fg_decode_layer(const fg_model_cfg* cfg, const fg_layer_weights* 
   if (!aligned16(ws)) return FG_ERR_SHAPE;
   return run_layer(*cfg, *wts, reinterpret_cast<const half_t*>(x_in), b, 1, false, t, *kv, batch_offset,
                    reinterpret_cast<half_t*>(x_out), ws, as_stream(stream));
+}
+
+static int paged_layer_entry(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in, int32_t b,
+                             int32_t s, bool prefill, const fg_kv_pages* pages, const fg_ragged* seqs, void* x_out,
+                             void* ws, size_t ws_bytes, void* stream) {
+  if (!cfg || !wts) return FG_ERR_NULL;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if ((rc = check_layer(cfg, wts))) return rc;
+  if ((rc = check_pages(cfg, pages, seqs))) return rc;
+  if (!prefill && !seqs->pos) return FG_ERR_NULL;
+  if (b < 0 || s < 0 || b > 65535 || (int64_t)b * s > 0x7fffffff) return FG_ERR_SHAPE;
+  if (prefill && s > (int64_t)seqs->table_stride * FG_PAGE_ROWS) return FG_ERR_SHAPE;
+  if (b == 0 || s == 0) return FG_OK;
+  if (!x_in || !x_out) return FG_ERR_NULL;
+  if (!aligned16(x_in) || !aligned16(x_out)) return FG_ERR_SHAPE;
+  const size_t need = carve_layer_ws(*cfg, *wts, (int64_t)b * s, nullptr).total;
+  if (!ws || ws_bytes < need) return FG_ERR_WORKSPACE;
+  if (!aligned16(ws)) return FG_ERR_SHAPE;
+  const PagedKv pk = {pages, seqs};
+  const fg_kv_cache none = {};
+  return run_layer(*cfg, *wts, reinterpret_cast<const half_t*>(x_in), b, s, prefill, 0, none, 0,
+                   reinterpret_cast<half_t*>(x_out), ws, as_stream(stream), &pk);
+}
+
+extern "C" int fg_decode_layer_paged(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in,
+                                     int32_t b, const fg_kv_pages* pages, const fg_ragged* seqs, void* x_out,
+                                     void* ws, size_t ws_bytes, void* stream) {
+  return paged_layer_entry(cfg, wts, x_in, b, 1, false, pages, seqs, x_out, ws, ws_bytes, stream);
+}
+
+extern "C" int fg_prefill_layer_paged(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in,
+                                      int32_t b, int32_t s, const fg_kv_pages* pages, const fg_ragged* seqs,
+                                      void* x_out, void* ws, size_t ws_bytes, void* stream) {
+  return paged_layer_entry(cfg, wts, x_in, b, s, true, pages, seqs, x_out, ws, ws_bytes, stream);
 }
 
 // ---------------------------------------------------------------- block generation

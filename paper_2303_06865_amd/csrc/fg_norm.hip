@@ -88,6 +88,35 @@ __global__ __launch_bounds__(256) void embed_kernel(const half_t* __restrict__ e
   }
 }
 
+// The same with a position per row (rows of sequences that are at different steps); row r takes
+// its token from ids[id_index[r]] (id_index == nullptr: ids[r]).
+__global__ __launch_bounds__(256) void embed_ragged_kernel(const half_t* __restrict__ emb,
+                                                           const half_t* __restrict__ pos,
+                                                           const int32_t* __restrict__ ids,
+                                                           const int32_t* __restrict__ id_index,
+                                                           const int32_t* __restrict__ positions, int64_t rows,
+                                                           int h1, int vocab, int max_pos,
+                                                           half_t* __restrict__ out) {
+  const int cpr = h1 >> 3;
+  const int64_t n = rows * cpr;
+  int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (; c < n; c += stride) {
+    const int64_t row = c / cpr;
+    const int ci = (int)(c - row * cpr);
+    int id = ids[id_index ? (int64_t)id_index[row] : row];
+    id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);   // never read outside the tables
+    int p = positions[row];
+    p = p < 0 ? 0 : (p >= max_pos ? max_pos - 1 : p);
+    const h8_t e = *reinterpret_cast<const h8_t*>(emb + (int64_t)id * h1 + ci * 8);
+    const h8_t q = *reinterpret_cast<const h8_t*>(pos + (int64_t)p * h1 + ci * 8);
+    h8_t o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (half_t)((float)e[i] + (float)q[i]);
+    *reinterpret_cast<h8_t*>(out + row * h1 + ci * 8) = o;
+  }
+}
+
 // Greedy token: argmax over a row of binary32 logits, lowest index on ties.
 __global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int64_t cols,
                                                      int32_t* __restrict__ out, int64_t out_stride) {
@@ -150,9 +179,37 @@ int embed_launch(const half_t* emb, const half_t* pos, const int32_t* ids, int64
   return FG_OK;
 }
 
+int embed_ragged_launch(const half_t* emb, const half_t* pos, const int32_t* ids, const int32_t* id_index,
+                        const int32_t* positions, int64_t rows, int32_t h1, int32_t vocab, int32_t max_pos,
+                        half_t* out, hipStream_t stream) {
+  if (rows == 0) return FG_OK;
+  const int64_t chunks = rows * (h1 / 8);
+  int64_t blocks = ceil_div(chunks, 256);
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  ProfScope prof(FG_K_EMBED, stream);
+  hipLaunchKernelGGL(embed_ragged_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, emb, pos, ids, id_index,
+                     positions, rows, (int)h1, (int)vocab, (int)max_pos, out);
+  FG_LAUNCH_CHECK();
+  return FG_OK;
+}
+
 }  // namespace fg
 
 using namespace fg;
+
+extern "C" int fg_embed_ragged(const fg_model_cfg* cfg, const void* embed_f16, const void* pos_f16,
+                               const int32_t* ids, const int32_t* positions, int64_t rows, void* out_f16,
+                               void* stream) {
+  if (!cfg) return FG_ERR_NULL;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if (rows < 0) return FG_ERR_SHAPE;
+  if (rows == 0) return FG_OK;
+  if (!embed_f16 || !pos_f16 || !ids || !positions || !out_f16) return FG_ERR_NULL;
+  return embed_ragged_launch(reinterpret_cast<const half_t*>(embed_f16), reinterpret_cast<const half_t*>(pos_f16), ids,
+                             nullptr, positions, rows, cfg->h1, cfg->vocab, cfg->max_pos,
+                             reinterpret_cast<half_t*>(out_f16), as_stream(stream));
+}
 
 extern "C" int fg_layernorm(const void* x_f16, const void* gamma_f16, const void* beta_f16, int64_t rows,
                             int64_t cols, float eps, void* out_f16, void* stream) {

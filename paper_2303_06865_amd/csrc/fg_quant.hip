@@ -116,7 +116,26 @@ struct KvAppendArgs {
   void* meta[2];
   int64_t ld;
   int32_t b, s, nh, dh, cap, batch_offset, pos0;
+  // paged destination (page_table != nullptr): row j of sequence i goes to position pos[i] + j of
+  // sequence seq_ids[i]; cap, batch_offset and pos0 are unused
+  const int32_t* page_table;
+  const int32_t* seq_ids;
+  const int32_t* pos;
+  int32_t table_stride, n_seqs, n_pages;
 };
+
+// First cache row index (in rows of dh elements) of (sequence bi, head, row offset j), or -1 if the
+// destination does not exist (paged: an id, position or page number out of range).
+__device__ __forceinline__ int64_t kv_dest_row(const KvAppendArgs& a, int64_t bi, int head, int j) {
+  if (!a.page_table) return ((int64_t)(a.batch_offset + bi) * a.nh + head) * a.cap + a.pos0 + j;
+  const int sid = a.seq_ids ? a.seq_ids[bi] : (int)bi;
+  const int p = (a.pos ? a.pos[bi] : 0) + j;
+  const int slot = p >> 6;
+  if (sid < 0 || sid >= a.n_seqs || p < 0 || slot >= a.table_stride) return -1;
+  const int page = a.page_table[(int64_t)sid * a.table_stride + slot];
+  if (page < 0 || page >= a.n_pages) return -1;
+  return ((int64_t)page * a.nh + head) * FG_PAGE_ROWS + (p & (FG_PAGE_ROWS - 1));
+}
 
 template <bool H16>
 __global__ __launch_bounds__(256) void kv_append_q4_kernel(KvAppendArgs a) {
@@ -135,12 +154,12 @@ __global__ __launch_bounds__(256) void kv_append_q4_kernel(KvAppendArgs a) {
     const int gi = (int)(g - row * gpr);
     const int head = gi / gph, gh = gi - head * gph;
     const int64_t bi = row / a.s;
-    const int pos = a.pos0 + (int)(row - bi * a.s);
     const h8_t v = *reinterpret_cast<const h8_t*>(x + row * a.ld + (int64_t)gi * kGroup + sub * 8);
     uint32_t p;
     float mn, sc;
-    quantize_group_8lanes<H16>(v, sub, p, mn, sc);
-    const int64_t crow = (((int64_t)(a.batch_offset + bi) * a.nh + head) * a.cap + pos);
+    quantize_group_8lanes<H16>(v, sub, p, mn, sc);   // all eight lanes of a group take part
+    const int64_t crow = kv_dest_row(a, bi, head, (int)(row - bi * a.s));
+    if (crow < 0) continue;
     codes[(crow * gph + gh) * 8 + sub] = p;
     if (sub == 0) {
       if (H16)
@@ -165,9 +184,8 @@ __global__ __launch_bounds__(256) void kv_append_f16_kernel(KvAppendArgs a) {
     const int ci = (int)(c - row * cpr);
     const int head = ci / cph, ch = ci - head * cph;
     const int64_t bi = row / a.s;
-    const int pos = a.pos0 + (int)(row - bi * a.s);
     const u4_t v = *reinterpret_cast<const u4_t*>(x + row * a.ld + (int64_t)ci * 8);
-    const int64_t crow = (((int64_t)(a.batch_offset + bi) * a.nh + head) * a.cap + pos);
+    const int64_t crow = kv_dest_row(a, bi, head, (int)(row - bi * a.s));
     *reinterpret_cast<u4_t*>(dst + crow * a.dh + ch * 8) = v;
   }
 }
@@ -199,6 +217,10 @@ int kv_append_launch(const fg_model_cfg& cfg, const half_t* k, const half_t* v, 
   a.cap = kv.cap;
   a.batch_offset = batch_offset;
   a.pos0 = pos0;
+  a.page_table = nullptr;
+  a.seq_ids = nullptr;
+  a.pos = nullptr;
+  a.table_stride = a.n_seqs = a.n_pages = 0;
   ProfScope prof(FG_K_KV_APPEND, stream);
   if (kv.dtype == FG_Q4G64 || kv.dtype == FG_Q4G64_H16) {
     const int64_t groups = (int64_t)b * s * cfg.h1 / kGroup;
@@ -212,6 +234,42 @@ int kv_append_launch(const fg_model_cfg& cfg, const half_t* k, const half_t* v, 
     dim3 grid(grid_for(chunks, 256), 2);
     hipLaunchKernelGGL(kv_append_f16_kernel, grid, dim3(256), 0, stream, a);
   }
+  FG_LAUNCH_CHECK();
+  return FG_OK;
+}
+
+int kv_append_paged_launch(const fg_model_cfg& cfg, const half_t* k, const half_t* v, int64_t row_stride,
+                           int32_t b, int32_t s, const fg_kv_pages& pages, const fg_ragged& seqs, bool use_pos,
+                           hipStream_t stream) {
+  if (b == 0 || s == 0) return FG_OK;
+  KvAppendArgs a;
+  a.src[0] = k;
+  a.src[1] = v;
+  a.codes[0] = pages.k_codes;
+  a.codes[1] = pages.v_codes;
+  a.meta[0] = pages.k_meta;
+  a.meta[1] = pages.v_meta;
+  a.ld = row_stride;
+  a.b = b;
+  a.s = s;
+  a.nh = cfg.nh;
+  a.dh = cfg.h1 / cfg.nh;
+  a.cap = 0;
+  a.batch_offset = 0;
+  a.pos0 = 0;
+  a.page_table = seqs.page_table;
+  a.seq_ids = seqs.seq_ids;
+  a.pos = use_pos ? seqs.pos : nullptr;
+  a.table_stride = seqs.table_stride;
+  a.n_seqs = seqs.n_seqs;
+  a.n_pages = pages.n_pages;
+  ProfScope prof(FG_K_KV_APPEND, stream);
+  const int64_t groups = (int64_t)b * s * cfg.h1 / kGroup;
+  dim3 grid(grid_for(groups, 32), 2);
+  if (pages.dtype == FG_Q4G64_H16)
+    hipLaunchKernelGGL(kv_append_q4_kernel<true>, grid, dim3(256), 0, stream, a);
+  else
+    hipLaunchKernelGGL(kv_append_q4_kernel<false>, grid, dim3(256), 0, stream, a);
   FG_LAUNCH_CHECK();
   return FG_OK;
 }
@@ -292,4 +350,20 @@ extern "C" int fg_kv_append(const fg_model_cfg* cfg, const void* k_f16, const vo
   if (!k_f16 || !v_f16) return FG_ERR_NULL;
   return kv_append_launch(*cfg, reinterpret_cast<const half_t*>(k_f16), reinterpret_cast<const half_t*>(v_f16),
                           row_stride, b, s, *kv, batch_offset, pos0, as_stream(stream));
+}
+
+extern "C" int fg_kv_append_paged(const fg_model_cfg* cfg, const void* k_f16, const void* v_f16, int64_t row_stride,
+                                  int32_t b, int32_t s, const fg_kv_pages* pages, const fg_ragged* seqs,
+                                  void* stream) {
+  if (!cfg) return FG_ERR_NULL;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  rc = check_pages(cfg, pages, seqs);
+  if (rc) return rc;
+  if (b < 0 || s < 0) return FG_ERR_SHAPE;
+  if (row_stride < cfg->h1 || row_stride % 8 != 0) return FG_ERR_SHAPE;
+  if (b == 0 || s == 0) return FG_OK;
+  if (!k_f16 || !v_f16) return FG_ERR_NULL;
+  return kv_append_paged_launch(*cfg, reinterpret_cast<const half_t*>(k_f16), reinterpret_cast<const half_t*>(v_f16),
+                                row_stride, b, s, *pages, *seqs, true, as_stream(stream));
 }
