@@ -316,6 +316,30 @@ int fg_prefill_layer_paged(const fg_model_cfg* cfg, const fg_layer_weights* wts,
 int fg_embed_ragged(const fg_model_cfg* cfg, const void* embed_f16, const void* pos_f16, const int32_t* ids,
                     const int32_t* positions, int64_t rows, void* out_f16, void* stream);
 
+/* Generation in the order of the appendix's diagonal block schedule, for a queue of n_seqs sequences
+ * (prompts of s tokens, n generated tokens each) cut into GPU batches of gpu_batch_size: batch g is
+ * admitted in iteration g, so in iteration `it` it is at token step it - g.  An iteration runs, layer
+ * by layer, the prefill of the admitted batch and ONE decode pass over all rows of the batches still
+ * generating (each layer's weights are streamed once for all of them), then emits one token per
+ * sequence in flight; n_seqs/gpu_batch_size + n - 1 iterations in all.  A batch is retired after its
+ * n-th token and its pages return to the pool; a sequence takes a page when it grows into one.
+ * The schedule only reorders independent work: out_ids equals fg_generate's for the same prompts.
+ * pages: host array of l pools with the same n_pages >= fg_diagonal_pages_needed(...) (else
+ * FG_ERR_WORKSPACE); their contents on entry do not matter.  prompt int32 [n_seqs, s] device; out_ids
+ * int32 [n_seqs, n] device.  ws >= fg_diagonal_workspace_bytes(...).  n_seqs % gpu_batch_size == 0.
+ * stats (host, may be NULL): decode_s holds the whole run (the phases interleave), prefill_s = 0,
+ * tokens = n_seqs * n.  peak_pages (host, may be NULL) receives the largest number of pages in use. */
+int fg_generate_diagonal(const fg_model_cfg* cfg, int32_t l, const fg_layer_weights* layers, const void* embed_f16,
+                         const void* pos_f16, const void* lnf_g, const void* lnf_b, const int32_t* prompt,
+                         int32_t n_seqs, int32_t s, int32_t n, int32_t gpu_batch_size, const fg_kv_pages* pages,
+                         int32_t* out_ids, void* ws, size_t ws_bytes, void* stream, fg_stats* stats,
+                         int32_t* peak_pages);
+size_t fg_diagonal_workspace_bytes(const fg_model_cfg* cfg, const fg_layer_weights* layer0, int32_t n_seqs,
+                                   int32_t s, int32_t n, int32_t gpu_batch_size);
+/* Pages per layer pool that the schedule above needs at its peak (host arithmetic only; -1 for bad
+ * arguments).  The block schedule needs n_seqs * ceil((s + n) / 64). */
+int64_t fg_diagonal_pages_needed(int32_t n_seqs, int32_t s, int32_t n, int32_t gpu_batch_size);
+
 /* ---- Per-kernel timing (HIP events on the caller's stream) -----------------------------
  * Between fg_profile_begin and fg_profile_end every kernel launch of the library is bracketed
  * by two events.  fg_profile_end synchronises and accumulates, per kernel class, the summed

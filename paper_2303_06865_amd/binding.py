@@ -116,6 +116,13 @@ EXPORTS = {
                                          C.c_void_p, C.c_size_t, C.c_void_p]),
     "fg_embed_ragged": (C.c_int, [C.POINTER(fg_model_cfg), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
                                   C.c_void_p, C.c_void_p]),
+    "fg_generate_diagonal": (C.c_int, [C.POINTER(fg_model_cfg), C.c_int32, C.POINTER(fg_layer_weights), C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                       C.c_int32, C.POINTER(fg_kv_pages), C.c_void_p, C.c_void_p, C.c_size_t,
+                                       C.c_void_p, C.POINTER(fg_stats), C.POINTER(C.c_int32)]),
+    "fg_diagonal_workspace_bytes": (C.c_size_t, [C.POINTER(fg_model_cfg), C.POINTER(fg_layer_weights), C.c_int32,
+                                                 C.c_int32, C.c_int32, C.c_int32]),
+    "fg_diagonal_pages_needed": (C.c_int64, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "fg_profile_begin": (C.c_int, []),
     "fg_profile_end": (C.c_int, []),
     "fg_profile_read": (C.c_int, [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
@@ -501,6 +508,31 @@ def fg_generate(cfg: Cfg, layers: Sequence[LayerWeights], embed: torch.Tensor, p
               "weight_bytes_per_step": stats.weight_bytes_per_step, "kv_bytes_last_step": stats.kv_bytes_last_step,
               "decode_step_s": [steps[i] for i in range(n - 1)]}
     return out_ids, sd
+
+
+def fg_diagonal_pages_needed(n_seqs: int, s: int, n: int, gpu_batch_size: int) -> int:
+    return lib().fg_diagonal_pages_needed(n_seqs, s, n, gpu_batch_size)
+
+
+def fg_generate_diagonal(cfg: Cfg, layers: Sequence[LayerWeights], embed: torch.Tensor, pos: torch.Tensor, lnf_g, lnf_b,
+                         prompt: torch.Tensor, n: int, gpu_batch_size: int, pages: Sequence[KVPages],
+                         ws: Optional[torch.Tensor] = None, out_ids: Optional[torch.Tensor] = None):
+    """Returns (ids int32 [n_seqs, n], {"total_s", "tokens", "peak_pages"})."""
+    assert prompt.dtype == torch.int32 and prompt.is_cuda and prompt.is_contiguous()
+    n_seqs, s = prompt.shape
+    l = len(layers)
+    larr = (fg_layer_weights * l)(*[w.c for w in layers])
+    parr = (fg_kv_pages * l)(*[p.c for p in pages])
+    if out_ids is None:
+        out_ids = torch.zeros((n_seqs, n), dtype=torch.int32, device=prompt.device)
+    if ws is None:
+        ws = _ws(lib().fg_diagonal_workspace_bytes(C.byref(cfg.c), C.byref(layers[0].c), n_seqs, s, n, gpu_batch_size))
+    stats = fg_stats(0.0, 0.0, 0, 0, 0, None)
+    peak = C.c_int32(0)
+    _check(lib().fg_generate_diagonal(C.byref(cfg.c), l, larr, _p(embed), _p(pos), _p(lnf_g), _p(lnf_b), _p(prompt),
+                                      n_seqs, s, n, gpu_batch_size, parr, _p(out_ids), _p(ws), ws.numel(), _stream(),
+                                      C.byref(stats), C.byref(peak)), "fg_generate_diagonal")
+    return out_ids, {"total_s": stats.decode_s, "tokens": stats.tokens, "peak_pages": peak.value}
 
 
 def fg_profile_begin() -> None:

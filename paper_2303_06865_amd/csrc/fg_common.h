@@ -94,7 +94,7 @@ int embed_ragged_launch(const half_t* emb, const half_t* pos, const int32_t* ids
                         const int32_t* positions, int64_t rows, int32_t h1, int32_t vocab, int32_t max_pos,
                         half_t* out, hipStream_t stream);
 int argmax_launch(const float* logits, int64_t rows, int64_t cols, int32_t* out, int64_t out_stride,
-                  hipStream_t stream);
+                  hipStream_t stream, const int32_t* out_index = nullptr);
 
 int kv_append_launch(const fg_model_cfg& cfg, const half_t* k, const half_t* v, int64_t row_stride,
                      int32_t b, int32_t s, const fg_kv_cache& kv, int32_t batch_offset, int32_t pos0,

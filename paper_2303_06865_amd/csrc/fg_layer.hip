@@ -267,7 +267,7 @@ static HeadWs carve_head_ws(const fg_model_cfg& c, int64_t rows, void* base) {
 
 static int run_lm_head(const fg_model_cfg& c, const half_t* x, int64_t ldx, int64_t rows, const half_t* g,
                        const half_t* bta, const half_t* emb, int32_t* out_ids, int64_t out_stride, float* logits,
-                       void* ws, hipStream_t st) {
+                       void* ws, hipStream_t st, const int32_t* out_index = nullptr) {
   HeadWs H = carve_head_ws(c, rows, ws);
   int rc;
   if ((rc = layernorm_launch(x, ldx, g, bta, rows, c.h1, c.ln_eps, H.y, c.h1, st))) return rc;
@@ -288,7 +288,7 @@ static int run_lm_head(const fg_model_cfg& c, const half_t* x, int64_t ldx, int6
   a.out_f32 = logits;
   a.ldo = c.vocab;
   if ((rc = linear_launch(a, H.gemm, H.gemm_bytes, st))) return rc;
-  return argmax_launch(logits, rows, c.vocab, out_ids, out_stride, st);
+  return argmax_launch(logits, rows, c.vocab, out_ids, out_stride, st, out_index);
 }
 
 }  // namespace fg
@@ -656,6 +656,278 @@ extern "C" int fg_generate(const fg_model_cfg* cfg, int32_t l, const fg_layer_we
     stats->kv_bytes_last_step = kv[0].dtype == FG_Q4G64       ? el / 2 + el / kGroup * 8
                                 : kv[0].dtype == FG_Q4G64_H16 ? el / 2 + el / kGroup * 4
                                                               : el * 2;
+    cleanup();
+  }
+  return FG_OK;
+}
+
+// ---------------------------------------------------------------- diagonal block schedule
+namespace {
+// Host bookkeeping of the diagonal order (appendix, "Diagonal block schedule"): GPU batch g is admitted
+// in iteration g, so in iteration `it` it is at token step it - g; it is retired after step n - 1.
+// Pages are taken one at a time as a sequence grows and returned when its batch retires.
+struct DiagPlan {
+  int n_seqs, s, n, gbs, ng, max_pages;
+  std::vector<int32_t> table;   // [n_seqs][max_pages], -1 = none
+  std::vector<int32_t> free_list;
+  int in_use = 0, peak = 0;
+  DiagPlan(int n_seqs_, int s_, int n_, int gbs_, int pool_pages)
+      : n_seqs(n_seqs_), s(s_), n(n_), gbs(gbs_), ng(n_seqs_ / gbs_),
+        max_pages((s_ + n_ + FG_PAGE_ROWS - 1) / FG_PAGE_ROWS), table((size_t)n_seqs_ * max_pages, -1) {
+    free_list.reserve(pool_pages);
+    for (int p = pool_pages - 1; p >= 0; --p) free_list.push_back(p);
+  }
+  int iterations() const { return ng + n - 1; }
+  bool ensure(int seq, int rows) {   // pages for positions 0 .. rows-1
+    const int need = (rows + FG_PAGE_ROWS - 1) / FG_PAGE_ROWS;
+    for (int slot = 0; slot < need; ++slot) {
+      int32_t& e = table[(size_t)seq * max_pages + slot];
+      if (e >= 0) continue;
+      if (free_list.empty()) return false;
+      e = free_list.back();
+      free_list.pop_back();
+      ++in_use;
+    }
+    peak = in_use > peak ? in_use : peak;
+    return true;
+  }
+  void release(int seq) {
+    for (int slot = 0; slot < max_pages; ++slot) {
+      int32_t& e = table[(size_t)seq * max_pages + slot];
+      if (e >= 0) {
+        free_list.push_back(e);
+        e = -1;
+        --in_use;
+      }
+    }
+  }
+  // groups active in iteration it: [g_lo, g_hi]; the admitted one (if any) is `it` itself
+  void active(int it, int& g_lo, int& g_hi) const {
+    g_lo = it - (n - 1) > 0 ? it - (n - 1) : 0;
+    g_hi = it < ng - 1 ? it : ng - 1;
+  }
+  // Takes the pages iteration `it` needs; false if the pool runs dry.
+  bool begin_iteration(int it) {
+    int g_lo, g_hi;
+    active(it, g_lo, g_hi);
+    for (int g = g_lo; g <= g_hi; ++g) {
+      const int rows = g == it ? s : s + (it - g);   // after this iteration's append
+      for (int q = g * gbs; q < (g + 1) * gbs; ++q)
+        if (!ensure(q, rows)) return false;
+    }
+    return true;
+  }
+  void end_iteration(int it) {
+    const int g = it - (n - 1);
+    if (g >= 0 && g < ng)
+      for (int q = g * gbs; q < (g + 1) * gbs; ++q) release(q);
+  }
+};
+
+struct DiagWs {
+  half_t* x_new;    // [gbs*s, h1]
+  half_t* x_dec;    // [bmax, h1]
+  float* logits;    // [max(gbs, bmax), vocab]
+  int32_t* ints;    // page table and the per-iteration row arrays
+  size_t n_ints;
+  void* layer;
+  size_t layer_bytes;
+  void* head;
+  size_t total;
+};
+int diag_bmax(int n_seqs, int n, int gbs) {
+  const int ng = n_seqs / gbs;
+  const int groups = ng < n - 1 ? ng : n - 1;
+  return groups * gbs;
+}
+DiagWs carve_diag_ws(const fg_model_cfg& c, const fg_layer_weights& w0, int n_seqs, int s, int n, int gbs,
+                     void* base) {
+  DiagWs D;
+  unsigned char* p = reinterpret_cast<unsigned char*>(base);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    unsigned char* r = p ? p + off : nullptr;
+    off += align_up(bytes, 256);
+    return r;
+  };
+  const int bmax = diag_bmax(n_seqs, n, gbs);
+  const int brow = bmax > 0 ? bmax : 1;
+  const int max_pages = (s + n + FG_PAGE_ROWS - 1) / FG_PAGE_ROWS;
+  D.x_new = reinterpret_cast<half_t*>(take((size_t)gbs * s * c.h1 * 2));
+  D.x_dec = reinterpret_cast<half_t*>(take((size_t)brow * c.h1 * 2));
+  D.logits = reinterpret_cast<float*>(take((size_t)(gbs > brow ? gbs : brow) * c.vocab * 4));
+  D.n_ints = (size_t)n_seqs * max_pages + gbs + 4 * (size_t)brow;
+  D.ints = reinterpret_cast<int32_t*>(take(D.n_ints * 4));
+  const size_t lp = carve_layer_ws(c, w0, (int64_t)gbs * s, nullptr).total;
+  const size_t ld = carve_layer_ws(c, w0, brow, nullptr).total;
+  D.layer_bytes = lp > ld ? lp : ld;
+  D.layer = take(D.layer_bytes);
+  D.head = take(carve_head_ws(c, gbs > brow ? gbs : brow, nullptr).total);
+  D.total = off;
+  return D;
+}
+bool diag_args_ok(int32_t n_seqs, int32_t s, int32_t n, int32_t gbs) {
+  return n_seqs > 0 && s > 0 && n > 0 && gbs > 0 && n_seqs % gbs == 0 && (int64_t)n_seqs * n <= 0x7fffffff &&
+         (int64_t)gbs * s <= 0x7fffffff && diag_bmax(n_seqs, n, gbs) <= 65535;
+}
+}  // namespace
+
+extern "C" int64_t fg_diagonal_pages_needed(int32_t n_seqs, int32_t s, int32_t n, int32_t gpu_batch_size) {
+  if (!diag_args_ok(n_seqs, s, n, gpu_batch_size)) return -1;
+  const int64_t all = (int64_t)n_seqs * ((s + n + FG_PAGE_ROWS - 1) / FG_PAGE_ROWS);
+  if (all > 0x7fffffff) return -1;
+  DiagPlan plan(n_seqs, s, n, gpu_batch_size, (int)all);
+  for (int it = 0; it < plan.iterations(); ++it) {
+    plan.begin_iteration(it);
+    plan.end_iteration(it);
+  }
+  return plan.peak;
+}
+
+extern "C" size_t fg_diagonal_workspace_bytes(const fg_model_cfg* cfg, const fg_layer_weights* layer0, int32_t n_seqs,
+                                              int32_t s, int32_t n, int32_t gpu_batch_size) {
+  if (!cfg || !layer0 || check_cfg(cfg) || !diag_args_ok(n_seqs, s, n, gpu_batch_size)) return 0;
+  return carve_diag_ws(*cfg, *layer0, n_seqs, s, n, gpu_batch_size, nullptr).total;
+}
+
+extern "C" int fg_generate_diagonal(const fg_model_cfg* cfg, int32_t l, const fg_layer_weights* layers,
+                                    const void* embed_f16, const void* pos_f16, const void* lnf_g, const void* lnf_b,
+                                    const int32_t* prompt, int32_t n_seqs, int32_t s, int32_t n,
+                                    int32_t gpu_batch_size, const fg_kv_pages* pages, int32_t* out_ids, void* ws,
+                                    size_t ws_bytes, void* stream, fg_stats* stats, int32_t* peak_pages) {
+  if (!cfg || !layers || !pages) return FG_ERR_NULL;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if (l <= 0 || !diag_args_ok(n_seqs, s, n, gpu_batch_size)) return FG_ERR_SHAPE;
+  if ((int64_t)s + n - 1 > cfg->max_pos || cfg->vocab % 8 != 0) return FG_ERR_SHAPE;
+  const int gbs = gpu_batch_size;
+  for (int j = 0; j < l; ++j) {
+    if ((rc = check_layer(cfg, &layers[j]))) return rc;
+    if (pages[j].dtype != FG_Q4G64 && pages[j].dtype != FG_Q4G64_H16) return FG_ERR_UNSUPPORTED;
+    if (pages[j].n_pages != pages[0].n_pages || pages[j].n_pages <= 0) return FG_ERR_SHAPE;
+    if (!pages[j].k_codes || !pages[j].v_codes || !pages[j].k_meta || !pages[j].v_meta) return FG_ERR_NULL;
+    if (layers[j].wqkv.dtype != layers[0].wqkv.dtype || layers[j].wo.dtype != layers[0].wo.dtype ||
+        layers[j].w1.dtype != layers[0].w1.dtype || layers[j].w2.dtype != layers[0].w2.dtype)
+      return FG_ERR_UNSUPPORTED;
+  }
+  if (!embed_f16 || !pos_f16 || !lnf_g || !lnf_b || !prompt || !out_ids) return FG_ERR_NULL;
+  const int64_t needed = fg_diagonal_pages_needed(n_seqs, s, n, gbs);
+  if (needed < 0 || pages[0].n_pages < needed) return FG_ERR_WORKSPACE;   // the pool cannot hold the schedule
+  const DiagWs need = carve_diag_ws(*cfg, layers[0], n_seqs, s, n, gbs, nullptr);
+  if (!ws || ws_bytes < need.total) return FG_ERR_WORKSPACE;
+  if (!aligned16(ws)) return FG_ERR_SHAPE;
+  const DiagWs D = carve_diag_ws(*cfg, layers[0], n_seqs, s, n, gbs, ws);
+  hipStream_t st = as_stream(stream);
+  const half_t* emb = reinterpret_cast<const half_t*>(embed_f16);
+  const half_t* pos = reinterpret_cast<const half_t*>(pos_f16);
+  const half_t* fg_ = reinterpret_cast<const half_t*>(lnf_g);
+  const half_t* fb_ = reinterpret_cast<const half_t*>(lnf_b);
+  const int64_t h1 = cfg->h1;
+
+  DiagPlan plan(n_seqs, s, n, gbs, pages[0].n_pages);
+  const int bmax = diag_bmax(n_seqs, n, gbs) > 0 ? diag_bmax(n_seqs, n, gbs) : 1;
+  // device int32 arrays, refreshed once per iteration in one copy: the page table, the admitted batch's
+  // sequence ids, and per decode row: sequence, position, where its input token is, where its output goes
+  const size_t tab_n = (size_t)n_seqs * plan.max_pages;
+  int32_t* d_table = D.ints;
+  int32_t* d_new = d_table + tab_n;
+  int32_t* d_seq = d_new + gbs;
+  int32_t* d_pos = d_seq + bmax;
+  int32_t* d_in = d_pos + bmax;
+  int32_t* d_out = d_in + bmax;
+  std::vector<int32_t> h(D.n_ints, 0);
+
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  auto cleanup = [&]() {
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  };
+#define FG_TRY(expr)       \
+  do {                     \
+    int _rc = (expr);      \
+    if (_rc) {             \
+      cleanup();           \
+      return _rc;          \
+    }                      \
+  } while (0)
+  if (stats) {
+    FG_HIP(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) {
+      cleanup();
+      return FG_ERR_DEVICE;
+    }
+    if (hipEventRecord(e0, st) != hipSuccess) {
+      cleanup();
+      return FG_ERR_DEVICE;
+    }
+  }
+  for (int it = 0; it < plan.iterations(); ++it) {
+    if (!plan.begin_iteration(it)) {
+      cleanup();
+      return FG_ERR_WORKSPACE;
+    }
+    int g_lo, g_hi;
+    plan.active(it, g_lo, g_hi);
+    const bool admit = it < plan.ng;
+    int b = 0;   // decode rows of this iteration: every sequence of the batches at steps 1 .. n-1
+    for (int g = g_lo; g <= g_hi; ++g) {
+      const int step = it - g;
+      if (step == 0) continue;
+      for (int q = g * gbs; q < (g + 1) * gbs; ++q, ++b) {
+        h[tab_n + gbs + b] = q;
+        h[tab_n + gbs + bmax + b] = s + step - 1;             // rows already cached = position of the fed-back token
+        h[tab_n + gbs + 2 * (size_t)bmax + b] = q * n + step - 1;   // its id in out_ids
+        h[tab_n + gbs + 3 * (size_t)bmax + b] = q * n + step;       // where this step's id goes
+      }
+    }
+    memcpy(h.data(), plan.table.data(), tab_n * 4);
+    if (admit)
+      for (int i = 0; i < gbs; ++i) h[tab_n + i] = it * gbs + i;
+    // the copy is ordered behind the previous iteration's kernels on the stream; the host buffer is
+    // pageable, so the call has taken its contents by the time it returns
+    if (hipMemcpyAsync(D.ints, h.data(), D.n_ints * 4, hipMemcpyHostToDevice, st) != hipSuccess) {
+      cleanup();
+      return FG_ERR_DEVICE;
+    }
+    fg_ragged rn = {d_table, d_new, nullptr, plan.max_pages, n_seqs};
+    fg_ragged rd = {d_table, d_seq, d_pos, plan.max_pages, n_seqs};
+    if (admit)
+      FG_TRY(embed_launch(emb, pos, prompt + (int64_t)it * gbs * s, 1, (int64_t)gbs * s, s, 0, cfg->h1, cfg->vocab,
+                          D.x_new, st));
+    if (b > 0)
+      FG_TRY(embed_ragged_launch(emb, pos, out_ids, d_in, d_pos, b, cfg->h1, cfg->vocab, cfg->max_pos, D.x_dec, st));
+    // one diagonal: layer by layer, the admitted batch's prefill square and the decode squares of the rest
+    const fg_kv_cache none = {};
+    for (int j = 0; j < l; ++j) {
+      if (admit) {
+        const PagedKv pk = {&pages[j], &rn};
+        FG_TRY(run_layer(*cfg, layers[j], D.x_new, gbs, s, true, 0, none, 0, D.x_new, D.layer, st, &pk));
+      }
+      if (b > 0) {
+        const PagedKv pk = {&pages[j], &rd};
+        FG_TRY(run_layer(*cfg, layers[j], D.x_dec, b, 1, false, 0, none, 0, D.x_dec, D.layer, st, &pk));
+      }
+    }
+    if (admit)
+      FG_TRY(run_lm_head(*cfg, D.x_new + (int64_t)(s - 1) * h1, (int64_t)s * h1, gbs, fg_, fb_, emb,
+                         out_ids + (int64_t)it * gbs * n, n, D.logits, D.head, st));
+    if (b > 0) FG_TRY(run_lm_head(*cfg, D.x_dec, h1, b, fg_, fb_, emb, out_ids, 0, D.logits, D.head, st, d_out));
+    plan.end_iteration(it);
+  }
+#undef FG_TRY
+  if (peak_pages) *peak_pages = plan.peak;
+  if (stats) {
+    float ms = 0.f;
+    if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) {
+      cleanup();
+      return FG_ERR_DEVICE;
+    }
+    (void)hipEventElapsedTime(&ms, e0, e1);
+    stats->prefill_s = 0.0;          // the phases interleave: the whole run is reported as one figure
+    stats->decode_s = ms * 1e-3;
+    stats->tokens = (int64_t)n_seqs * n;
+    stats->weight_bytes_per_step = 0;
+    stats->kv_bytes_last_step = 0;
     cleanup();
   }
   return FG_OK;

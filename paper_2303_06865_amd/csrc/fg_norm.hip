@@ -118,8 +118,10 @@ __global__ __launch_bounds__(256) void embed_ragged_kernel(const half_t* __restr
 }
 
 // Greedy token: argmax over a row of binary32 logits, lowest index on ties.
+// Row r's result goes to out[r * out_stride], or to out[out_index[r]] when out_index is given.
 __global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ logits, int64_t cols,
-                                                     int32_t* __restrict__ out, int64_t out_stride) {
+                                                     int32_t* __restrict__ out, int64_t out_stride,
+                                                     const int32_t* __restrict__ out_index) {
   __shared__ float bv[4];
   __shared__ int bi[4];
   const float* r = logits + (int64_t)blockIdx.x * cols;
@@ -153,15 +155,17 @@ __global__ __launch_bounds__(256) void argmax_kernel(const float* __restrict__ l
         best = bv[k];
         idx = bi[k];
       }
-    out[(int64_t)blockIdx.x * out_stride] = idx == 0x7fffffff ? 0 : idx;
+    const int64_t dst = out_index ? (int64_t)out_index[blockIdx.x] : (int64_t)blockIdx.x * out_stride;
+    out[dst] = idx == 0x7fffffff ? 0 : idx;
   }
 }
 
 int argmax_launch(const float* logits, int64_t rows, int64_t cols, int32_t* out, int64_t out_stride,
-                  hipStream_t stream) {
+                  hipStream_t stream, const int32_t* out_index) {
   if (rows == 0) return FG_OK;
   ProfScope prof(FG_K_ARGMAX, stream);
-  hipLaunchKernelGGL(argmax_kernel, dim3((unsigned)rows), dim3(256), 0, stream, logits, cols, out, out_stride);
+  hipLaunchKernelGGL(argmax_kernel, dim3((unsigned)rows), dim3(256), 0, stream, logits, cols, out, out_stride,
+                     out_index);
   FG_LAUNCH_CHECK();
   return FG_OK;
 }

@@ -6,6 +6,7 @@ algorithmic bytes / flops per launch.  It exists so that `rocprofv3 --kernel-tra
   python3 -m paper_2303_06865_amd.kernel_bench linear --m 144 --n 36864 --k 12288 --wdtype q4t
   python3 -m paper_2303_06865_amd.kernel_bench attn_decode --batch 144 --nh 96 --rows 528
   python3 -m paper_2303_06865_amd.kernel_bench attn_decode_topk --batch 144 --nh 96 --rows 528 --topk 53
+  python3 -m paper_2303_06865_amd.kernel_bench attn_decode_paged --batch 144 --nh 96 --rows 528
   python3 -m paper_2303_06865_amd.kernel_bench attn_prefill --batch 8 --nh 96 --seq 512
   python3 -m paper_2303_06865_amd.kernel_bench copy --mib 1024      # calibration for HBM counters
 
@@ -47,7 +48,8 @@ def _torch_time(fn, iters, warm):
 
 def main(argv=None):
     ap = argparse.ArgumentParser()
-    ap.add_argument("op", choices=["linear", "attn_decode", "attn_decode_topk", "attn_prefill", "copy"])
+    ap.add_argument("op", choices=["linear", "attn_decode", "attn_decode_topk", "attn_decode_paged", "attn_prefill",
+                                   "copy"])
     ap.add_argument("--m", type=int, default=144)
     ap.add_argument("--n", type=int, default=36864)
     ap.add_argument("--k", type=int, default=12288)
@@ -105,6 +107,27 @@ def main(argv=None):
                        flops=4 * a.batch * a.nh * a.rows * a.dh)
             out["classes"] = _time_classes(lambda: B.fg_decode_attention(cfg, qkv, 3 * h1, a.batch, a.rows, kv, 0),
                                            a.iters, a.warmup)
+    elif a.op == "attn_decode_paged":
+        # every sequence `rows` long, its pages scattered over the pool by a random permutation
+        h1 = a.nh * a.dh
+        cfg = B.Cfg(h1, a.nh, 4 * h1, 50272, 4096)
+        h16 = a.kv == "q4h"
+        assert a.kv != "f16", "pages hold 4-bit rows only"
+        kvb = 0.5625 if h16 else 0.625
+        per_seq = -(-a.rows // B.PAGE_ROWS)
+        n_pages = a.batch * per_seq
+        pages = B.KVPages(cfg, n_pages, h16, zero=False)
+        pages.k_codes.random_(0, 256)
+        pages.v_codes.random_(0, 256)
+        pages.k_meta.copy_(torch.randn(pages.k_meta.shape, device=dev).abs_().mul_(0.3))
+        pages.v_meta.copy_(torch.randn(pages.v_meta.shape, device=dev).abs_().mul_(0.3))
+        table = torch.randperm(n_pages, device=dev).to(torch.int32).reshape(a.batch, per_seq).contiguous()
+        seqs = B.Ragged(table, None, torch.full((a.batch,), a.rows, dtype=torch.int32, device=dev))
+        qkv = torch.randn(a.batch, 3 * h1, device=dev, dtype=torch.float16)
+        out.update(batch=a.batch, nh=a.nh, dh=a.dh, rows=a.rows, kv=a.kv,
+                   bytes=int(2 * a.batch * a.nh * a.rows * a.dh * kvb), flops=4 * a.batch * a.nh * a.rows * a.dh)
+        out["classes"] = _time_classes(lambda: B.fg_decode_attention_paged(cfg, qkv, 3 * h1, a.batch, pages, seqs, 0),
+                                       a.iters, a.warmup)
     elif a.op == "attn_prefill":
         h1 = a.nh * a.dh
         cfg = B.Cfg(h1, a.nh, 4 * h1, 50272, 4096)

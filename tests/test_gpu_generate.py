@@ -105,3 +105,46 @@ def test_generate_single_token_and_async_call():
                                dev(prompt), 1, 1, 3, kv, want_stats=False)
     torch.cuda.synchronize()
     assert stats is None and np.array_equal(host(ids), ref)
+
+
+# ------------------------------------------------------------------ diagonal block schedule
+@pytest.mark.parametrize("n_seqs,gbs,s,n,meta_f16", [
+    (6, 2, 11, 6, False),     # fewer batches than steps: all in flight together
+    (8, 1, 9, 3, False),      # more batches than steps: pages are recycled
+    (4, 2, 60, 7, True),      # sequences grow across a page boundary; FP16-pair pages
+    (3, 3, 5, 1, False),      # n = 1: prefill iterations only
+])
+def test_generate_diagonal_schedule(n_seqs, gbs, s, n, meta_f16):
+    """Appendix, diagonal block schedule over paged caches: the ids are those of the oracle's block
+    schedule (the oracle pins its own diagonal order to it), the page peak is the oracle's."""
+    sh = synth.Shape(h1=256, nh=4, h2=512, vocab=2000, max_pos=96, l=3)
+    ocfg, cfg, olayers, layers, m = _models(sh, 11, True, 0.08, True, True)
+    prompt = synth.prompt_ids(n_seqs, s, sh.vocab, 13)
+    ref, logits, _ = O.generate(ocfg, olayers, m["embed"], m["pos"], m["lnf_g"], m["lnf_b"], prompt, n, n_seqs // gbs,
+                                gbs, True, return_trace=True)
+    _, opeak = O.generate_diagonal(ocfg, olayers[:1], m["embed"], m["pos"], m["lnf_g"], m["lnf_b"], prompt, n, gbs,
+                                   return_page_use=True)
+    need = B.fg_diagonal_pages_needed(n_seqs, s, n, gbs)
+    assert need == opeak
+    pages = [B.KVPages(cfg, need, meta_f16, zero=False) for _ in layers]
+    for p in pages:     # the pool's previous contents must not matter
+        p.k_codes.random_(0, 256)
+        p.v_codes.random_(0, 256)
+    ids, st = B.fg_generate_diagonal(cfg, layers, dev(m["embed"]), dev(m["pos"]), dev(m["lnf_g"]), dev(m["lnf_b"]),
+                                     dev(prompt), n, gbs, pages)
+    torch.cuda.synchronize()
+    got = host(ids)
+    assert got.shape == (n_seqs, n) and st["tokens"] == n_seqs * n and st["peak_pages"] == need and st["total_s"] > 0
+    assert _compare_ids(got, ref, logits, 1e-2) <= 1
+
+
+def test_generate_diagonal_rejects_a_pool_that_is_too_small():
+    sh = synth.Shape(h1=128, nh=2, h2=256, vocab=520, max_pos=96, l=1)
+    ocfg, cfg, olayers, layers, m = _models(sh, 9, True, 0.08, True, True)
+    prompt = synth.prompt_ids(4, 70, sh.vocab, 9)
+    need = B.fg_diagonal_pages_needed(4, 70, 4, 1)
+    assert need == 8 and B.fg_diagonal_pages_needed(4, 70, 4, 3) == -1
+    pages = [B.KVPages(cfg, need - 1)]
+    with pytest.raises(RuntimeError):
+        B.fg_generate_diagonal(cfg, layers, dev(m["embed"]), dev(m["pos"]), dev(m["lnf_g"]), dev(m["lnf_b"]),
+                               dev(prompt), 4, 1, pages)
