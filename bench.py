@@ -40,6 +40,10 @@ WORKLOADS = {
     # ... and with the weights' pairs in FP16 as well: 4.5 bits per stored element everywhere
     "opt175b_q4_h16": ("OPT_175B", "h16", "h16", 4, 36, 512, 32),
     "kv_stress_175b_layer_h16kv": ("OPT_175B", True, "h16", 1, 512, 2048, 64),
+    # the appendix's diagonal block schedule over paged caches (run_diagonal): the same 144 sequences
+    # admitted four at a time; and the 128+128 setting, where the staggered lengths save cache memory
+    "opt175b_q4_diagonal": ("OPT_175B", True, True, 36, 4, 512, 32),
+    "opt175b_q4_128_128_diagonal": ("OPT_175B", True, True, 36, 4, 128, 128),
     "opt30b_q4": ("OPT_30B", True, True, 8, 32, 512, 32),
     "opt6.7b_f16": ("OPT_6_7B", False, False, 4, 32, 512, 32),
     "opt125m_layer_q4": ("OPT_125M_LAYER", True, True, 1, 4, 32, 9),
@@ -206,6 +210,78 @@ def run_kv_stress(args, torch, B, synth):
     print(json.dumps(line))
 
 
+def run_diagonal(args, torch, B, synth):
+    """The whole queue of ngb x gbs sequences generated in the diagonal order (fg_generate_diagonal):
+    one GPU batch admitted per iteration, paged 4-bit caches sized by fg_diagonal_pages_needed."""
+    shape_name, wq, kvq, ngb, gbs, s, n = WORKLOADS[args.workload]
+    sh = getattr(synth, shape_name)
+    if args.layers:
+        sh = synth.Shape(sh.h1, sh.nh, sh.h2, sh.vocab, sh.max_pos, args.layers, sh.ln_eps)
+    n_seqs = ngb * gbs
+    cfg = B.Cfg(sh.h1, sh.nh, sh.h2, sh.vocab, sh.max_pos, sh.ln_eps)
+    t_setup = time.time()
+    layers, emb, pos, lnf_g, lnf_b = build_model(sh, wq, args.seed, torch, B)
+    need = B.fg_diagonal_pages_needed(n_seqs, s, n, gbs)
+    pages = [B.KVPages(cfg, need, kvq == "h16", zero=False) for _ in range(sh.l)]
+    ws = torch.empty(B.lib().fg_diagonal_workspace_bytes(B.C.byref(cfg.c), B.C.byref(layers[0].c), n_seqs, s, n, gbs),
+                     dtype=torch.uint8, device="cuda")
+    out_ids = torch.zeros((n_seqs, n), dtype=torch.int32, device="cuda")
+    prompt = torch.from_numpy(synth.prompt_ids(n_seqs, s, sh.vocab, args.seed)).cuda()
+    torch.cuda.synchronize()
+    resident = sum(w.nbytes() for w in layers) + sum(p.nbytes() for p in pages) + emb.numel() * 2 + pos.numel() * 2
+    t_setup = time.time() - t_setup
+
+    def step():
+        return B.fg_generate_diagonal(cfg, layers, emb, pos, lnf_g, lnf_b, prompt, n, gbs, pages, ws=ws, out_ids=out_ids)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.fg_profile_begin()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        _, st = step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = B.fg_profile_end()
+    K = args.steps
+    P = 4 * sh.h1 * sh.h1 + 2 * sh.h1 * sh.h2
+    rl = {}
+    for name, bound, work in (("gemm_large_m", "mfma", 2.0 * n_seqs * s * P * sh.l),
+                              ("gemm_small_m", "mfma", 2.0 * n_seqs * (n - 1) * (sh.l * P + sh.vocab * sh.h1)
+                               + 2.0 * n_seqs * sh.vocab * sh.h1),
+                              ("attn_decode", "hbm", sum(2.0 * n_seqs * sh.l * sh.h1 * (s + i) * bpe(kvq)
+                                                         for i in range(1, n)))):
+        if name not in prof:
+            continue
+        ms = prof[name]["ms"] / K
+        peak = HBM_PEAK if bound == "hbm" else MFMA_F16_PEAK
+        ach = work / (ms * 1e-3)
+        rl[name] = {"bound": bound, "achieved": ach / (1e9 if bound == "hbm" else 1e12),
+                    "peak": peak / (1e9 if bound == "hbm" else 1e12), "unit": "GB/s" if bound == "hbm" else "TFLOP/s",
+                    "frac": ach / peak, "traffic": None, "ms_per_step": ms,
+                    "launches_per_step": prof[name]["launches"] / K,
+                    "avg_launch_us": 1e3 * prof[name]["ms"] / prof[name]["launches"]}
+    dominant = max(rl, key=lambda k: rl[k]["ms_per_step"])
+    block_pages = n_seqs * -(-(s + n) // B.PAGE_ROWS)
+    line = {
+        "metric": "generated tokens/s + % peak HBM BW, 4-bit OPT-175B-shape decode, 1 GPU",
+        "value": n_seqs * n * K / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": 1e3 * elapsed / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": args.workload + ("" if not args.layers else "_%dlayers" % args.layers),
+                   "shape": {"l": sh.l, "h1": sh.h1, "nh": sh.nh, "h2": sh.h2, "vocab": sh.vocab},
+                   "weights": "q4g64_h16" if wq == "h16" else "q4g64",
+                   "kv_cache": "paged " + ("q4g64_h16" if kvq == "h16" else "q4g64"), "schedule": "diagonal",
+                   "sequences": n_seqs, "admitted_per_iteration": gbs, "iterations": ngb + n - 1,
+                   "prompt_len": s, "gen_len": n, "resident_gb": resident / 1e9, "setup_s": t_setup,
+                   "peak_pages_per_layer": st["peak_pages"], "block_schedule_pages_per_layer": block_pages},
+        "roofline": dict(rl[dominant], kernel=dominant), "roofline_kernels": rl,
+        "kernel_ms": {k: v["ms"] / K for k, v in prof.items() if v["launches"]},
+    }
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -232,6 +308,8 @@ def main():
 
     if args.workload.startswith("kv_stress"):
         return run_kv_stress(args, torch, B, synth)
+    if args.workload.endswith("_diagonal"):
+        return run_diagonal(args, torch, B, synth)
     shape_name, wq, kvq, ngb, gbs, s, n = WORKLOADS[args.workload]
     sh = getattr(synth, shape_name)
     if args.layers:
