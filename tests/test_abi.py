@@ -133,3 +133,53 @@ def test_workspace_queries_are_pure_host_functions():
     g = L.fg_workspace_bytes(C.byref(cfg), C.byref(w), 4, 1, 32)
     assert g >= p + 4 * 32 * 768 * 2 + 4 * 50272 * 4
     assert L.fg_workspace_bytes(C.byref(cfg), C.byref(w), 0, 1, 32) == 0
+
+
+def test_paged_and_diagonal_argument_errors_need_no_gpu():
+    L = B.lib()
+    cfg = _cfg()
+    a = 4096
+    mat = lambda r, c, dt=B.FG_Q4G64: B.fg_mat(a, a, dt, 0, r, c)
+    w = B.fg_layer_weights(mat(2304, 768), mat(768, 768), mat(3072, 768), mat(768, 3072), None, None, None, None,
+                           a, a, a, a)
+    assert C.sizeof(B.fg_kv_pages) == 40 and C.sizeof(B.fg_ragged) == 32
+    pages = B.fg_kv_pages(a, a, a, a, B.FG_Q4G64, 8)
+    seqs = B.fg_ragged(a, None, a, 2, 4)
+    ws = C.c_void_p(a)
+    att = lambda pg=pages, sq=seqs, b=4, bias=1, stride=2304: L.fg_decode_attention_paged(
+        C.byref(cfg), a, stride, b, C.byref(pg), C.byref(sq), bias, a, None)
+    assert att(pg=B.fg_kv_pages(a, a, a, a, B.FG_F16, 8)) == B.FG_ERR_UNSUPPORTED     # pages hold 4-bit rows only
+    assert att(pg=B.fg_kv_pages(a, a, a, a, B.FG_Q4G64, 0)) == B.FG_ERR_SHAPE
+    assert att(pg=B.fg_kv_pages(a, None, a, a, B.FG_Q4G64, 8)) == B.FG_ERR_NULL
+    assert att(sq=B.fg_ragged(None, None, a, 2, 4)) == B.FG_ERR_NULL                  # no page table
+    assert att(sq=B.fg_ragged(a, None, None, 2, 4)) == B.FG_ERR_NULL                  # no length per row
+    assert att(sq=B.fg_ragged(a, None, a, 0, 4)) == B.FG_ERR_SHAPE
+    assert att(bias=-1) == B.FG_ERR_SHAPE
+    assert att(stride=700) == B.FG_ERR_SHAPE
+    assert att(b=0) == B.FG_OK
+    assert L.fg_kv_append_paged(C.byref(cfg), a, a, 2304, 4, -1, C.byref(pages), C.byref(seqs), None) == B.FG_ERR_SHAPE
+    assert L.fg_kv_append_paged(C.byref(cfg), None, a, 2304, 4, 1, C.byref(pages), C.byref(seqs), None) == B.FG_ERR_NULL
+    lay = lambda sq=seqs, nws=1 << 40: L.fg_decode_layer_paged(C.byref(cfg), C.byref(w), a, 4, C.byref(pages),
+                                                               C.byref(sq), a, ws, nws, None)
+    assert lay(nws=8) == B.FG_ERR_WORKSPACE
+    assert lay(sq=B.fg_ragged(a, None, None, 2, 4)) == B.FG_ERR_NULL                  # decode needs positions
+    # a prompt longer than the page table can address
+    assert L.fg_prefill_layer_paged(C.byref(cfg), C.byref(w), a, 4, 129, C.byref(pages), C.byref(seqs), a, ws, 1 << 40,
+                                    None) == B.FG_ERR_SHAPE
+    assert L.fg_embed_ragged(C.byref(cfg), a, a, a, None, 4, a, None) == B.FG_ERR_NULL
+    # the schedule's page arithmetic is host-only: 4 batches of one sequence in flight at 70..73 rows
+    assert L.fg_diagonal_pages_needed(4, 70, 4, 1) == 8
+    # 4 batches of two, all in flight at the end (rows 64..67 -> the last three batches hold two pages each)
+    assert L.fg_diagonal_pages_needed(8, 60, 8, 2) == 14
+    assert L.fg_diagonal_pages_needed(4, 70, 4, 3) == -1                              # 4 % 3 != 0
+    assert L.fg_diagonal_pages_needed(4, 0, 4, 1) == -1
+    larr = (B.fg_layer_weights * 1)(w)
+    parr = (B.fg_kv_pages * 1)(pages)
+    gen = lambda n_seqs, s, n, gbs, nws=1 << 40: L.fg_generate_diagonal(C.byref(cfg), 1, larr, a, a, a, a, a, n_seqs, s,
+                                                                        n, gbs, parr, a, ws, nws, None, None, None)
+    assert gen(4, 70, 4, 3) == B.FG_ERR_SHAPE
+    assert gen(4, 126, 4, 1) == B.FG_ERR_WORKSPACE     # rows 126..129 in flight: 9 pages, the pool has 8
+    assert gen(4, 70, 4, 1, nws=8) == B.FG_ERR_WORKSPACE
+    assert gen(4, 2040, 10, 1) == B.FG_ERR_SHAPE       # positions beyond max_pos
+    assert L.fg_diagonal_workspace_bytes(C.byref(cfg), C.byref(w), 4, 70, 4, 1) > 0
+    assert L.fg_diagonal_workspace_bytes(C.byref(cfg), C.byref(w), 4, 70, 4, 3) == 0
