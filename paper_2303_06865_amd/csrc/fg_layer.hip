@@ -837,11 +837,16 @@ extern "C" int fg_generate_diagonal(const fg_model_cfg* cfg, int32_t l, const fg
   int32_t* d_out = d_in + bmax;
   std::vector<int32_t> h(D.n_ints, 0);
 
-  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipEvent_t e0 = nullptr, e1 = nullptr, copied = nullptr;
   auto cleanup = [&]() {
     if (e0) (void)hipEventDestroy(e0);
     if (e1) (void)hipEventDestroy(e1);
+    if (copied) {
+      (void)hipEventSynchronize(copied);   // the host buffer must outlive the last copy that reads it
+      (void)hipEventDestroy(copied);
+    }
   };
+  FG_HIP(hipEventCreateWithFlags(&copied, hipEventDisableTiming));
 #define FG_TRY(expr)       \
   do {                     \
     int _rc = (expr);      \
@@ -850,16 +855,10 @@ extern "C" int fg_generate_diagonal(const fg_model_cfg* cfg, int32_t l, const fg
       return _rc;          \
     }                      \
   } while (0)
-  if (stats) {
-    FG_HIP(hipEventCreate(&e0));
-    if (hipEventCreate(&e1) != hipSuccess) {
-      cleanup();
-      return FG_ERR_DEVICE;
-    }
-    if (hipEventRecord(e0, st) != hipSuccess) {
-      cleanup();
-      return FG_ERR_DEVICE;
-    }
+  if (stats && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess ||
+                hipEventRecord(e0, st) != hipSuccess)) {
+    cleanup();
+    return FG_ERR_DEVICE;
   }
   for (int it = 0; it < plan.iterations(); ++it) {
     if (!plan.begin_iteration(it)) {
@@ -869,6 +868,10 @@ extern "C" int fg_generate_diagonal(const fg_model_cfg* cfg, int32_t l, const fg
     int g_lo, g_hi;
     plan.active(it, g_lo, g_hi);
     const bool admit = it < plan.ng;
+    if (it > 0 && hipEventSynchronize(copied) != hipSuccess) {   // the previous copy has read h
+      cleanup();
+      return FG_ERR_DEVICE;
+    }
     int b = 0;   // decode rows of this iteration: every sequence of the batches at steps 1 .. n-1
     for (int g = g_lo; g <= g_hi; ++g) {
       const int step = it - g;
@@ -883,9 +886,11 @@ extern "C" int fg_generate_diagonal(const fg_model_cfg* cfg, int32_t l, const fg
     memcpy(h.data(), plan.table.data(), tab_n * 4);
     if (admit)
       for (int i = 0; i < gbs; ++i) h[tab_n + i] = it * gbs + i;
-    // the copy is ordered behind the previous iteration's kernels on the stream; the host buffer is
-    // pageable, so the call has taken its contents by the time it returns
-    if (hipMemcpyAsync(D.ints, h.data(), D.n_ints * 4, hipMemcpyHostToDevice, st) != hipSuccess) {
+    // The copy is ordered behind the previous iteration's kernels on the stream.  The host buffer is
+    // rewritten in the next iteration, so that iteration first waits until this copy has been done
+    // (the wait above); the host therefore runs at most one iteration ahead of the GPU.
+    if (hipMemcpyAsync(D.ints, h.data(), D.n_ints * 4, hipMemcpyHostToDevice, st) != hipSuccess ||
+        hipEventRecord(copied, st) != hipSuccess) {
       cleanup();
       return FG_ERR_DEVICE;
     }
@@ -928,7 +933,7 @@ extern "C" int fg_generate_diagonal(const fg_model_cfg* cfg, int32_t l, const fg
     stats->tokens = (int64_t)n_seqs * n;
     stats->weight_bytes_per_step = 0;
     stats->kv_bytes_last_step = 0;
-    cleanup();
   }
+  cleanup();
   return FG_OK;
 }
