@@ -387,7 +387,8 @@ def test_decode_attention_topk_full_k_equals_dense():
 
 # ------------------------------------------------------------------ prefill attention
 @pytest.mark.parametrize("nh,dh", [(2, 128), (3, 64)])
-@pytest.mark.parametrize("b,s", [(1, 1), (2, 7), (1, 64), (2, 65), (1, 100), (1, 200), (3, 32)])
+@pytest.mark.parametrize("b,s", [(1, 1), (2, 7), (1, 64), (2, 65), (1, 100), (1, 200), (3, 32), (1, 127), (2, 128),
+                                 (1, 129), (1, 300), (2, 512)])
 def test_prefill_attention(b, s, nh, dh):
     h1 = nh * dh
     cfg = B.Cfg(h1, nh, 4 * h1, 1000, 4096)
