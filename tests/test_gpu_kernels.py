@@ -68,6 +68,44 @@ def test_quantize_h16_variant_bit_exact(rows, cols, std):
     assert np.array_equal(host(out).view(np.uint32), ref.view(np.uint32))
 
 
+@pytest.mark.parametrize("meta_f16", [False, True])
+def test_quantize_arbitrary_finite_bit_patterns_bit_exact(meta_f16):
+    """Every finite FP16 bit pattern can occur: subnormals, both zeros, the largest magnitudes, groups
+    whose maximum is 0 (where min + 15*scale does not return the maximum exactly).  Codes, pairs and
+    both dequantized forms (binary32 for the cache, FP16 for the weights) must equal the oracle's."""
+    rng = np.random.default_rng(17)
+    bits = rng.integers(0, 1 << 16, size=(64, 512), dtype=np.uint16)
+    bits[(bits & 0x7C00) == 0x7C00] &= 0x83FF                    # no infinities or NaNs
+    x = bits.view(np.float16).copy()
+    x[0] = np.float16(-1.0)
+    x[0, ::64] = 0.0                                             # maximum 0, minimum -1 in every group
+    x[1, :64] = np.float16(5.96e-8)
+    x[1, 0] = 0.0                                                # range of one FP16 subnormal unit
+    if meta_f16:                                                 # keep the range within what an FP16 scale can express
+        x = (x.astype(np.float32) * np.float32(2.0 ** -4)).astype(np.float16)
+    quant = O.quantize_groupwise_h16 if meta_f16 else O.quantize_groupwise
+    codes_ref, meta_ref = quant(x)
+    codes, meta = B.fg_quantize_groupwise(dev(x), meta_f16=meta_f16)
+    torch.cuda.synchronize()
+    mb = np.uint16 if meta_f16 else np.uint32
+    assert np.array_equal(host(codes), codes_ref)
+    assert np.array_equal(host(meta).view(mb), meta_ref.view(mb))
+    out = B.fg_dequantize_groupwise(codes, meta)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(out).view(np.uint32), O.dequantize_groupwise(codes_ref, meta_ref).view(np.uint32))
+    # the FP16 weight form, read out of the GEMM with one-hot activations (products with 1 and sums with
+    # zeros are exact): rows of x as a [64, 512] weight matrix in the tiled layout
+    wm = B.Mat(64, 512, B.FG_Q4G64_H16 if meta_f16 else B.FG_Q4G64, codes, meta).tiled()
+    w_ref = O.dequantize_groupwise_f16(codes_ref, meta_ref)
+    for k0 in (0, 64, 448):
+        e = np.zeros((64, 512), np.float16)
+        e[np.arange(64), k0 + np.arange(64)] = 1.0               # row i picks column k0 + i
+        got = host(B.fg_linear(wm, None, dev(e)))                # got[i, n] = w[n, k0 + i]
+        torch.cuda.synchronize()
+        # compared as numbers: a weight of -0 comes out of the sum with zeros as +0
+        assert np.array_equal(got.astype(np.float32), w_ref[:, k0:k0 + 64].T.astype(np.float32))
+
+
 def test_quantize_empty_input_is_a_noop():
     x = torch.empty((0, 128), dtype=torch.float16, device="cuda")
     codes, meta = B.fg_quantize_groupwise(x)
