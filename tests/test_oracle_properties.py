@@ -9,6 +9,10 @@ from hypothesis.extra import numpy as hnp
 
 from oracle import fg_oracle as O
 
+# the same examples on every run and machine: nothing random at test time, no example database
+settings.register_profile("fixed", derandomize=True, database=None, deadline=None)
+settings.load_profile("fixed")
+
 F16 = st.floats(width=16, allow_nan=False, allow_infinity=False)
 GROUPS = hnp.arrays(np.float16, (3, 128), elements=F16)
 # a few values repeated many times, and mixtures of huge and tiny magnitudes
