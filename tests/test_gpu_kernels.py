@@ -122,7 +122,8 @@ def test_dequantize_bit_exact():
 
 
 # ------------------------------------------------------------------ LayerNorm
-@pytest.mark.parametrize("rows,cols", [(1, 768), (5, 12288), (33, 4096), (2, 7168)])
+@pytest.mark.parametrize("rows,cols", [(1, 768), (5, 12288), (33, 4096), (2, 7168), (3, 64), (4, 4104), (2, 16384), (2, 16392),
+                                       (1, 49152)])
 def test_layernorm(rows, cols):
     x = (_rand16((rows, cols), 3.0, rows + cols).astype(np.float32) + 0.7).astype(np.float16)
     g = (1 + _rand16(cols, 0.1, 1).astype(np.float32)).astype(np.float16)
