@@ -767,7 +767,8 @@ DiagWs carve_diag_ws(const fg_model_cfg& c, const fg_layer_weights& w0, int n_se
   return D;
 }
 bool diag_args_ok(int32_t n_seqs, int32_t s, int32_t n, int32_t gbs) {
-  return n_seqs > 0 && s > 0 && n > 0 && gbs > 0 && n_seqs % gbs == 0 && (int64_t)n_seqs * n <= 0x7fffffff &&
+  return n_seqs > 0 && s > 0 && n > 0 && gbs > 0 && n_seqs % gbs == 0 && (int64_t)s + n <= 0x3fffffff &&
+         (int64_t)n_seqs * n <= 0x7fffffff &&
          (int64_t)gbs * s <= 0x7fffffff && diag_bmax(n_seqs, n, gbs) <= 65535;
 }
 }  // namespace
