@@ -115,3 +115,60 @@ def test_decode_attention_full_size_sampled(b, rows):
     got = np.stack([host(out[si, hi * dh:(hi + 1) * dh]) for (si, hi) in pairs])
     assert_close(got, O.round_f16(np.stack(refs)), "full-size decode attention rows=%d" % rows)
     assert bool(torch.isfinite(out.float()).all())
+
+
+def test_prefill_attention_full_size_sampled():
+    """One GPU batch of the OPT-175B workload (36 sequences x 96 heads x 512 positions): the launch
+    bench.py times (persistent workgroups, 128-query items).  Sampled (sequence, head) pairs are
+    computed whole by the oracle from the same FP16 q, k, v."""
+    b, s, nh, dh = 36, 512, 96, 128
+    h1 = nh * dh
+    cfg = B.Cfg(h1, nh, 4 * h1, 50272, 4096)
+    qkv = _gen((b * s, 3 * h1), 1.0, 11)
+    out = B.fg_prefill_attention(cfg, qkv, b, s)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    pairs = [(0, 0), (b - 1, nh - 1), (17, 40)] + [(int(rng.integers(0, b)), int(rng.integers(0, nh))) for _ in range(5)]
+    for (si, hi) in pairs:
+        blk = host(qkv[si * s:(si + 1) * s]).astype(np.float64)
+        q, k, v = (blk[:, j * h1 + hi * dh: j * h1 + (hi + 1) * dh] for j in range(3))
+        ref = O.round_f16(O.attn_prefill(q, k, v))
+        got = host(out[si * s:(si + 1) * s, hi * dh:(hi + 1) * dh])
+        assert_close(got, ref, "full-size prefill attention seq %d head %d" % (si, hi))
+    assert bool(torch.isfinite(out.float()).all())
+
+
+def test_layernorm_full_size_sampled():
+    rows, cols = 18432, 12288
+    x = _gen((rows, cols), 3.0, 21) + 0.5
+    g = _gen((cols,), 0.1, 22) + 1.0
+    be = _gen((cols,), 0.1, 23)
+    out = B.fg_layernorm(x, g, be, 1e-5)
+    torch.cuda.synchronize()
+    idx = _sample(rows, [255, 256, rows // 2], 12, 3)
+    ti = torch.from_numpy(idx).cuda()
+    ref = O.round_f16(O.layernorm(host(x[ti]), host(g), host(be), 1e-5))
+    assert_close(host(out[ti]), ref, "full-size layernorm", rel=5e-4, mabs=4e-3)
+
+
+@pytest.mark.parametrize("meta_f16", [False, True])
+def test_kv_append_full_size_sampled_bit_exact(meta_f16):
+    """The prefill append of one GPU batch of the OPT-175B workload (36 x 512 rows x 12288): sampled
+    (sequence, head) streams must hold exactly the oracle's codes and pairs."""
+    b, s, nh, dh = 36, 512, 96, 128
+    h1 = nh * dh
+    cfg = B.Cfg(h1, nh, 4 * h1, 50272, 4096)
+    qkv = _gen((b * s, 3 * h1), 1.0, 31)
+    kv = B.KVCache(cfg, b, s + 4, True, zero=False, meta_f16=meta_f16)
+    B.fg_kv_append(cfg, qkv[:, h1:], qkv[:, 2 * h1:], 3 * h1, b, s, kv, 0, 0)
+    torch.cuda.synchronize()
+    quant = O.quantize_groupwise_h16 if meta_f16 else O.quantize_groupwise
+    bits = np.uint16 if meta_f16 else np.uint32
+    rng = np.random.default_rng(6)
+    pairs = [(0, 0), (b - 1, nh - 1)] + [(int(rng.integers(0, b)), int(rng.integers(0, nh))) for _ in range(6)]
+    for (si, hi) in pairs:
+        for j, (codes_dev, meta_dev) in enumerate(((kv.k_codes, kv.k_meta), (kv.v_codes, kv.v_meta))):
+            rows16 = host(qkv[si * s:(si + 1) * s, (j + 1) * h1 + hi * dh:(j + 1) * h1 + (hi + 1) * dh]).copy()
+            codes, meta = quant(rows16)
+            assert np.array_equal(host(codes_dev[si, hi, :s]), codes)
+            assert np.array_equal(host(meta_dev[si, hi, :s]).view(bits), meta.reshape(s, dh // 64, 2).view(bits))
