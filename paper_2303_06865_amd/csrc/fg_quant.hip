@@ -41,10 +41,28 @@ __device__ __forceinline__ void quantize_group_8lanes(const h8_t v, int sub, uin
   }
   uint32_t p = 0;
   if (scale > 0.0f) {
+    // The code is rint(Q), Q = the correctly rounded quotient (x - min) / scale.  An IEEE division per
+    // element makes this kernel VALU-bound, so the quotient is first taken as (x - min) * rcp(scale):
+    // rcp is good to 1 ulp and the product adds half an ulp, so it is within 15 * 1.5 * 2^-23 < 3e-6
+    // of the exact quotient, as is Q (half an ulp of 15 = 5e-7).  Both therefore round to the same
+    // integer unless the fast quotient lies within 1e-4 of a half-integer; only then (2e-4 of all
+    // elements, and every exact tie) the lane redoes its eight elements with the exact division.
+    const float inv = __builtin_amdgcn_rcpf(scale);
+    float t[8];
+    bool near_half = false;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      float t = (x[i] - mn) / scale;
-      float r = rintf(t);  // ties to even
+      t[i] = (x[i] - mn) * inv;
+      const float frac = t[i] - floorf(t[i]);
+      near_half |= fabsf(frac - 0.5f) < 1e-4f;
+    }
+    if (near_half) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t[i] = (x[i] - mn) / scale;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float r = rintf(t[i]);  // ties to even
       r = fminf(fmaxf(r, 0.0f), 15.0f);
       p |= ((uint32_t)(int)r) << (4 * i);
     }
@@ -137,29 +155,38 @@ __device__ __forceinline__ int64_t kv_dest_row(const KvAppendArgs& a, int64_t bi
   return ((int64_t)page * a.nh + head) * FG_PAGE_ROWS + (p & (FG_PAGE_ROWS - 1));
 }
 
+// Grid (wave units / 4, 8-group chunks of a token row, {K, V}).  A wave unit is 8 consecutive
+// positions of one sequence; the wave takes 8 consecutive groups of each of those token rows (512
+// contiguous bytes per row), two rows per pass with both loads issued before either is used, and what
+// it writes for a head (64 bytes of codes per position at head size 128) is contiguous over the unit.
+// Which sequence and positions a wave covers is one scalar division per wave: the per-item index
+// arithmetic has no division (64-bit divisions per item made the first version VALU-bound).
+constexpr int kKvPosPerWave = 8;
 template <bool H16>
 __global__ __launch_bounds__(256) void kv_append_q4_kernel(KvAppendArgs a) {
-  const int which = blockIdx.y;
+  const int which = blockIdx.z;
   const half_t* __restrict__ x = a.src[which];
   uint32_t* __restrict__ codes = reinterpret_cast<uint32_t*>(a.codes[which]);
   void* __restrict__ meta = a.meta[which];
-  const int gph = a.dh / kGroup;              // groups per head
+  const int gph = a.dh / kGroup;              // groups per head: 1 or 2
   const int gpr = a.nh * gph;                 // groups per token row
-  const int64_t n_groups = (int64_t)a.b * a.s * gpr;
-  const int sub = threadIdx.x & 7;
-  int64_t g = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 3;
-  const int64_t stride = ((int64_t)gridDim.x * blockDim.x) >> 3;
-  for (; g < n_groups; g += stride) {
-    const int64_t row = g / gpr;
-    const int gi = (int)(g - row * gpr);
-    const int head = gi / gph, gh = gi - head * gph;
-    const int64_t bi = row / a.s;
-    const h8_t v = *reinterpret_cast<const h8_t*>(x + row * a.ld + (int64_t)gi * kGroup + sub * 8);
+  const int sub = threadIdx.x & 7, lg = (threadIdx.x & 63) >> 3;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t units_per_seq = (uint32_t)(a.s + kKvPosPerWave - 1) / kKvPosPerWave;
+  const uint32_t unit = blockIdx.x * 4u + (uint32_t)wave;
+  const uint32_t bi = unit / units_per_seq;
+  if (bi >= (uint32_t)a.b) return;
+  const int pos_base = (int)(unit - bi * units_per_seq) * kKvPosPerWave;
+  const int gi = blockIdx.y * 8 + lg;
+  if (gi >= gpr) return;                      // whole groups of 8 lanes drop out together (partial last chunk)
+  const int head = gph == 2 ? gi >> 1 : gi, gh = gph == 2 ? gi & 1 : 0;
+  const half_t* src = x + (int64_t)bi * a.s * a.ld + (int64_t)gi * kGroup + sub * 8;
+  auto finish = [&](int pos, const h8_t v) {
     uint32_t p;
     float mn, sc;
     quantize_group_8lanes<H16>(v, sub, p, mn, sc);   // all eight lanes of a group take part
-    const int64_t crow = kv_dest_row(a, bi, head, (int)(row - bi * a.s));
-    if (crow < 0) continue;
+    const int64_t crow = kv_dest_row(a, bi, head, pos);
+    if (crow < 0) return;
     codes[(crow * gph + gh) * 8 + sub] = p;
     if (sub == 0) {
       if (H16)
@@ -167,6 +194,16 @@ __global__ __launch_bounds__(256) void kv_append_q4_kernel(KvAppendArgs a) {
       else
         reinterpret_cast<float2*>(meta)[crow * gph + gh] = make_float2(mn, sc);
     }
+  };
+#pragma unroll
+  for (int k = 0; k < kKvPosPerWave; k += 2) {
+    const int p0 = pos_base + k, p1 = p0 + 1;   // wave-uniform
+    if (p0 >= a.s) break;
+    const bool two = p1 < a.s;
+    const h8_t v0 = *reinterpret_cast<const h8_t*>(src + (int64_t)p0 * a.ld);
+    const h8_t v1 = *reinterpret_cast<const h8_t*>(src + (int64_t)(two ? p1 : p0) * a.ld);
+    finish(p0, v0);
+    if (two) finish(p1, v1);
   }
 }
 
@@ -223,8 +260,8 @@ int kv_append_launch(const fg_model_cfg& cfg, const half_t* k, const half_t* v, 
   a.table_stride = a.n_seqs = a.n_pages = 0;
   ProfScope prof(FG_K_KV_APPEND, stream);
   if (kv.dtype == FG_Q4G64 || kv.dtype == FG_Q4G64_H16) {
-    const int64_t groups = (int64_t)b * s * cfg.h1 / kGroup;
-    dim3 grid(grid_for(groups, 32), 2);
+    const int gpr = cfg.h1 / kGroup;
+    dim3 grid((unsigned)ceil_div(b * ceil_div(s, kKvPosPerWave), 4), (unsigned)ceil_div(gpr, 8), 2);
     if (kv.dtype == FG_Q4G64_H16)
       hipLaunchKernelGGL(kv_append_q4_kernel<true>, grid, dim3(256), 0, stream, a);
     else
@@ -264,8 +301,8 @@ int kv_append_paged_launch(const fg_model_cfg& cfg, const half_t* k, const half_
   a.n_seqs = seqs.n_seqs;
   a.n_pages = pages.n_pages;
   ProfScope prof(FG_K_KV_APPEND, stream);
-  const int64_t groups = (int64_t)b * s * cfg.h1 / kGroup;
-  dim3 grid(grid_for(groups, 32), 2);
+  const int gpr = cfg.h1 / kGroup;
+  dim3 grid((unsigned)ceil_div(b * ceil_div(s, kKvPosPerWave), 4), (unsigned)ceil_div(gpr, 8), 2);
   if (pages.dtype == FG_Q4G64_H16)
     hipLaunchKernelGGL(kv_append_q4_kernel<true>, grid, dim3(256), 0, stream, a);
   else
