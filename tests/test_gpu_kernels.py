@@ -491,3 +491,31 @@ def test_argmax_lowest_index_on_exact_ties():
     ids, logits = B.fg_lm_head_greedy(cfg, dev(x), dev(np.ones(128, np.float16)), dev(np.zeros(128, np.float16)),
                                       dev(m["embed"]))
     assert np.all(host(logits) == 0) and np.all(host(ids) == 0)
+
+
+# ------------------------------------------------------------------ determinism
+def test_results_are_bit_identical_from_run_to_run():
+    """Nothing in the path depends on the order in which workgroups finish: the stream-K partial sums
+    are added up by a second pass in a fixed order, the attention kernels merge per-wave results in a
+    fixed order.  Same inputs, same bits, every time."""
+    w = dev(_rand16((2304, 768), 0.02, 1))
+    x = dev(_rand16((144, 768), 1.0, 2))
+    wm = B.Mat.from_f16(w, True, tiled=True)
+    ref = B.fg_linear(wm, None, x).clone()
+    big = B.Mat.from_f16(dev(_rand16((4352, 128), 0.02, 3)), True, tiled=True)
+    xb = dev(_rand16((4100, 128), 1.0, 4))
+    refb = B.fg_linear(big, None, xb).clone()
+    nh, dh, rows = 12, 64, 300
+    cfg = B.Cfg(nh * dh, nh, 4 * nh * dh, 1000, 512)
+    kv = B.KVCache(cfg, 5, rows, True)
+    kvx = dev(_rand16((5 * rows, 3 * nh * dh), 1.0, 5))
+    B.fg_kv_append(cfg, kvx[:, nh * dh:], kvx[:, 2 * nh * dh:], 3 * nh * dh, 5, rows, kv, 0, 0)
+    q = dev(_rand16((5, 3 * nh * dh), 1.0, 6))
+    refa = B.fg_decode_attention(cfg, q, 3 * nh * dh, 5, rows, kv, 0).clone()
+    refp = B.fg_prefill_attention(cfg, kvx[:rows * 5], 5, rows).clone()
+    torch.cuda.synchronize()
+    for _ in range(5):
+        assert torch.equal(B.fg_linear(wm, None, x), ref)
+        assert torch.equal(B.fg_linear(big, None, xb), refb)
+        assert torch.equal(B.fg_decode_attention(cfg, q, 3 * nh * dh, 5, rows, kv, 0), refa)
+        assert torch.equal(B.fg_prefill_attention(cfg, kvx[:rows * 5], 5, rows), refp)
