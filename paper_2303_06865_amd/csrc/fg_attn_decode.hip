@@ -74,7 +74,7 @@ __device__ __forceinline__ void merge_and_store(const float* sm_m, const float* 
 // row of the page table, and every sequence has its own length.  A wave keeps 64 consecutive table
 // entries in one register (one per lane) and picks the page of a chunk with a lane read.
 template <int DH, int WPH, bool H16, bool PAGED = false>
-__global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, 3) void attn_decode_q4_kernel(AttnArgs a) {
   using meta_t = typename MetaRaw<H16>::type;
   constexpr int GPR = DH / 64;       // quantization groups per row of this head
   constexpr int NS = 2 / GPR;        // scores per lane per chunk (lane owns groups 2L, 2L+1)
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void attn_decode_q4_kernel(AttnArgs a) {
     // ---- online softmax (every processed chunk has at least one valid row)
     float cmax = sc[0];
     if (NS == 2) cmax = fmaxf(cmax, sc[NS - 1]);
-    cmax = wave_max(cmax);
+    cmax = uniform(wave_max(cmax));
     const float m_new = fmaxf(m_run, cmax);
     if (m_new > m_run) {   // wave-uniform
       const float alpha = fast_exp2((m_run - m_new) * kLog2e);
