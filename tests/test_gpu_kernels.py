@@ -337,6 +337,17 @@ def test_decode_attention_many_heads(b, nh, dh, rows, quant):
     assert_close(got, ref, "decode attention b=%d nh=%d dh=%d rows=%d q=%s" % (b, nh, dh, rows, quant))
 
 
+@pytest.mark.parametrize("b,nh,dh,rows,meta_f16", [
+    (51, 72, 64, 70, False),     # 3672 heads
+    (57, 75, 64, 130, True),     # 4275 heads, the last workgroup has three of its four waves busy
+    (33, 128, 128, 90, False),   # 4224 heads at head size 128
+])
+def test_decode_attention_more_heads_than_wave_slots(b, nh, dh, rows, meta_f16):
+    """More heads than the chip holds waves at once (3072): the launch runs in several rounds."""
+    got, ref = _decode_attn_case(nh, dh, True, rows, b=b, batch=b, boff=0, seed=b + nh, meta_f16=meta_f16)
+    assert_close(got, ref, "decode attention, b=%d nh=%d dh=%d" % (b, nh, dh))
+
+
 @pytest.mark.parametrize("quant", [True, False])
 def test_decode_attention_peaked_softmax(quant):
     """Large key norm: a near one-hot softmax, where a wrong max/rescale shows immediately."""

@@ -234,3 +234,11 @@ def test_paged_calls_reject_bad_arguments():
         B.fg_decode_attention_paged(cfg, q, 3 * sh.h1, 1, pages, B.Ragged(table, None, None), 0)
     with pytest.raises(RuntimeError):      # row stride smaller than a row
         B.fg_kv_append_paged(cfg, q, q, 8, 1, 1, pages, B.Ragged(table, None, dev(np.zeros(1, np.int32))))
+
+
+def test_decode_attention_paged_more_heads_than_wave_slots():
+    """3720 heads of different lengths: more than the chip holds waves at once."""
+    rng = np.random.default_rng(2)
+    lens = [int(v) for v in rng.integers(1, 140, size=31)]
+    got, ref, _ = _attention_case(120, 64, lens, seed=41)
+    assert_close(got, ref, "paged decode attention, 3720 heads")
