@@ -23,7 +23,7 @@
 //     them exactly in registers (no LDS round trip for FP16 weights) and feeds them to the MFMA as
 //     the B operand.
 //   * Work = (output tile, K step) pairs.  Whole rounds of tiles go one tile per workgroup, walked in
-//     groups of 8 row blocks so that concurrently running workgroups share activations and weights
+//     groups of 4 row blocks so that concurrently running workgroups share activations and weights
 //     in L2; the remaining tiles are cut stream-K fashion into equal contiguous ranges with a
 //     deterministic second-pass reduction.  The grid is always 256 workgroups, one per CU.
 #include "fg_common.h"
@@ -37,7 +37,7 @@ constexpr int kKS = 64;       // K elements per step = one quantization group
 constexpr int kBStageQ4 = 8 * (1024 + 256);   // bytes of weight codes + meta per stage (8 column tiles)
 constexpr int kBStageF16 = kBN * kKS * 2;     // FP16 weights: 256 rows of 128 bytes, laid out like the activations
 constexpr int kMaxMT = 5;     // decode shape: up to 5 row tiles of 32 (160 rows)
-constexpr int kGroupM = 8;    // row blocks per group in the tile walk
+constexpr int kGroupM = 4;    // row blocks per group in the tile walk
 constexpr int kLdsBytes = 160 * 1024;
 constexpr int kFinishItems = 8;   // float4 items per thread of the reduction pass
 
@@ -65,7 +65,9 @@ __device__ __forceinline__ int64_t work_begin(int64_t total, int grid, int p) { 
 __device__ __forceinline__ int swz(int row, int kc) { return kc ^ ((row >> 1) & 7); }
 
 // linear tile number -> (row block, column block): groups of kGroupM row blocks, inside a group the
-// row block runs fastest, so 32 consecutive tiles (one XCD's share of a round) form an 8 x 4 patch
+// row block runs fastest, so 32 consecutive tiles (one XCD's share of a round) form a patch of 4 row blocks x 8 column
+// blocks: per K step the 32 workgroups then fetch 4 activation tiles (32 KiB each) and 8 weight tiles
+// (10 KiB each) into that XCD's L2, the least of all patch shapes
 __device__ __forceinline__ void tile_coords(int64_t t, int m_blocks, int n_tiles, int& mblk, int& n_tile) {
   const int64_t per_group = (int64_t)kGroupM * n_tiles;
   const int g = (int)(t / per_group);
