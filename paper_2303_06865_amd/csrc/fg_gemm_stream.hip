@@ -39,7 +39,8 @@ constexpr int kBStageF16 = kBN * kKS * 2;     // FP16 weights: 256 rows of 128 b
 constexpr int kMaxMT = 5;     // decode shape: up to 5 row tiles of 32 (160 rows)
 constexpr int kGroupM = 4;    // row blocks per group in the tile walk
 constexpr int kLdsBytes = 160 * 1024;
-constexpr int kFinishItems = 8;   // float4 items per thread of the reduction pass
+constexpr int kFinishItems = 4;   // float4 items per thread of the reduction pass
+constexpr int kFinishParts = 4;   // contributors whose loads are in flight together
 
 struct StreamArgs {
   const uint8_t* w;     // tiled codes
@@ -486,7 +487,8 @@ __global__ __launch_bounds__(NW * 64) void gemm_stream_kernel(StreamArgs a) {
         for (int j = 0; j < NT; ++j)
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            *dst = make_float4(acc[m][j][4 * q], acc[m][j][4 * q + 1], acc[m][j][4 * q + 2], acc[m][j][4 * q + 3]);
+            if (m0 + (wm * MT + m) * 32 + q * 8 < a.M)   // rows beyond M: padding, never read back
+              *dst = make_float4(acc[m][j][4 * q], acc[m][j][4 * q + 1], acc[m][j][4 * q + 2], acc[m][j][4 * q + 3]);
             dst += NW * 64;
           }
     }
@@ -523,28 +525,44 @@ __global__ __launch_bounds__(512) void gemm_stream_finish_kernel(StreamArgs a, i
   const int tid = threadIdx.x, wave = tid >> 6, l32 = tid & 31, kb = (tid >> 5) & 1;
   const int wm = wave / wn_n, wn = wave - wm * wn_n;
   // this thread's float4 items e = blockIdx.y + i * gridDim.y, e = (m*nt + j)*4 + q; the launch keeps
-  // their number within kFinishItems.  Contributors outermost, so that the loads of one contributor
-  // for all items are in flight together; the sum still runs in ascending K order per item.
+  // their number within kFinishItems.  The loads of up to kFinishParts contributors for all items are
+  // in flight together (a tile of the decode shapes has 2 to 7 contributors: one or two dependent
+  // round trips instead of one per contributor); the sum still runs in ascending K order per item.
   const int n_items = mt * nt * 4;
   float4 v[kFinishItems];
 #pragma unroll
   for (int i = 0; i < kFinishItems; ++i) v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int p = p_lo; p <= p_hi; ++p) {
-    const int64_t pb = work_begin(a.rem_work, a.grid, p);
-    if (work_begin(a.rem_work, a.grid, p + 1) == pb) continue;
-    const int s = pb >= w0 ? 0 : 1;
-    const float4* src = reinterpret_cast<const float4*>(a.partial + ((int64_t)p * 2 + s) * slot) + tid;
-#pragma unroll
-    for (int i = 0; i < kFinishItems; ++i) {
-      const int e = blockIdx.y + i * gridDim.y;
-      if (e < n_items) {
-        const float4 x = src[(int64_t)e * nthr];
-        v[i].x += x.x;
-        v[i].y += x.y;
-        v[i].z += x.z;
-        v[i].w += x.w;
-      }
+  int p = p_lo;
+  while (p <= p_hi) {
+    const float4* src[kFinishParts];
+    int n = 0;
+    for (; p <= p_hi && n < kFinishParts; ++p) {
+      const int64_t pb = work_begin(a.rem_work, a.grid, p);
+      if (work_begin(a.rem_work, a.grid, p + 1) == pb) continue;
+      const int s = pb >= w0 ? 0 : 1;
+      src[n++] = reinterpret_cast<const float4*>(a.partial + ((int64_t)p * 2 + s) * slot) + tid;
     }
+    float4 x[kFinishParts][kFinishItems];
+#pragma unroll
+    for (int c = 0; c < kFinishParts; ++c)
+#pragma unroll
+      for (int i = 0; i < kFinishItems; ++i) {
+        const int e = blockIdx.y + i * gridDim.y;
+        // items whose eight rows (8q .. 8q+7 of row tile m) all lie beyond M were never written
+        const bool live = e < n_items && m0 + (wm * mt + (e >> 2) / nt) * 32 + (e & 3) * 8 < a.M;
+        x[c][i] = (c < n && live) ? src[c < n ? c : 0][(int64_t)e * nthr] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+    for (int c = 0; c < kFinishParts; ++c)
+      if (c < n) {
+#pragma unroll
+        for (int i = 0; i < kFinishItems; ++i) {
+          v[i].x += x[c][i].x;
+          v[i].y += x[c][i].y;
+          v[i].z += x[c][i].z;
+          v[i].w += x[c][i].w;
+        }
+      }
   }
 #pragma unroll
   for (int i = 0; i < kFinishItems; ++i) {
@@ -610,6 +628,9 @@ Shape pick_shape(int64_t m) {
   return {need < 1 ? 1 : need, 2, 1, 4};
 }
 
+// blocks along y of the reduction pass: every thread takes at most kFinishItems of the mt*nt*4 items
+static inline unsigned finish_y(const Shape& sh) { return (unsigned)ceil_div(sh.mt * sh.nt * 4, kFinishItems); }
+
 template <int MT, int NT, int WM, int NW, bool F16W, bool H16M = false>
 int launch_t(const StreamArgs& a, hipStream_t stream) {
   using C = StreamCfg<MT, NT, WM, NW, F16W>;
@@ -671,7 +692,7 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
                                                   : launch_t<8, 1, 1, 8, false>(a, stream);
     if (rc) return rc;
     if (rem_tiles > 0) {
-      hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, 8), dim3(sh.nw * 64), 0, stream, a, sh.mt,
+      hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, finish_y(sh)), dim3(sh.nw * 64), 0, stream, a, sh.mt,
                          sh.nt, sh.wm);
       FG_LAUNCH_CHECK();
     }
@@ -699,7 +720,7 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   }
   if (rem_tiles > 0) {
     ProfScope prof(FG_K_GEMM_SMALL_M_FINISH, stream);
-    hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, sh.mt * sh.nt >= 4 ? 8 : 4),
+    hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, finish_y(sh)),
                        dim3(sh.nw * 64), 0, stream, a, sh.mt, sh.nt, sh.wm);
     FG_LAUNCH_CHECK();
   }
