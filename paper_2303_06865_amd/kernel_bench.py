@@ -59,6 +59,7 @@ def main(argv=None):
     ap.add_argument("--nh", type=int, default=96)
     ap.add_argument("--dh", type=int, default=128)
     ap.add_argument("--rows", type=int, default=528, help="cached positions read by decode attention")
+    ap.add_argument("--cap", type=int, default=0, help="attn_decode*: cache capacity in positions (default rows + 64)")
     ap.add_argument("--seq", type=int, default=512)
     ap.add_argument("--topk", type=int, default=0, help="attn_decode_topk: rows kept (default: ceil(rows / 10))")
     ap.add_argument("--kv", choices=["q4", "q4h", "f16"], default="q4", help="cache storage: 4-bit, 4-bit with FP16 pairs, FP16")
@@ -83,7 +84,7 @@ def main(argv=None):
         cfg = B.Cfg(h1, a.nh, 4 * h1, 50272, 4096)
         q4 = a.kv != "f16"
         kvb = {"q4": 0.625, "q4h": 0.5625, "f16": 2.0}[a.kv]
-        kv = B.KVCache(cfg, a.batch, a.rows + 64, q4, zero=False, meta_f16=a.kv == "q4h")
+        kv = B.KVCache(cfg, a.batch, a.cap or a.rows + 64, q4, zero=False, meta_f16=a.kv == "q4h")
         if q4:
             kv.k_codes.random_(0, 256)
             kv.v_codes.random_(0, 256)
