@@ -204,12 +204,12 @@ TILED_CASES = [
     (36, 992, 832, True, False, True),       # ragged column block (992 = 31 tiles of 32)
     (48, 288, 192, False, True, False),
     (100, 544, 1024, True, False, False),
-    (144, 1024, 12288, True, False, True),
+    (144, 1024, 12288, True, False, True),   # 4 tiles over 256 workgroups: 64 contributors per tile in the reduction pass
     (150, 768, 768, False, False, False),
     (200, 512, 256, True, True, True),       # two row blocks
     (300, 800, 448, True, False, True),
     (161, 320, 64, True, False, True),       # smallest prefill-shape launch: one ragged 256-row block, one K step
-    (600, 768, 768, True, False, True),      # prefill shape (2 x 2 waves), stream-K pieces only
+    (600, 768, 768, True, False, True),      # prefill shape (256-row blocks, 8 waves), stream-K pieces only
     (1100, 544, 448, True, True, False),
     (4100, 4352, 128, True, False, True),    # 17 x 17 tiles: one whole round + 33 stream-K tiles, ragged last block
     (2304, 15360, 64, False, True, False),   # 540 tiles: two whole rounds + 28
