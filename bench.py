@@ -9,6 +9,13 @@ KV cache, block 4 x 36 sequences, prompt 512, 32 generated tokens (Section 6 wor
 Prints ONE JSON line with generated tokens/s (paper's definition: bls*n / (prefill + decode time)),
 the per-kernel-class rooflines measured live with HIP events on the launch stream, the decode-phase
 HBM fraction, and the CPU oracle timed on a bounded slice of the same workload.
+
+One pass of the headline workload takes about 25 s, so --steps and --warmup are UPPER BOUNDS under a
+wall-clock budget (--budget-s, counted from process start): after the first pass has been timed, the
+number of passes that still fit is planned (plan_passes), and the line reports the counts actually
+run.  The timed passes carry HIP events only on the few long prefill kernels (a pair of events costs
+microseconds per launch, which a decode step of a thousand short launches would feel); one extra,
+untimed pass with events on every launch gives the per-kernel-class table.
 """
 from __future__ import annotations
 
@@ -18,6 +25,7 @@ import os
 import sys
 import time
 
+T_PROCESS_START = time.perf_counter()
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
@@ -53,6 +61,27 @@ WORKLOADS = {
 }
 
 
+# kernel classes that are few, long launches in a generation pass: timing them inside the timed region
+# costs nothing measurable (about 2000 event pairs per pass against 25 s)
+CHEAP_TO_TIME = ("gemm_large_m", "attn_prefill")
+
+
+def plan_passes(steps, warmup, pass_s, avail_s):
+    """How many passes to run when ONE pass has already been run and took pass_s seconds and avail_s
+    seconds are left for further warm-up and timed passes.  steps / warmup are the requested counts,
+    taken as upper bounds.  The pass already run is the first warm-up pass if warmup >= 1, otherwise the
+    first timed pass.  Timed passes have priority over further warm-up passes; at least one pass is
+    timed whatever the budget says.  Returns (warmup passes in total, timed passes in total)."""
+    steps = max(1, int(steps))
+    warmup = max(0, int(warmup))
+    fit = int(avail_s // pass_s) if pass_s > 0 and avail_s > 0 else 0
+    if warmup == 0:
+        return 0, 1 + min(steps - 1, fit)
+    k = min(steps, max(1, fit))
+    w = 1 + min(warmup - 1, max(0, fit - k))
+    return w, k
+
+
 def bpe(q):
     """Stored bytes per element: FP16, 4-bit with binary32 pairs, or ("h16") 4-bit with FP16 pairs."""
     return 0.5625 if q == "h16" else (0.625 if q else 2.0)
@@ -84,40 +113,51 @@ def build_model(sh, wq, seed, torch, B, embeddings=True):
     return layers, emb, pos, ones, zeros
 
 
-def cpu_baseline(sh, wq, kvq, s, n, budget_s=25.0):
-    """The oracle as it stands, on the host cores, on a bounded slice of the workload: a decode step
-    of ONE layer for 4 sequences at the real widths, with each projection cut to a 512-row slab of
-    its weight matrix; scaled to the full matrices and to l layers.  Reported, not a target."""
+def cpu_baseline(sh, wq, kvq, s, n, bls, budget_s=25.0):
+    """The oracle as it stands (numpy, float64; its matrix products run on numpy's BLAS threads), on
+    the host cores, on a bounded slice of the workload at the real widths: ONE layer, the decode step
+    of 4 sequences at the mean cache length and the prefill of one sequence, each projection cut to a
+    slab of rows of its weight matrix and the attention to as many heads as fit the time budget; the
+    pieces are scaled to the full matrices / all heads, then to l layers, s + n - 1 positions and the
+    whole block, giving the same quantity as the headline: generated tokens per second of the block,
+    bls * n / (prefill + decode).  Reported, not a target."""
     import numpy as np
     from oracle import fg_oracle as O
-    from paper_2303_06865_amd import synth
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
         threads = os.cpu_count() or 1
-    b, slab = 4, 512
+    t_begin = time.perf_counter()
+    b, slab = 4, 1024
     rows = s + n // 2
     h1, h2, nh, dh = sh.h1, sh.h2, sh.nh, sh.dh
     rng = np.random.default_rng(0)
     f16 = lambda shape, std: (rng.standard_normal(shape, dtype=np.float32) * np.float32(std)).astype(np.float16)
     slabs = {"wqkv": (3 * h1, h1), "wo": (h1, h1), "w1": (h2, h1), "w2": (h1, h2)}
     mats = {k: O.Mat.from_f16(f16((min(slab, r), c), 0.02), bool(wq), wq == "h16") for k, (r, c) in slabs.items()}
+    ones, zeros = np.ones(h1, np.float16), np.zeros(h1, np.float16)
+
+    def linears(x, a):
+        """all four projections on x [m, h1] / a [m, h2], seconds scaled to the full matrices"""
+        t = 0.0
+        for k, (r, c) in slabs.items():
+            xin = a if k == "w2" else x
+            t0 = time.perf_counter()
+            O.round_f16(O.linear(xin, mats[k], None))
+            t += (time.perf_counter() - t0) * (r / min(slab, r))
+        return t
+
+    def layernorms(x):
+        t0 = time.perf_counter()
+        O.round_f16(O.layernorm(x.astype(np.float64), ones, zeros, 1e-5))
+        return 2 * (time.perf_counter() - t0)
+
+    # ---- decode step of one layer, b sequences
     kv = O.KVCache.empty(b, nh, rows + 1, dh, bool(kvq), kvq == "h16")
     kv.store(0, 0, f16((b, rows, h1), 1.0), f16((b, rows, h1), 1.0))
-    x = f16((b, h1), 1.0)
-    a = f16((b, h2), 1.0)
-    ones, zeros = np.ones(h1, np.float16), np.zeros(h1, np.float16)
-    t_total = 0.0
-    t0 = time.perf_counter()
-    y = O.round_f16(O.layernorm(x.astype(np.float64), ones, zeros, 1e-5))
-    t_ln = time.perf_counter() - t0
-    t_lin = 0.0
-    for k, (r, c) in slabs.items():
-        xin = a if k == "w2" else y
-        t0 = time.perf_counter()
-        O.round_f16(O.linear(xin, mats[k], None))
-        t_lin += (time.perf_counter() - t0) * (r / min(slab, r))
+    x, a = f16((b, h1), 1.0), f16((b, h2), 1.0)
+    t_dec = layernorms(x) + linears(x, a)
     t0 = time.perf_counter()
     kv.store(0, rows, f16((b, 1, h1), 1.0), f16((b, 1, h1), 1.0))
     q = x.astype(np.float64).reshape(b, nh, dh)
@@ -127,15 +167,35 @@ def cpu_baseline(sh, wq, kvq, s, n, budget_s=25.0):
             kh, vh = kv.load(bi, h, rows + 1)
             O.attn_decode(q[bi, h], kh, vh)
             heads += 1
-        if time.perf_counter() - t0 > budget_s / 2:
+        if time.perf_counter() - t0 > budget_s * 0.3:
             break
-    t_att = (time.perf_counter() - t0) * (b * nh / max(heads, 1))
-    t_layer = 2 * t_ln + t_lin + t_att
-    t_total = t_layer * sh.l
-    return {"value": b / t_total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": "extrapolated: oracle decode step of one layer, 4 sequences, %d cached rows, real widths "
-                      "(h1=%d, h2=%d, %d heads), each projection timed on a 512-row slab of its matrix and scaled "
-                      "to the full matrix, then x%d layers" % (rows + 1, h1, h2, nh, sh.l)}
+    t_dec += (time.perf_counter() - t0) * (b * nh / max(heads, 1))
+    t_dec_seq = t_dec / b                                  # seconds per sequence, layer and decode step
+    # ---- prefill of one layer, one sequence of s positions
+    xs, as_ = f16((s, h1), 1.0), f16((s, h2), 1.0)
+    t_pre = layernorms(xs) + linears(xs, as_)
+    qkv = f16((s, 3, nh, dh), 1.0).astype(np.float64)
+    t0 = time.perf_counter()
+    heads = 0
+    for h in range(nh):
+        O.attn_prefill(qkv[:, 0, h], qkv[:, 1, h], qkv[:, 2, h])
+        heads += 1
+        if time.perf_counter() - t0 > budget_s * 0.2:
+            break
+    t_pre += (time.perf_counter() - t0) * (nh / heads)
+    okv = O.KVCache.empty(1, nh, s, dh, bool(kvq), kvq == "h16")
+    t0 = time.perf_counter()
+    okv.store(0, 0, xs.reshape(1, s, h1), xs.reshape(1, s, h1))
+    t_pre += time.perf_counter() - t0
+    t_block = sh.l * bls * (t_pre + (n - 1) * t_dec_seq)   # the sequences of a block, one after the other
+    return {"value": bls * n / t_block, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "decode_tokens_per_s": 1.0 / (sh.l * t_dec_seq), "measured_s": time.perf_counter() - t_begin,
+            "sample": "extrapolated: the numpy oracle (float64, BLAS on %d threads) on ONE layer at the real widths "
+                      "(h1=%d, h2=%d, %d heads): decode step of 4 sequences at %d cached rows and prefill of one "
+                      "sequence of %d positions, each projection timed on a %d-row slab of its weight matrix, "
+                      "attention on the heads that fit the time budget; scaled to full matrices and all heads, "
+                      "x%d layers, x%d sequences, %d tokens each" % (threads, h1, h2, nh, rows + 1, s, slab, sh.l,
+                                                                    bls, n)}
 
 
 def run_kv_stress(args, torch, B, synth):
@@ -234,17 +294,28 @@ def run_diagonal(args, torch, B, synth):
     def step():
         return B.fg_generate_diagonal(cfg, layers, emb, pos, lnf_g, lnf_b, prompt, n, gbs, pages, ws=ws, out_ids=out_ids)
 
-    for _ in range(args.warmup):
+    # the first pass is timed on the host to plan how many passes fit the wall-clock budget
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    if args.warmup == 0:
+        B.fg_profile_begin()
+    _, st = step()
+    torch.cuda.synchronize()
+    first_s = time.perf_counter() - t0
+    W, K = plan_passes(args.steps, args.warmup, first_s,
+                       args.budget_s - (time.perf_counter() - T_PROCESS_START) - 10.0)
+    for _ in range(W - 1):
         step()
     torch.cuda.synchronize()
-    B.fg_profile_begin()
+    elapsed = first_s if args.warmup == 0 else 0.0
+    if args.warmup != 0:
+        B.fg_profile_begin()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(K - (1 if args.warmup == 0 else 0)):
         _, st = step()
     torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    elapsed += time.perf_counter() - t0
     prof = B.fg_profile_end()
-    K = args.steps
     P = 4 * sh.h1 * sh.h1 + 2 * sh.h1 * sh.h2
     rl = {}
     for name, bound, work in (("gemm_large_m", "mfma", 2.0 * n_seqs * s * P * sh.l),
@@ -266,7 +337,7 @@ def run_diagonal(args, torch, B, synth):
     block_pages = n_seqs * -(-(s + n) // B.PAGE_ROWS)
     line = {
         "metric": "generated tokens/s + % peak HBM BW, 4-bit OPT-175B-shape decode, 1 GPU",
-        "value": n_seqs * n * K / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "value": n_seqs * n * K / elapsed, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": 1e3 * elapsed / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": args.workload + ("" if not args.layers else "_%dlayers" % args.layers),
@@ -282,14 +353,48 @@ def run_diagonal(args, torch, B, synth):
     print(json.dumps(line))
 
 
+def roofline_table(prof, alg, passes, small_flops, small_bytes):
+    """Per kernel class: algorithmic work / summed event time.  alg: {class: (bound, work per pass)}."""
+    rl = {}
+    for name, (bound, work) in alg.items():
+        if name not in prof:
+            continue
+        ms = prof[name]["ms"] / passes
+        launches = prof[name]["launches"]
+        if name == "gemm_small_m" and "gemm_small_m_finish" in prof:
+            ms += prof["gemm_small_m_finish"]["ms"] / passes      # the reduction pass belongs to the projection
+        peak = HBM_PEAK if bound == "hbm" else MFMA_F16_PEAK
+        ach = work / (ms * 1e-3)
+        rl[name] = {"bound": bound, "achieved": ach / 1e9 if bound == "hbm" else ach / 1e12,
+                    "peak": peak / 1e9 if bound == "hbm" else peak / 1e12,
+                    "unit": "GB/s" if bound == "hbm" else "TFLOP/s", "frac": ach / peak, "traffic": None,
+                    "ms_per_step": ms, "launches_per_step": launches / passes,
+                    "avg_launch_us": 1e3 * ms * passes / launches}
+    if "gemm_small_m" in rl:
+        # The decode projections stream every weight once (HBM bound) and do 2*bls flops per weight
+        # (MFMA bound): the roofline is whichever takes longer at this block size; both fractions are kept.
+        r = rl["gemm_small_m"]
+        ms = r["ms_per_step"]
+        r["includes"] = "gemm_small_m_finish (reduction pass of the split contraction)"
+        r["hbm_frac"] = small_bytes / (ms * 1e-3) / HBM_PEAK
+        r["mfma_frac"] = small_flops / (ms * 1e-3) / MFMA_F16_PEAK
+        if small_flops / MFMA_F16_PEAK > small_bytes / HBM_PEAK:
+            r.update(bound="mfma", achieved=small_flops / (ms * 1e-3) / 1e12, peak=MFMA_F16_PEAK / 1e12,
+                     unit="TFLOP/s", frac=r["mfma_frac"])
+    return rl
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5, help="timed passes, at most (see --budget-s)")
+    ap.add_argument("--warmup", type=int, default=1, help="warm-up passes, at most")
+    ap.add_argument("--budget-s", type=float, default=400.0,
+                    help="wall-clock budget of the whole run in seconds, counted from process start")
     ap.add_argument("--workload", default="opt175b_q4", choices=sorted(WORKLOADS))
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; marks the line)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-table", action="store_true", help="skip the extra pass with events on every launch")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -328,76 +433,86 @@ def main():
     resident = sum(w.nbytes() for w in layers) + sum(k.nbytes() for k in kv) + emb.numel() * 2 + pos.numel() * 2
     t_setup = time.time() - t_setup
 
-    def step(want_stats):
-        return B.fg_generate(cfg, layers, emb, pos, lnf_g, lnf_b, prompt, n, ngb, gbs, kv, ws=ws, out_ids=out_ids,
-                             want_stats=want_stats)
+    def one_pass():
+        """One step of the benchmark: fg_generate over the block; returns (stats, wall seconds)."""
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        st = B.fg_generate(cfg, layers, emb, pos, lnf_g, lnf_b, prompt, n, ngb, gbs, kv, ws=ws, out_ids=out_ids,
+                           want_stats=True)[1]
+        torch.cuda.synchronize()
+        return st, time.perf_counter() - t0
 
-    warm_stats = None
-    for _ in range(args.warmup):
-        warm_stats = step(True)[1]     # per-token-step timers only: no per-kernel events in the warm-up
-    torch.cuda.synchronize()
+    # ---- first pass (warm-up if one was asked for), then plan what still fits the budget
+    timed_cheap = list(CHEAP_TO_TIME)
+    stats, walls = [], []
+    if args.warmup == 0:
+        B.fg_profile_begin(timed_cheap)
+    st, first_s = one_pass()
+    if args.warmup == 0:
+        stats.append(st)
+        walls.append(first_s)
+    reserve = (0.0 if args.no_kernel_table else 1.25 * first_s) + (0.0 if args.no_cpu_baseline else 35.0) + 5.0
+    avail = args.budget_s - (time.perf_counter() - T_PROCESS_START) - reserve
+    W, K = plan_passes(args.steps, args.warmup, first_s, avail)
+    for _ in range(W - 1):
+        one_pass()
+    # ---- timed region: K passes, events only on the few long prefill launches
+    if args.warmup != 0:
+        B.fg_profile_begin(timed_cheap)
+    while len(stats) < K:
+        st, w = one_pass()
+        stats.append(st)
+        walls.append(w)
+    prof_timed = B.fg_profile_end()
+    elapsed = sum(walls)
 
-    # ---- timed region: exactly K steps, per-kernel-class HIP events recorded on the launch stream
-    B.fg_profile_begin()
-    stats = []
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        stats.append(step(True)[1])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    prof = B.fg_profile_end()
-
-    K = args.steps
     tokens = bls * n * K
     value = tokens / elapsed
     prefill_s = sum(st["prefill_s"] for st in stats) / K
     decode_s = sum(st["decode_s"] for st in stats) / K
     step_s = [sum(st["decode_step_s"][i] for st in stats) / K for i in range(n - 1)]
 
+    # ---- one extra pass with events on every launch: the per-kernel-class table (not part of `value`)
+    prof_all, evented = None, None
+    if not args.no_kernel_table:
+        B.fg_profile_begin()
+        st, w = one_pass()
+        prof_all = B.fg_profile_end()
+        evented = {"wall_s": w, "prefill_s": st["prefill_s"], "decode_s": st["decode_s"]}
+
     # ---- algorithmic bytes / flops of each kernel class per generate (Section 4.3 terms, re-priced)
     P = 4 * sh.h1 * sh.h1 + 2 * sh.h1 * sh.h2
     w_bytes = sh.l * P * bpe(wq)
     head_bytes = sh.vocab * sh.h1 * 2.0
     kv_bytes = [2.0 * bls * sh.l * sh.h1 * (s + i) * bpe(kvq) for i in range(1, n)]
+    small_bytes = (n - 1) * (w_bytes + head_bytes) + head_bytes
     alg = {
         "gemm_large_m": ("mfma", 2.0 * bls * s * P * sh.l),
         "attn_prefill": ("mfma", 4.0 * bls * s * s * sh.h1 * sh.l / 2.0),
         "attn_decode": ("hbm", float(sum(kv_bytes))),
-        "gemm_small_m": ("hbm", (n - 1) * (w_bytes + head_bytes) + head_bytes),
+        "gemm_small_m": ("hbm", small_bytes),
         "kv_append": ("hbm", (2.0 * bls * s * sh.h1 * (2.0 + bpe(kvq)) + (n - 1) * 2.0 * bls * sh.h1 * (2 + bpe(kvq))) * sh.l),
     }
     small_flops = 2.0 * bls * ((n - 1) * (sh.l * P + sh.vocab * sh.h1) + sh.vocab * sh.h1)
-    rl = {}
-    for name, (bound, work) in alg.items():
-        if name not in prof:
-            continue
-        ms = prof[name]["ms"] / K
-        peak = HBM_PEAK if bound == "hbm" else MFMA_F16_PEAK
-        ach = work / (ms * 1e-3)
-        rl[name] = {"bound": bound, "achieved": ach / 1e9 if bound == "hbm" else ach / 1e12,
-                    "peak": peak / 1e9 if bound == "hbm" else peak / 1e12,
-                    "unit": "GB/s" if bound == "hbm" else "TFLOP/s", "frac": ach / peak, "traffic": None,
-                    "ms_per_step": ms, "launches_per_step": prof[name]["launches"] / K,
-                    "avg_launch_us": 1e3 * prof[name]["ms"] / prof[name]["launches"]}
-    if "gemm_small_m" in rl:
-        # The decode projections stream every weight once (HBM bound) and do 2*bls flops per weight
-        # (MFMA bound): the roofline is whichever takes longer at this block size; both fractions are kept.
-        ms = prof["gemm_small_m"]["ms"] / K
-        r = rl["gemm_small_m"]
-        r["hbm_frac"] = r["frac"]
-        r["mfma_frac"] = small_flops / (ms * 1e-3) / MFMA_F16_PEAK
-        if small_flops / MFMA_F16_PEAK > alg["gemm_small_m"][1] / HBM_PEAK:
-            r.update(bound="mfma", achieved=small_flops / (ms * 1e-3) / 1e12, peak=MFMA_F16_PEAK / 1e12,
-                     unit="TFLOP/s", frac=r["mfma_frac"])
-    dominant = max(rl, key=lambda k: rl[k]["ms_per_step"]) if rl else None
+    rl_timed = roofline_table(prof_timed, alg, K, small_flops, small_bytes)
+    rl_all = roofline_table(prof_all, alg, 1, small_flops, small_bytes) if prof_all else {}
+    for k, v in rl_timed.items():
+        v["measured_in"] = "the %d timed passes" % K
+    for k, v in rl_all.items():
+        v["measured_in"] = "one extra pass with events on every launch"
+    table = dict(rl_all)
+    table.update(rl_timed)     # where both exist, the figure taken over the timed region wins
+    dominant = max(table, key=lambda k: table[k]["ms_per_step"]) if table else None
+    # HBM traffic per launch comes from rocprofv3 counter runs (it cannot be measured from inside this
+    # process); the summaries under profiles/ and the file that collects their figures say when and how
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(traffic_file):
         try:
-            tr = json.load(open(traffic_file)).get(args.workload, {})
-            for k, v in tr.items():
-                if k in rl:
-                    rl[k]["traffic"] = v
+            tr = json.load(open(traffic_file))
+            for k, v in tr.get(args.workload, {}).items():
+                if k in table:
+                    table[k]["traffic"] = v
+                    table[k]["traffic_source"] = tr.get("_source", "profiles/traffic.json (rocprofv3 --pmc runs)")
         except Exception:
             pass
 
@@ -410,35 +525,31 @@ def main():
             "hbm_frac_avg": (w_bytes + sum(kv_bytes) / (n - 1)) / (decode_s / (n - 1)) / HBM_PEAK,
             "hbm_frac_at_step": {str(i + 1): (w_bytes + kv_bytes[i]) / step_s[i] / HBM_PEAK for i in pick},
             "bytes_per_step_avg": w_bytes + sum(kv_bytes) / (n - 1),
+            "note": "timed passes: no per-launch events on the decode kernels",
         }
-        if warm_stats is not None:
-            # the timed region brackets every launch with two HIP events for the per-kernel figures, which
-            # costs a few microseconds per launch; the last warm-up pass ran the same work without them
-            wd = warm_stats["decode_s"]
-            decode["without_kernel_events"] = {
-                "ms_per_token_step": 1e3 * wd / (n - 1),
-                "hbm_frac_avg": (w_bytes + sum(kv_bytes) / (n - 1)) / (wd / (n - 1)) / HBM_PEAK,
-                "prefill_s": warm_stats["prefill_s"],
-            }
 
     line = {
         "metric": "generated tokens/s + % peak HBM BW, 4-bit OPT-175B-shape decode, 1 GPU",
-        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": 1e3 * elapsed / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": args.workload + ("" if not args.layers else "_%dlayers" % args.layers),
                    "shape": {"l": sh.l, "h1": sh.h1, "nh": sh.nh, "h2": sh.h2, "vocab": sh.vocab},
                    "weights": "q4g64_h16" if wq == "h16" else ("q4g64" if wq else "f16"), "kv_cache": "q4g64_h16" if kvq == "h16" else ("q4g64" if kvq else "f16"),
                    "block": "%dx%d" % (ngb, gbs), "prompt_len": s, "gen_len": n,
-                   "resident_gb": resident / 1e9, "setup_s": t_setup},
+                   "resident_gb": resident / 1e9, "setup_s": t_setup,
+                   "requested": {"steps": args.steps, "warmup": args.warmup, "budget_s": args.budget_s},
+                   "first_pass_s": first_s},
         "prefill_s": prefill_s, "decode_s": decode_s, "decode": decode,
-        "roofline": (dict(rl[dominant], kernel=dominant) if dominant else None),
-        "roofline_kernels": rl,
-        "kernel_ms": {k: v["ms"] / K for k, v in prof.items() if v["launches"]},
+        "roofline": (dict(table[dominant], kernel=dominant) if dominant else None),
+        "roofline_kernels": table,
+        "kernel_ms": {k: v["ms"] for k, v in (prof_all or prof_timed).items() if v["launches"]},
+        "evented_pass": evented,
         "paper_context": "FlexGen reports 1.12 token/s for OPT-175B (4-bit) on one 16 GB T4 with CPU offloading",
     }
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(sh, wq, kvq, s, n)
+        line["cpu_baseline"] = cpu_baseline(sh, wq, kvq, s, n, bls)
+    line["wall_s"] = time.perf_counter() - T_PROCESS_START
     print(json.dumps(line))
 
 

@@ -354,6 +354,10 @@ typedef enum {
   FG_K_COUNT
 } fg_kernel_class;
 int fg_profile_begin(void);
+/* As fg_profile_begin, but only launches of the classes whose bit (1u << class) is set in class_mask
+ * are bracketed; the others run exactly as without profiling (an event pair costs a few microseconds
+ * per launch, which matters where a step is a thousand short launches). */
+int fg_profile_begin_classes(uint32_t class_mask);
 int fg_profile_end(void);
 int fg_profile_read(int kernel_class, double* total_ms, int64_t* launches);
 const char* fg_kernel_class_name(int kernel_class);

@@ -3,23 +3,28 @@ JSON line with its average launch duration (from the library's own HIP-event pro
 algorithmic bytes / flops per launch.  It exists so that `rocprofv3 --kernel-trace --stats` and
 `rocprofv3 --pmc ...` can be pointed at a single kernel at the shape the benchmark runs it at:
 
-  python3 -m paper_2303_06865_amd.kernel_bench linear --m 144 --n 36864 --k 12288 --wdtype q4t
-  python3 -m paper_2303_06865_amd.kernel_bench attn_decode --batch 144 --nh 96 --rows 528
-  python3 -m paper_2303_06865_amd.kernel_bench attn_decode_topk --batch 144 --nh 96 --rows 528 --topk 53
-  python3 -m paper_2303_06865_amd.kernel_bench attn_decode_paged --batch 144 --nh 96 --rows 528
-  python3 -m paper_2303_06865_amd.kernel_bench attn_prefill --batch 8 --nh 96 --seq 512
-  python3 -m paper_2303_06865_amd.kernel_bench copy --mib 1024      # calibration for HBM counters
+  python3 kernel_bench.py linear --m 144 --n 36864 --k 12288 --wdtype q4t
+  python3 kernel_bench.py attn_decode --batch 144 --nh 96 --rows 528
+  python3 kernel_bench.py attn_decode_topk --batch 144 --nh 96 --rows 528 --topk 53
+  python3 kernel_bench.py attn_decode_paged --batch 144 --nh 96 --rows 528
+  python3 kernel_bench.py attn_prefill --batch 8 --nh 96 --seq 512
+  python3 kernel_bench.py copy --mib 1024      # calibration for HBM counters
 
 Inputs are seeded synthetic tensors generated on the device (weights ~ N(0, 0.02), activations
 ~ N(0, 1), cache codes uniform), i.e. the value distributions of the benchmark's model builder.
 """
 import argparse
 import json
+import os
 import sys
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
 
 import torch
 
-from . import binding as B
+from paper_2303_06865_amd import binding as B
 
 
 def _time_classes(fn, iters, warm):

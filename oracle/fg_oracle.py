@@ -160,21 +160,6 @@ def dequantize_groupwise_f16(codes: np.ndarray, meta: np.ndarray, group: int = G
     return _dequantize_exact(codes, meta, group).astype(np.float16)
 
 
-def tile_weights(codes: np.ndarray, meta: np.ndarray):
-    """The streaming order of a quantized weight matrix (a pure permutation of the canonical bytes):
-    tiles of 32 rows x 64 columns, row blocks outermost, then the tiles of a row block along the
-    columns; inside a tile the 16-byte piece of (row r, half h of the 64-column group) sits at
-    byte 16*(32*h + r); meta: 32 pairs per tile, in the same tile order."""
-    n, kh = codes.shape
-    k = kh * 2
-    assert n % 32 == 0 and k % GROUP == 0
-    ks = k // GROUP
-    c = codes.reshape(n // 32, 32, ks, 2, 16)          # [row block, r, k tile, h, 16 bytes]
-    c = c.transpose(0, 2, 3, 1, 4)                     # [row block, k tile, h, r, 16]
-    m = meta.reshape(n // 32, 32, ks, 2).transpose(0, 2, 1, 3)   # [row block, k tile, r, {min,scale}]
-    return np.ascontiguousarray(c).reshape(n, kh), np.ascontiguousarray(m).reshape(n, ks, 2)
-
-
 # --------------------------------------------------------------------------
 # Section 3 building blocks (float64)
 # --------------------------------------------------------------------------
@@ -458,7 +443,7 @@ def greedy(logits32: np.ndarray) -> np.ndarray:
 
 def generate(cfg: ModelCfg, layers: List[LayerWeights], emb16, pos16, lnf_g, lnf_b,
              prompt: np.ndarray, n: int, num_gpu_batches: int, gpu_batch_size: int,
-             kv_quantized: bool, return_trace: bool = False):
+             kv_quantized: bool, return_trace: bool = False, kv_meta_f16: bool = False):
     """Generate n tokens for a block of num_gpu_batches x gpu_batch_size
     sequences with the block schedule (Algorithm 1): token step i outermost,
     then layer j, then GPU batch k.  Step 1 is the prefill of the whole prompt
@@ -466,14 +451,14 @@ def generate(cfg: ModelCfg, layers: List[LayerWeights], emb16, pos16, lnf_g, lnf
     in one memory the load/store calls of Algorithm 1 have nothing to move, so
     only compute(i, j, k) remains.
 
-    prompt int32 [bls, s].  Returns ids int32 [bls, n] (and, on request, the
-    per-step logits float32 [n, bls, vocab])."""
+    prompt int32 [bls, s].  kv_meta_f16: the compressed cache keeps FP16 (min, scale) pairs.
+    Returns ids int32 [bls, n] (and, on request, the per-step logits float32 [n, bls, vocab])."""
     bls, s = prompt.shape
     assert bls == num_gpu_batches * gpu_batch_size
     assert n >= 1 and s + n - 1 <= cfg.max_pos
     l = len(layers)
     cap = s + n
-    caches = [KVCache.empty(bls, cfg.nh, cap, cfg.dh, kv_quantized) for _ in range(l)]
+    caches = [KVCache.empty(bls, cfg.nh, cap, cfg.dh, kv_quantized, kv_meta_f16) for _ in range(l)]
     ids = np.zeros((bls, n), np.int32)
     trace = []
     sl = [slice(k * gpu_batch_size, (k + 1) * gpu_batch_size) for k in range(num_gpu_batches)]

@@ -124,6 +124,7 @@ EXPORTS = {
                                                  C.c_int32, C.c_int32, C.c_int32]),
     "fg_diagonal_pages_needed": (C.c_int64, [C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "fg_profile_begin": (C.c_int, []),
+    "fg_profile_begin_classes": (C.c_int, [C.c_uint32]),
     "fg_profile_end": (C.c_int, []),
     "fg_profile_read": (C.c_int, [C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "fg_kernel_class_name": (C.c_char_p, [C.c_int]),
@@ -535,8 +536,15 @@ def fg_generate_diagonal(cfg: Cfg, layers: Sequence[LayerWeights], embed: torch.
     return out_ids, {"total_s": stats.decode_s, "tokens": stats.tokens, "peak_pages": peak.value}
 
 
-def fg_profile_begin() -> None:
-    _check(lib().fg_profile_begin(), "fg_profile_begin")
+def fg_profile_begin(classes: Optional[Sequence[str]] = None) -> None:
+    """classes: names from KERNEL_CLASSES to time (None = all of them)."""
+    if classes is None:
+        _check(lib().fg_profile_begin(), "fg_profile_begin")
+        return
+    mask = 0
+    for name in classes:
+        mask |= 1 << KERNEL_CLASSES.index(name)
+    _check(lib().fg_profile_begin_classes(mask), "fg_profile_begin_classes")
 
 
 def fg_profile_end() -> Dict[str, Dict[str, float]]:

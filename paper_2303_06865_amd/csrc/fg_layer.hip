@@ -23,6 +23,7 @@ struct ProfRec {
   hipEvent_t e0, e1;
 };
 static bool g_prof_on = false;
+static uint32_t g_prof_mask = 0xffffffffu;   // bit k set: launches of kernel class k are timed
 static std::vector<ProfRec> g_prof_open;
 static double g_prof_ms[FG_K_COUNT];
 static int64_t g_prof_n[FG_K_COUNT];
@@ -30,10 +31,15 @@ static int64_t g_prof_n[FG_K_COUNT];
 bool profile_enabled() { return g_prof_on; }
 
 void profile_mark(int kclass, hipStream_t stream, bool begin) {
+  if (!((g_prof_mask >> kclass) & 1u)) return;
   if (begin) {
     ProfRec r;
     r.k = kclass;
-    if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return;
+    if (hipEventCreate(&r.e0) != hipSuccess) return;
+    if (hipEventCreate(&r.e1) != hipSuccess) {
+      (void)hipEventDestroy(r.e0);
+      return;
+    }
     (void)hipEventRecord(r.e0, stream);
     g_prof_open.push_back(r);
   } else {
@@ -209,10 +215,13 @@ struct PagedKv {
 };
 static int run_layer(const fg_model_cfg& c, const fg_layer_weights& w, const half_t* x_in, int32_t b, int32_t s,
                      bool prefill, int32_t t, const fg_kv_cache& kv, int32_t batch_offset, half_t* x_out,
-                     void* ws, hipStream_t st, const PagedKv* paged = nullptr) {
+                     void* ws, size_t ws_bytes, hipStream_t st, const PagedKv* paged = nullptr) {
   const int64_t rows = (int64_t)b * (prefill ? s : 1);
   const int64_t h1 = c.h1;
   LayerWs L = carve_layer_ws(c, w, rows, ws);
+  // the scratch is carved for THIS row count; the size of the GEMMs' partial-sum area is not monotone in
+  // the row count, so a buffer sized for more rows need not be large enough
+  if (L.total > ws_bytes) return FG_ERR_WORKSPACE;
   int rc;
   if ((rc = layernorm_launch(x_in, h1, reinterpret_cast<const half_t*>(w.ln1_g),
                              reinterpret_cast<const half_t*>(w.ln1_b), rows, h1, c.ln_eps, L.y, h1, st)))
@@ -273,8 +282,9 @@ static HeadWs carve_head_ws(const fg_model_cfg& c, int64_t rows, void* base) {
 
 static int run_lm_head(const fg_model_cfg& c, const half_t* x, int64_t ldx, int64_t rows, const half_t* g,
                        const half_t* bta, const half_t* emb, int32_t* out_ids, int64_t out_stride, float* logits,
-                       void* ws, hipStream_t st, const int32_t* out_index = nullptr) {
+                       void* ws, size_t ws_bytes, hipStream_t st, const int32_t* out_index = nullptr) {
   HeadWs H = carve_head_ws(c, rows, ws);
+  if (H.total > ws_bytes) return FG_ERR_WORKSPACE;
   int rc;
   if ((rc = layernorm_launch(x, ldx, g, bta, rows, c.h1, c.ln_eps, H.y, c.h1, st))) return rc;
   LinearArgs a;
@@ -325,7 +335,7 @@ extern "C" const char* fg_kernel_class_name(int k) {
   return (k >= 0 && k < FG_K_COUNT) ? names[k] : "?";
 }
 
-extern "C" int fg_profile_begin(void) {
+extern "C" int fg_profile_begin_classes(uint32_t class_mask) {
   for (auto& r : g_prof_open) {
     (void)hipEventDestroy(r.e0);
     (void)hipEventDestroy(r.e1);
@@ -333,9 +343,12 @@ extern "C" int fg_profile_begin(void) {
   g_prof_open.clear();
   memset(g_prof_ms, 0, sizeof(g_prof_ms));
   memset(g_prof_n, 0, sizeof(g_prof_n));
-  g_prof_on = true;
+  g_prof_mask = class_mask;
+  g_prof_on = class_mask != 0;
   return FG_OK;
 }
+
+extern "C" int fg_profile_begin(void) { return fg_profile_begin_classes(0xffffffffu); }
 
 extern "C" int fg_profile_end(void) {
   g_prof_on = false;
@@ -417,7 +430,7 @@ extern "C" int fg_lm_head_greedy(const fg_model_cfg* cfg, const void* x_f16, int
   if (!ws || ws_bytes < carve_head_ws(*cfg, rows, nullptr).total) return FG_ERR_WORKSPACE;
   return run_lm_head(*cfg, reinterpret_cast<const half_t*>(x_f16), x_row_stride, rows,
                      reinterpret_cast<const half_t*>(lnf_g), reinterpret_cast<const half_t*>(lnf_b),
-                     reinterpret_cast<const half_t*>(embed_f16), out_ids, out_stride, logits_f32, ws,
+                     reinterpret_cast<const half_t*>(embed_f16), out_ids, out_stride, logits_f32, ws, ws_bytes,
                      as_stream(stream));
 }
 
@@ -453,7 +466,7 @@ extern "C" int fg_prefill_layer(const fg_model_cfg* cfg, const fg_layer_weights*
   if (!ws || ws_bytes < need) return FG_ERR_WORKSPACE;
   if (!aligned16(ws)) return FG_ERR_SHAPE;
   return run_layer(*cfg, *wts, reinterpret_cast<const half_t*>(x_in), b, s, true, 0, *kv, batch_offset,
-                   reinterpret_cast<half_t*>(x_out), ws, as_stream(stream));
+                   reinterpret_cast<half_t*>(x_out), ws, ws_bytes, as_stream(stream));
 }
 
 extern "C" int fg_decode_layer(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in, int32_t b,
@@ -470,7 +483,7 @@ extern "C" int fg_decode_layer(const fg_model_cfg* cfg, const fg_layer_weights* 
   if (!ws || ws_bytes < need) return FG_ERR_WORKSPACE;
   if (!aligned16(ws)) return FG_ERR_SHAPE;
   return run_layer(*cfg, *wts, reinterpret_cast<const half_t*>(x_in), b, 1, false, t, *kv, batch_offset,
-                   reinterpret_cast<half_t*>(x_out), ws, as_stream(stream));
+                   reinterpret_cast<half_t*>(x_out), ws, ws_bytes, as_stream(stream));
 }
 
 static int paged_layer_entry(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in, int32_t b,
@@ -493,7 +506,7 @@ static int paged_layer_entry(const fg_model_cfg* cfg, const fg_layer_weights* wt
   const PagedKv pk = {pages, seqs};
   const fg_kv_cache none = {};
   return run_layer(*cfg, *wts, reinterpret_cast<const half_t*>(x_in), b, s, prefill, 0, none, 0,
-                   reinterpret_cast<half_t*>(x_out), ws, as_stream(stream), &pk);
+                   reinterpret_cast<half_t*>(x_out), ws, ws_bytes, as_stream(stream), &pk);
 }
 
 extern "C" int fg_decode_layer_paged(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in,
@@ -614,11 +627,11 @@ extern "C" int fg_generate(const fg_model_cfg* cfg, int32_t l, const fg_layer_we
     for (int k = 0; k < num_gpu_batches; ++k) {
       half_t* xk = G.x_all + (int64_t)k * gpu_batch_size * s * h1;
       FG_TRY(run_layer(*cfg, layers[j], xk, gpu_batch_size, s, true, 0, kv[j], k * gpu_batch_size, xk, G.layer,
-                       st));
+                       G.layer_bytes, st));
     }
   }
   FG_TRY(run_lm_head(*cfg, G.x_all + (int64_t)(s - 1) * h1, (int64_t)s * h1, bls, fg_, fb_, emb, out_ids, n,
-                     G.logits, G.head, st));
+                     G.logits, G.head, G.head_bytes, st));
   FG_TRY(mark());
   // ---- token steps 2..n: decode.  Every layer takes all bls rows in one pass, so its weights are
   // streamed from HBM once per step for the whole block.
@@ -626,8 +639,8 @@ extern "C" int fg_generate(const fg_model_cfg* cfg, int32_t l, const fg_layer_we
     const int t = s + i - 1;   // rows already cached = absolute position of the token fed back
     FG_TRY(embed_launch(emb, pos, out_ids + (i - 1), n, bls, 1, t, cfg->h1, cfg->vocab, G.x_dec, st));
     for (int j = 0; j < l; ++j)
-      FG_TRY(run_layer(*cfg, layers[j], G.x_dec, bls, 1, false, t, kv[j], 0, G.x_dec, G.layer, st));
-    FG_TRY(run_lm_head(*cfg, G.x_dec, h1, bls, fg_, fb_, emb, out_ids + i, n, G.logits, G.head, st));
+      FG_TRY(run_layer(*cfg, layers[j], G.x_dec, bls, 1, false, t, kv[j], 0, G.x_dec, G.layer, G.layer_bytes, st));
+    FG_TRY(run_lm_head(*cfg, G.x_dec, h1, bls, fg_, fb_, emb, out_ids + i, n, G.logits, G.head, G.head_bytes, st));
     FG_TRY(mark());
   }
 #undef FG_TRY
@@ -739,6 +752,7 @@ struct DiagWs {
   void* layer;
   size_t layer_bytes;
   void* head;
+  size_t head_bytes;
   size_t total;
 };
 int diag_bmax(int n_seqs, int n, int gbs) {
@@ -764,11 +778,20 @@ DiagWs carve_diag_ws(const fg_model_cfg& c, const fg_layer_weights& w0, int n_se
   D.logits = reinterpret_cast<float*>(take((size_t)(gbs > brow ? gbs : brow) * c.vocab * 4));
   D.n_ints = (size_t)n_seqs * max_pages + gbs + 4 * (size_t)brow;
   D.ints = reinterpret_cast<int32_t*>(take(D.n_ints * 4));
-  const size_t lp = carve_layer_ws(c, w0, (int64_t)gbs * s, nullptr).total;
-  const size_t ld = carve_layer_ws(c, w0, brow, nullptr).total;
-  D.layer_bytes = lp > ld ? lp : ld;
+  // Per-layer scratch: the largest need over the prefill square and EVERY decode row count the schedule
+  // runs (gbs, 2*gbs, ..., bmax).  Not just the largest row count: the partial-sum area of the GEMMs
+  // depends on the tile shape picked for the row count and can shrink when the rows grow.
+  D.layer_bytes = carve_layer_ws(c, w0, (int64_t)gbs * s, nullptr).total;
+  size_t head_bytes = carve_head_ws(c, gbs, nullptr).total;
+  for (int b = gbs; b <= bmax; b += gbs) {
+    const size_t ld = carve_layer_ws(c, w0, b, nullptr).total;
+    D.layer_bytes = ld > D.layer_bytes ? ld : D.layer_bytes;
+    const size_t hd = carve_head_ws(c, b, nullptr).total;
+    head_bytes = hd > head_bytes ? hd : head_bytes;
+  }
   D.layer = take(D.layer_bytes);
-  D.head = take(carve_head_ws(c, gbs > brow ? gbs : brow, nullptr).total);
+  D.head_bytes = head_bytes;
+  D.head = take(head_bytes);
   D.total = off;
   return D;
 }
@@ -913,17 +936,17 @@ extern "C" int fg_generate_diagonal(const fg_model_cfg* cfg, int32_t l, const fg
     for (int j = 0; j < l; ++j) {
       if (admit) {
         const PagedKv pk = {&pages[j], &rn};
-        FG_TRY(run_layer(*cfg, layers[j], D.x_new, gbs, s, true, 0, none, 0, D.x_new, D.layer, st, &pk));
+        FG_TRY(run_layer(*cfg, layers[j], D.x_new, gbs, s, true, 0, none, 0, D.x_new, D.layer, D.layer_bytes, st, &pk));
       }
       if (b > 0) {
         const PagedKv pk = {&pages[j], &rd};
-        FG_TRY(run_layer(*cfg, layers[j], D.x_dec, b, 1, false, 0, none, 0, D.x_dec, D.layer, st, &pk));
+        FG_TRY(run_layer(*cfg, layers[j], D.x_dec, b, 1, false, 0, none, 0, D.x_dec, D.layer, D.layer_bytes, st, &pk));
       }
     }
     if (admit)
       FG_TRY(run_lm_head(*cfg, D.x_new + (int64_t)(s - 1) * h1, (int64_t)s * h1, gbs, fg_, fb_, emb,
-                         out_ids + (int64_t)it * gbs * n, n, D.logits, D.head, st));
-    if (b > 0) FG_TRY(run_lm_head(*cfg, D.x_dec, h1, b, fg_, fb_, emb, out_ids, 0, D.logits, D.head, st, d_out));
+                         out_ids + (int64_t)it * gbs * n, n, D.logits, D.head, D.head_bytes, st));
+    if (b > 0) FG_TRY(run_lm_head(*cfg, D.x_dec, h1, b, fg_, fb_, emb, out_ids, 0, D.logits, D.head, D.head_bytes, st, d_out));
     plan.end_iteration(it);
   }
 #undef FG_TRY

@@ -385,6 +385,7 @@ extern "C" int fg_kv_append(const fg_model_cfg* cfg, const void* k_f16, const vo
   if (row_stride < cfg->h1 || row_stride % 8 != 0) return FG_ERR_SHAPE;
   if (b == 0 || s == 0) return FG_OK;
   if (!k_f16 || !v_f16) return FG_ERR_NULL;
+  if (((uintptr_t)k_f16 | (uintptr_t)v_f16) & 15u) return FG_ERR_SHAPE;   // the kernels load 16 bytes per lane
   return kv_append_launch(*cfg, reinterpret_cast<const half_t*>(k_f16), reinterpret_cast<const half_t*>(v_f16),
                           row_stride, b, s, *kv, batch_offset, pos0, as_stream(stream));
 }
@@ -401,6 +402,7 @@ extern "C" int fg_kv_append_paged(const fg_model_cfg* cfg, const void* k_f16, co
   if (row_stride < cfg->h1 || row_stride % 8 != 0) return FG_ERR_SHAPE;
   if (b == 0 || s == 0) return FG_OK;
   if (!k_f16 || !v_f16) return FG_ERR_NULL;
+  if (((uintptr_t)k_f16 | (uintptr_t)v_f16) & 15u) return FG_ERR_SHAPE;
   return kv_append_paged_launch(*cfg, reinterpret_cast<const half_t*>(k_f16), reinterpret_cast<const half_t*>(v_f16),
                                 row_stride, b, s, *pages, *seqs, true, as_stream(stream));
 }

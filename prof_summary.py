@@ -1,6 +1,6 @@
 """Turn rocprofv3 results into the short text summaries kept under profiles/:
-  python -m paper_2303_06865_amd.prof_summary <results.db>                 kernel-trace database (rocpd SQLite)
-  python -m paper_2303_06865_amd.prof_summary <x_counter_collection.csv>   --pmc run with --output-format csv
+  python3 prof_summary.py <results.db>                 kernel-trace database (rocpd SQLite)
+  python3 prof_summary.py <x_counter_collection.csv>   --pmc run with --output-format csv
 For counters the summary is the mean value per dispatch of every (kernel, counter) pair."""
 import csv
 import re

@@ -183,3 +183,28 @@ def test_paged_and_diagonal_argument_errors_need_no_gpu():
     assert gen(4, 2040, 10, 1) == B.FG_ERR_SHAPE       # positions beyond max_pos
     assert L.fg_diagonal_workspace_bytes(C.byref(cfg), C.byref(w), 4, 70, 4, 1) > 0
     assert L.fg_diagonal_workspace_bytes(C.byref(cfg), C.byref(w), 4, 70, 4, 3) == 0
+
+
+@pytest.mark.parametrize("h1,nh,h2,dtype", [(768, 12, 3072, B.FG_Q4G64_TILED), (12288, 96, 49152, B.FG_Q4G64_TILED),
+                                            (768, 12, 3072, B.FG_Q4G64)])
+def test_diagonal_workspace_covers_every_decode_row_count(h1, nh, h2, dtype):
+    """The per-layer scratch of the diagonal driver must be large enough for EVERY row count an
+    iteration can run, not only the largest: the partial-sum area of the projections depends on the
+    tile shape picked for the row count (160 rows take more than 161..192).  Host arithmetic only:
+    the driver's total must exceed the largest single need plus what it reserves besides."""
+    L = B.lib()
+    cfg = _cfg(h1=h1, nh=nh, h2=h2)
+    a = 4096
+    mat = lambda r, c: B.fg_mat(a, a, dtype, 0, r, c)
+    w = B.fg_layer_weights(mat(3 * h1, h1), mat(h1, h1), mat(h2, h1), mat(h1, h2), None, None, None, None, a, a, a, a)
+    n_seqs, s, n, gbs = 192, 16, 32, 8
+    bmax = min(n_seqs // gbs, n - 1) * gbs
+    assert bmax == 192
+    need = [L.fg_layer_workspace_bytes(C.byref(cfg), C.byref(w), b) for b in range(gbs, bmax + 1, gbs)]
+    need.append(L.fg_layer_workspace_bytes(C.byref(cfg), C.byref(w), gbs * s))
+    if dtype == B.FG_Q4G64_TILED:
+        # the case behind this test: the need is not monotone in the row count
+        assert need[160 // gbs - 1] > need[192 // gbs - 1]
+    total = L.fg_diagonal_workspace_bytes(C.byref(cfg), C.byref(w), n_seqs, s, n, gbs)
+    other = gbs * s * h1 * 2 + bmax * h1 * 2 + bmax * 50272 * 4     # activations and logits it also holds
+    assert total >= max(need) + other

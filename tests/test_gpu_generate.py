@@ -8,7 +8,7 @@ import torch
 from oracle import fg_oracle as O
 from paper_2303_06865_amd import binding as B
 from paper_2303_06865_amd import synth
-from tests.util import cfg_pair, dev, host, oracle_layer
+from tests.util import assert_close, cfg_pair, dev, host, oracle_layer
 
 pytestmark = pytest.mark.gpu
 
@@ -33,26 +33,57 @@ def _gpu_generate(cfg, layers, m, prompt, n, ngb, gbs, quant_kv):
     return host(ids), stats
 
 
-def _compare_ids(got, ref, logits, err=2e-3):
-    """Ids must be equal.  The one admissible exception is a near-tie: the GPU's token is the
-    oracle's runner-up region, i.e. the oracle's own logit gap between its winner and the GPU's
-    choice is below 4 x `err` x rms of that logit row, `err` being the relative logit error to
-    expect: 2e-3 with FP16 caches; 1e-2 with 4-bit caches, where the two sides' caches differ by
-    whole quantization steps in a fraction of a percent of their entries (an FP16 ulp of difference
-    in a K/V value that crosses a rounding boundary) and short contexts average little of that
-    away.  Such events are printed; a sequence is not compared past its first near-tie because its
-    later tokens legitimately follow a different prefix.  Returns the number of near-ties."""
+def _gpu_logits_trace(cfg, layers, m, prompt, n, ngb, gbs, quant_kv, meta_f16=False):
+    """The block schedule of fg_generate replayed through the library's per-step calls (embedding,
+    prefill layer per GPU batch, decode layer over the whole block, final LN + head), feeding back the
+    device's own greedy ids, so that the logits of EVERY token step can be read out.  Same kernels at
+    the same launch shapes as inside fg_generate.  Returns (ids [bls, n], logits float32 [n, bls, vocab])."""
+    bls, s = prompt.shape
+    E, P, G, Bt = dev(m["embed"]), dev(m["pos"]), dev(m["lnf_g"]), dev(m["lnf_b"])
+    kv = [B.KVCache(cfg, bls, s + n, quant_kv, meta_f16=meta_f16) for _ in layers]
+    ids = np.zeros((bls, n), np.int32)
+    trace = []
+    parts = []
+    for k in range(ngb):
+        x = B.fg_embed(cfg, E, P, dev(prompt[k * gbs:(k + 1) * gbs].reshape(-1)), s, 0).reshape(gbs, s, cfg.h1)
+        for j, w in enumerate(layers):
+            x = B.fg_prefill_layer(cfg, w, x, kv[j], batch_offset=k * gbs)
+        parts.append(x[:, -1].contiguous())
+    tok, lg = B.fg_lm_head_greedy(cfg, torch.cat(parts, 0).contiguous(), G, Bt, E)
+    ids[:, 0] = host(tok)
+    trace.append(host(lg))
+    for i in range(1, n):
+        x = B.fg_embed(cfg, E, P, dev(ids[:, i - 1].copy()), 1, s + i - 1)
+        for j, w in enumerate(layers):
+            x = B.fg_decode_layer(cfg, w, x, s + i - 1, kv[j])
+        tok, lg = B.fg_lm_head_greedy(cfg, x, G, Bt, E)
+        ids[:, i] = host(tok)
+        trace.append(host(lg))
+    torch.cuda.synchronize()
+    return ids, np.stack(trace)
+
+
+def _compare_ids(got, ref, ologits, glogits, what):
+    """Greedy ids must be equal.  The one admissible exception is a near-tie, decided by MEASUREMENT:
+    at the first step where a sequence's id differs, both sides have seen the same prefix, so their
+    logit rows are comparable; `err` is the largest difference between the device's and the oracle's
+    logits of that row, and the oracle's own gap between its winner and the device's choice must not
+    exceed 2 * err (the device's choice then really is within its logit error of the top).  A sequence
+    is not compared past its first near-tie, since its later tokens follow a different prefix.
+    Every near-tie is recorded and listed in the run's summary.  Returns their number."""
+    from tests import util
+    util.ID_COMPARISONS[0] += 1
     ties = 0
     for b, i in np.argwhere(got != ref):
         if np.any(got[b, :i] != ref[b, :i]):
             continue
-        row = logits[i, b].astype(np.float64)
-        gap = float(row[ref[b, i]] - row[got[b, i]])
-        allowed = 4 * err * float(np.sqrt((row ** 2).mean()))
-        assert 0 <= gap < allowed, "sequence %d step %d: ids %d vs %d, oracle gap %.3e (near-tie bound %.3e)" % (
-            b, i, got[b, i], ref[b, i], gap, allowed)
-        print("near-tie: sequence %d step %d ids %d vs %d, oracle gap %.3e < %.3e" % (
-            b, i, got[b, i], ref[b, i], gap, allowed))
+        orow = ologits[i, b].astype(np.float64)
+        err = float(np.abs(glogits[i, b].astype(np.float64) - orow).max())
+        gap = float(orow[ref[b, i]] - orow[got[b, i]])
+        assert 0 <= gap <= 2 * err, "%s: sequence %d step %d: ids %d vs %d, oracle gap %.3e > 2 x measured logit error %.3e" % (
+            what, b, i, got[b, i], ref[b, i], gap, err)
+        util.NEAR_TIES.append("%s: sequence %d step %d ids %d vs %d, oracle gap %.3e, measured logit error %.3e" % (
+            what, b, i, got[b, i], ref[b, i], gap, err))
         ties += 1
     return ties
 
@@ -68,8 +99,12 @@ def test_generate_opt125m_config(n):
                                 return_trace=True)
     got, stats = _gpu_generate(cfg, layers, m, prompt, n, 1, 4, True)
     assert got.shape == (4, n)
-    _compare_ids(got, ref, logits)
-    assert np.array_equal(got, ref)
+    assert np.array_equal(got, ref)            # this configuration: no near-tie is admitted
+    ids2, glogits = _gpu_logits_trace(cfg, layers, m, prompt, n, 1, 4, True)
+    assert np.array_equal(ids2, got)           # the replay is the same computation
+    assert _compare_ids(got, ref, logits, glogits, "opt125m n=%d" % n) == 0
+    # logits of every step against the oracle's, as activations (they are O(1) here)
+    assert_close(glogits, logits, "logits of all steps")
     assert stats["tokens"] == 4 * n and stats["prefill_s"] > 0 and len(stats["decode_step_s"]) == n - 1
     w_elems = 4 * 768 * 768 + 2 * 768 * 3072
     assert stats["weight_bytes_per_step"] == w_elems * 5 // 8
@@ -88,7 +123,9 @@ def test_generate_small_multilayer_and_factorisations(quant):
     outs = []
     for ngb, gbs in ((1, 6), (2, 3), (6, 1), (3, 2)):
         got, _ = _gpu_generate(cfg, layers, m, prompt, 6, ngb, gbs, quant)
-        assert _compare_ids(got, ref, logits, 1e-2 if quant else 2e-3) <= 1
+        ids2, glogits = _gpu_logits_trace(cfg, layers, m, prompt, 6, ngb, gbs, quant)
+        assert np.array_equal(ids2, got)
+        assert _compare_ids(got, ref, logits, glogits, "3 layers %dx%d quant=%s" % (ngb, gbs, quant)) <= 1
         outs.append(got)
     for o in outs[1:]:
         assert np.array_equal(o, outs[0])
@@ -113,6 +150,7 @@ def test_generate_single_token_and_async_call():
     (8, 1, 9, 3, False),      # more batches than steps: pages are recycled
     (4, 2, 60, 7, True),      # sequences grow across a page boundary; FP16-pair pages
     (3, 3, 5, 1, False),      # n = 1: prefill iterations only
+    (176, 8, 5, 23, False),   # decode passes of 8, 16, ..., 176 rows: every tile shape, across 160 rows
 ])
 def test_generate_diagonal_schedule(n_seqs, gbs, s, n, meta_f16):
     """Appendix, diagonal block schedule over paged caches: the ids are those of the oracle's block
@@ -121,7 +159,7 @@ def test_generate_diagonal_schedule(n_seqs, gbs, s, n, meta_f16):
     ocfg, cfg, olayers, layers, m = _models(sh, 11, True, 0.08, True, True)
     prompt = synth.prompt_ids(n_seqs, s, sh.vocab, 13)
     ref, logits, _ = O.generate(ocfg, olayers, m["embed"], m["pos"], m["lnf_g"], m["lnf_b"], prompt, n, n_seqs // gbs,
-                                gbs, True, return_trace=True)
+                                gbs, True, return_trace=True, kv_meta_f16=meta_f16)
     _, opeak = O.generate_diagonal(ocfg, olayers[:1], m["embed"], m["pos"], m["lnf_g"], m["lnf_b"], prompt, n, gbs,
                                    return_page_use=True)
     need = B.fg_diagonal_pages_needed(n_seqs, s, n, gbs)
@@ -135,7 +173,10 @@ def test_generate_diagonal_schedule(n_seqs, gbs, s, n, meta_f16):
     torch.cuda.synchronize()
     got = host(ids)
     assert got.shape == (n_seqs, n) and st["tokens"] == n_seqs * n and st["peak_pages"] == need and st["total_s"] > 0
-    assert _compare_ids(got, ref, logits, 1e-2) <= 1
+    # the diagonal order only reorders independent work: the block-schedule replay supplies the logits
+    ids2, glogits = _gpu_logits_trace(cfg, layers, m, prompt, n, n_seqs // gbs, gbs, True, meta_f16)
+    ties = _compare_ids(got, ref, logits, glogits, "diagonal %d seqs gbs %d s %d n %d" % (n_seqs, gbs, s, n))
+    assert ties <= max(1, n_seqs // 64)
 
 
 def test_generate_diagonal_rejects_a_pool_that_is_too_small():

@@ -11,6 +11,7 @@ from oracle import fg_oracle as O
 from paper_2303_06865_amd import binding as B
 from paper_2303_06865_amd import synth
 from tests.util import assert_close, dev, host, rel_l2
+from tests.weight_layout import tile_weights
 
 pytestmark = pytest.mark.gpu
 
@@ -153,7 +154,7 @@ def _linear_case(m, n, k, quant, bias, relu, residual, seed, std_w=0.02, std_x=1
         assert np.array_equal(host(wm.data), om.codes) and np.array_equal(host(wm.meta).view(bits), om.meta.view(bits))
     if tiled:
         wm = wm.tiled()
-        tc, tmeta = O.tile_weights(om.codes, om.meta)
+        tc, tmeta = tile_weights(om.codes, om.meta)
         assert np.array_equal(host(wm.data), tc) and np.array_equal(host(wm.meta).view(bits), tmeta.view(bits))
     out = B.fg_linear(wm, dev(b16), dev(x16), dev(r16), relu)
     torch.cuda.synchronize()

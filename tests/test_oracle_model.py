@@ -127,3 +127,74 @@ def test_decode_step_uses_absolute_position():
     pos3[7:] += np.float16(1.0)      # rows >= s+n-1 are never read
     c = O.generate(cfg, layers, m["embed"], pos3, m["lnf_g"], m["lnf_b"], prompt, 4, 1, 1, False)
     assert np.array_equal(a, c)
+
+
+# ---------------------------------------------------------------- LM head (final LN + tied head)
+def test_lm_head_logits_against_torch_float64():
+    """Independent formulation with library routines: torch.nn.functional.layer_norm in float64,
+    FP16 storage of the normalised row, then a float64 matmul against the SAME matrix that embeds the
+    tokens (tied head).  A missing final LayerNorm, a swapped gamma/beta, a transposed head or a head
+    that is not the embedding fails here."""
+    import torch
+    rng = np.random.default_rng(11)
+    cfg = O.ModelCfg(h1=64, nh=1, h2=128, vocab=37, max_pos=8)
+    x = (rng.standard_normal((5, 64)) * 3.0 + 0.7).astype(np.float16)       # non-zero mean: LN must centre it
+    g = (1.0 + 0.3 * rng.standard_normal(64)).astype(np.float16)
+    b = (0.2 * rng.standard_normal(64)).astype(np.float16)
+    emb = (rng.standard_normal((37, 64)) * 0.5).astype(np.float16)
+    got = O.lm_head_logits(cfg, x, g, b, emb)
+    assert got.dtype == np.float32 and got.shape == (5, 37)
+    y = torch.nn.functional.layer_norm(torch.from_numpy(x.astype(np.float64)), (64,),
+                                       torch.from_numpy(g.astype(np.float64)), torch.from_numpy(b.astype(np.float64)),
+                                       cfg.ln_eps)
+    y = y.to(torch.float16).to(torch.float64)                               # FP16 storage of the LN output
+    ref = (y @ torch.from_numpy(emb.astype(np.float64)).T).numpy()
+    assert np.allclose(got, ref, rtol=2e-6, atol=2e-6)
+    # the pieces that must be there: without the LN, or with the untransposed / another matrix, it differs
+    no_ln = x.astype(np.float64) @ emb.astype(np.float64).T
+    assert np.abs(got - no_ln).max() > 0.5
+
+
+def test_lm_head_one_hot_state_selects_one_embedding_column():
+    """Closed form.  With gamma = 1, beta = 0 a hidden state c*e_j normalises to
+    (e_j - 1/h) * c / sqrt(c^2 (1/h)(1 - 1/h) + eps); its logit against embedding row v is therefore
+    a * (E[v, j] - mean(E[v, :])): the head reads COLUMN j of E (row-major [vocab, h1], tied), which
+    pins orientation and tying, and the centring pins the final LayerNorm."""
+    h, vocab, j, c = 64, 23, 17, 4.0
+    rng = np.random.default_rng(5)
+    emb = (rng.standard_normal((vocab, h))).astype(np.float16)
+    cfg = O.ModelCfg(h1=h, nh=1, h2=128, vocab=vocab, max_pos=8)
+    x = np.zeros((1, h), np.float16)
+    x[0, j] = c
+    got = O.lm_head_logits(cfg, x, np.ones(h, np.float16), np.zeros(h, np.float16), emb)[0].astype(np.float64)
+    var = c * c * (1.0 / h) * (1.0 - 1.0 / h)
+    inv = 1.0 / np.sqrt(var + cfg.ln_eps)
+    y = np.full(h, -c / h * inv)
+    y[j] = (c - c / h) * inv
+    y = y.astype(np.float16).astype(np.float64)                              # FP16 storage of the LN output
+    ref = np.array([sum(float(y[k]) * float(emb[v, k]) for k in range(h)) for v in range(vocab)])
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-6)
+    # ... which is, up to the FP16 rounding of y, a multiple of the centred column j of E
+    e64 = emb.astype(np.float64)
+    approx = (c * inv) * (e64[:, j] - e64.mean(axis=1))
+    assert np.abs(got - approx).max() < 2e-2 * np.abs(approx).max()
+    assert int(O.greedy(got[None].astype(np.float32))[0]) == int(np.argmax(e64[:, j] - e64.mean(axis=1)))
+
+
+def test_generate_first_token_from_independent_pieces():
+    """Token 1 of generate() recomputed with torch float64 for the model-level glue (embedding sum,
+    final LayerNorm, tied head) around the oracle's own prefill_layer (pinned in test_oracle_layer)."""
+    import torch
+    sh, cfg, layers, m = _tiny_model(quant=True)
+    prompt = synth.prompt_ids(2, 6, sh.vocab, 2)
+    ids = O.generate(cfg, layers, m["embed"], m["pos"], m["lnf_g"], m["lnf_b"], prompt, 1, 1, 2, True)
+    E = torch.from_numpy(m["embed"].astype(np.float64))
+    P = torch.from_numpy(m["pos"].astype(np.float64))
+    x = (E[torch.from_numpy(prompt.astype(np.int64))] + P[:6][None]).to(torch.float16).numpy()
+    for j in range(2):
+        x = O.prefill_layer(cfg, layers[j], x, O.KVCache.empty(2, sh.nh, 7, sh.dh, True))
+    y = torch.nn.functional.layer_norm(torch.from_numpy(x[:, -1].astype(np.float64)), (sh.h1,),
+                                       torch.from_numpy(m["lnf_g"].astype(np.float64)),
+                                       torch.from_numpy(m["lnf_b"].astype(np.float64)), cfg.ln_eps)
+    logits = (y.to(torch.float16).to(torch.float64) @ E.T).to(torch.float32)
+    assert np.array_equal(ids[:, 0], torch.argmax(logits, dim=-1).numpy().astype(np.int32))

@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 
 from oracle import fg_oracle as O
+from tests.weight_layout import tile_weights
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -203,7 +204,7 @@ def test_tiled_order_is_the_documented_permutation():
     rng = np.random.default_rng(3)
     codes = rng.integers(0, 256, size=(n, k // 2), dtype=np.uint8)
     meta = rng.standard_normal((n, k // 64, 2)).astype(np.float32)
-    tc, tm = O.tile_weights(codes, meta)
+    tc, tm = tile_weights(codes, meta)
     assert tc.shape == codes.shape and tm.shape == meta.shape
     flat, mflat = tc.reshape(-1), tm.reshape(-1, 2)
     kt = k // 64
@@ -300,8 +301,8 @@ def test_h16_weight_form_is_single_rounding_and_tiles_like_the_binary32_form():
     # within half a step of the original weight
     sc = np.repeat(m.meta[..., 1].astype(np.float64), 64, axis=1)
     assert np.all(np.abs(d - w.astype(np.float64)) <= sc / 2 + 2.0 ** -11 * np.abs(d) + 1e-12)
-    tc, tm = O.tile_weights(m.codes, m.meta)
-    tc32, tm32 = O.tile_weights(m.codes, m.meta.astype(np.float32))
+    tc, tm = tile_weights(m.codes, m.meta)
+    tc32, tm32 = tile_weights(m.codes, m.meta.astype(np.float32))
     assert tm.dtype == np.float16 and np.array_equal(tc, tc32) and np.array_equal(tm.astype(np.float32), tm32)
     x = _rand16((3, 128), 1.0, 34).astype(np.float64)
     y = O.linear(x, m, None)

@@ -25,18 +25,28 @@ def rel_l2(got, ref):
     return float(np.sqrt(((got - ref) ** 2).sum()) / (den if den > 0 else 1.0))
 
 
+# Filled while the GPU tests run and printed by conftest's terminal summary, so that a green record
+# states them: every comparison that used the scaled absolute bound, and every near-tie of greedy ids.
+SCALED_BOUND_CASES = []
+NEAR_TIES = []
+ID_COMPARISONS = [0]
+
+
 def assert_close(got, ref, what="", rel=REL_L2, mabs=MAX_ABS):
-    """The bar: relative L2 <= 2e-3 and max abs <= 1e-2.  The absolute bound is meant for O(1)
-    activations; FP16 storage alone costs |v| * 2^-11 per rounding, so for tensors whose largest
-    magnitude exceeds 4 the absolute bound scales with it (1e-2 per 4 units = 5 FP16 ulps)."""
+    """The bar: relative L2 <= 2e-3 and max abs <= 1e-2, flat, wherever the reference stays within
+    +-4.  The absolute bound is meant for O(1) activations; FP16 storage alone costs |v| * 2^-11 per
+    rounding, so for a tensor whose largest magnitude exceeds 4 the absolute bound scales with it
+    (1e-2 per 4 units = 5 FP16 ulps), and the case is recorded and listed at the end of the run."""
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
     assert got.shape == ref.shape, (what, got.shape, ref.shape)
     assert np.all(np.isfinite(got)), what + ": non-finite output"
     r = rel_l2(got, ref)
     m = float(np.abs(got - ref).max()) if got.size else 0.0
-    if ref.size:
-        mabs = mabs * max(1.0, float(np.abs(ref).max()) / 4.0)
+    top = float(np.abs(ref).max()) if ref.size else 0.0
+    if top > 4.0:
+        mabs = mabs * top / 4.0
+        SCALED_BOUND_CASES.append((what, top, m, mabs))
     assert r <= rel and m <= mabs, "%s: rel L2 %.3e (<= %.1e), max abs %.3e (<= %.1e)" % (what, r, rel, m, mabs)
     return r, m
 
@@ -75,27 +85,30 @@ def oracle_cache_dense(kv, rows):
     return k.astype(np.float64), v.astype(np.float64)
 
 
-def assert_cache_close(kv_dev, okv, seqs, rows, what=""):
-    """Compare a device cache with the oracle's after both ran the same layer.  The K/V rows that
-    were quantized differ by FP16 ulps between the two sides, and quantization turns an ulp into a
-    whole step for the few elements that sit on a rounding boundary (or moves a group's min/max by
-    an ulp).  So: every value within 1.05 steps of the oracle's, at most 3 % of the values more than
-    a tenth of a step away, and overall relative L2 within 2 %."""
-    kg, vg = cache_rows_dense(kv_dev, rows)
-    kr, vr = oracle_cache_dense(okv, rows)
-    for name, g, r, meta in (("K", kg, kr, okv.k_meta if okv.quantized else None),
-                             ("V", vg, vr, okv.v_meta if okv.quantized else None)):
-        g, r = g[seqs], r[seqs]
-        if meta is None:
-            assert_close(g, r, what + " " + name + " cache (FP16)")
-            continue
-        step = meta[seqs][:, :, :rows, :, 1].astype(np.float64).repeat(64, axis=-1).reshape(r.shape)
-        d = np.abs(g - r)
-        tol = step * 1.05 + 2e-3 * np.abs(r) + 1e-6
-        assert np.all(d <= tol), "%s %s cache: %d values off by more than one step" % (what, name, int((d > tol).sum()))
-        frac = float((d > 0.1 * step + 2e-3 * np.abs(r) + 1e-6).mean())
-        assert frac <= 0.03, "%s %s cache: %.2f %% of values moved" % (what, name, 100 * frac)
-        assert rel_l2(g, r) <= 2e-2, "%s %s cache: rel L2 %.3e" % (what, name, rel_l2(g, r))
+def assert_cache_holds_rows(kv_dev, k16, v16, b0, pos0, what=""):
+    """Strict form of the cache check: the device cache rows b0.., pos0.. must be, BIT FOR BIT, what
+    the oracle's store (Section 5 quantizer along the hidden dimension, or a plain FP16 copy) makes of
+    the FP16 K/V rows k16, v16 [nb, npos, h1] that the device itself produced.  The caller obtains
+    those rows through the library's own LayerNorm and projection calls on the layer's input (the
+    same kernels at the same shapes as inside the layer, hence the same bits) and compares THEM with
+    the oracle's K/V under the activation tolerance.  Comparing the two caches directly would measure
+    something else: an FP16 ulp of difference in a K/V value that straddles a rounding boundary
+    becomes a whole quantization step."""
+    nb, npos, h1 = k16.shape
+    nh = kv_dev.k_codes.shape[1]
+    dh = h1 // nh
+    tmp = O.KVCache.empty(nb, nh, npos, dh, kv_dev.quantized, getattr(kv_dev, "meta_f16", False))
+    tmp.store(0, 0, k16, v16)
+    sl = (slice(b0, b0 + nb), slice(None), slice(pos0, pos0 + npos))
+    if kv_dev.quantized:
+        bits = np.uint16 if tmp.meta_f16 else np.uint32
+        for name, codes, meta, rc, rm in (("K", kv_dev.k_codes, kv_dev.k_meta, tmp.k_codes, tmp.k_meta),
+                                          ("V", kv_dev.v_codes, kv_dev.v_meta, tmp.v_codes, tmp.v_meta)):
+            assert np.array_equal(host(codes[sl]), rc), "%s %s cache: codes differ" % (what, name)
+            assert np.array_equal(host(meta[sl]).view(bits), rm.view(bits)), "%s %s cache: pairs differ" % (what, name)
+    else:
+        assert np.array_equal(host(kv_dev.k_codes[sl]), tmp.k_f16), what + " K cache (FP16)"
+        assert np.array_equal(host(kv_dev.v_codes[sl]), tmp.v_f16), what + " V cache (FP16)"
 
 
 def upload_cache(kv_dev, okv):
