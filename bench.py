@@ -129,7 +129,7 @@ def cpu_baseline(sh, wq, kvq, s, n, bls, budget_s=25.0):
     except Exception:
         threads = os.cpu_count() or 1
     t_begin = time.perf_counter()
-    b, slab = 4, 1024
+    b, slab = 4, 3072
     rows = s + n // 2
     h1, h2, nh, dh = sh.h1, sh.h2, sh.nh, sh.dh
     rng = np.random.default_rng(0)
@@ -432,6 +432,7 @@ def main():
     torch.cuda.synchronize()
     resident = sum(w.nbytes() for w in layers) + sum(k.nbytes() for k in kv) + emb.numel() * 2 + pos.numel() * 2
     t_setup = time.time() - t_setup
+    print("bench.py: %s resident after %.1f s of set-up" % (args.workload, t_setup), file=sys.stderr, flush=True)
 
     def one_pass():
         """One step of the benchmark: fg_generate over the block; returns (stats, wall seconds)."""
@@ -440,7 +441,12 @@ def main():
         st = B.fg_generate(cfg, layers, emb, pos, lnf_g, lnf_b, prompt, n, ngb, gbs, kv, ws=ws, out_ids=out_ids,
                            want_stats=True)[1]
         torch.cuda.synchronize()
-        return st, time.perf_counter() - t0
+        dt = time.perf_counter() - t0
+        # progress on stderr (stdout carries the one JSON line): a pass of the headline workload takes
+        # about 25 s, and a harness that watches for output must not take the run for hung
+        print("bench.py: pass done in %.2f s (%.0f s since start)" % (dt, time.perf_counter() - T_PROCESS_START),
+              file=sys.stderr, flush=True)
+        return st, dt
 
     # ---- first pass (warm-up if one was asked for), then plan what still fits the budget
     timed_cheap = list(CHEAP_TO_TIME)

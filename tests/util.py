@@ -26,29 +26,80 @@ def rel_l2(got, ref):
 
 
 # Filled while the GPU tests run and printed by conftest's terminal summary, so that a green record
-# states them: every comparison that used the scaled absolute bound, and every near-tie of greedy ids.
-SCALED_BOUND_CASES = []
+# states them: every near-tie of greedy ids that a comparison admitted.
 NEAR_TIES = []
 ID_COMPARISONS = [0]
 
 
 def assert_close(got, ref, what="", rel=REL_L2, mabs=MAX_ABS):
-    """The bar: relative L2 <= 2e-3 and max abs <= 1e-2, flat, wherever the reference stays within
-    +-4.  The absolute bound is meant for O(1) activations; FP16 storage alone costs |v| * 2^-11 per
-    rounding, so for a tensor whose largest magnitude exceeds 4 the absolute bound scales with it
-    (1e-2 per 4 units = 5 FP16 ulps), and the case is recorded and listed at the end of the run."""
+    """The bar, flat: relative L2 <= 2e-3 and max abs <= 1e-2, whatever the magnitude of the
+    reference (the largest references of the suite, the 175B-shape projections with outputs up to
+    +-17, come within 2e-3)."""
     got = np.asarray(got, np.float64)
     ref = np.asarray(ref, np.float64)
     assert got.shape == ref.shape, (what, got.shape, ref.shape)
     assert np.all(np.isfinite(got)), what + ": non-finite output"
     r = rel_l2(got, ref)
     m = float(np.abs(got - ref).max()) if got.size else 0.0
-    top = float(np.abs(ref).max()) if ref.size else 0.0
-    if top > 4.0:
-        mabs = mabs * top / 4.0
-        SCALED_BOUND_CASES.append((what, top, m, mabs))
     assert r <= rel and m <= mabs, "%s: rel L2 %.3e (<= %.1e), max abs %.3e (<= %.1e)" % (what, r, rel, m, mabs)
     return r, m
+
+
+class nudged_kv_rows:
+    """Context manager for ORACLE-side sensitivity runs: while it is active, every FP16 K/V row that
+    an oracle cache stores is first moved by one FP16 ulp in a random tenth of its elements.  Two
+    correct implementations of the projections differ by exactly such ulps (summation order, the
+    rounding of the last bit); the stored 4-bit code of an element that sits at a rounding boundary
+    then moves by a whole quantization step.  Running the oracle twice, plain and nudged, measures how
+    far the SPECIFICATION's own outputs move under differences that are not errors; that distance,
+    not a guessed constant, is what the few comparisons that exceed the flat bar are held to."""
+
+    def __init__(self, seed=1, frac=0.1):
+        self.rng = np.random.default_rng(seed)
+        self.frac = frac
+
+    def _nudge(self, a):
+        a = np.array(a, dtype=np.float16, copy=True)
+        m = self.rng.random(a.shape) < self.frac
+        up = np.nextafter(a, np.float16(np.inf))
+        a[m] = up[m]
+        return a
+
+    def __enter__(self):
+        self.saved = [(cls, cls.store) for cls in (O.KVCache, O.PagedKVCache)]
+        for cls, orig in self.saved:
+            def store(obj, b0, pos0, k16, v16, _orig=orig):
+                return _orig(obj, b0, pos0, self._nudge(k16), self._nudge(v16))
+            cls.store = store
+        return self
+
+    def __exit__(self, *exc):
+        for cls, orig in self.saved:
+            cls.store = orig
+        return False
+
+
+BEYOND_FLAT = []   # comparisons admitted beyond the flat bar on the strength of a sensitivity run
+
+
+def assert_close_or_within_sensitivity(got, ref, alt_fn, what):
+    """The flat bar; where it is exceeded, the oracle's own output under FP16-ulp differences in the
+    freshly stored K/V rows (alt_fn() runs the oracle again inside nudged_kv_rows) decides: the device
+    may be as far from the oracle as 1.5 times the distance between the oracle's two runs, in max abs
+    and in relative L2.  Such cases are recorded and listed in the run's summary."""
+    got = np.asarray(got, np.float64)
+    ref = np.asarray(ref, np.float64)
+    assert got.shape == ref.shape and np.all(np.isfinite(got)), what
+    r = rel_l2(got, ref)
+    m = float(np.abs(got - ref).max())
+    if r <= REL_L2 and m <= MAX_ABS:
+        return
+    alt = np.asarray(alt_fn(), np.float64)
+    sr, sm = rel_l2(alt, ref), float(np.abs(alt - ref).max())
+    msg = "%s: rel L2 %.3e, max abs %.3e; the oracle itself moves by rel L2 %.3e, max abs %.3e under one-ulp K/V differences" % (
+        what, r, m, sr, sm)
+    assert r <= max(REL_L2, 1.5 * sr) and m <= max(MAX_ABS, 1.5 * sm), msg
+    BEYOND_FLAT.append(msg)
 
 
 def oracle_layer(t, quant, meta_f16=False):
@@ -85,30 +136,33 @@ def oracle_cache_dense(kv, rows):
     return k.astype(np.float64), v.astype(np.float64)
 
 
-def assert_cache_holds_rows(kv_dev, k16, v16, b0, pos0, what=""):
-    """Strict form of the cache check: the device cache rows b0.., pos0.. must be, BIT FOR BIT, what
-    the oracle's store (Section 5 quantizer along the hidden dimension, or a plain FP16 copy) makes of
-    the FP16 K/V rows k16, v16 [nb, npos, h1] that the device itself produced.  The caller obtains
-    those rows through the library's own LayerNorm and projection calls on the layer's input (the
-    same kernels at the same shapes as inside the layer, hence the same bits) and compares THEM with
-    the oracle's K/V under the activation tolerance.  Comparing the two caches directly would measure
-    something else: an FP16 ulp of difference in a K/V value that straddles a rounding boundary
-    becomes a whole quantization step."""
-    nb, npos, h1 = k16.shape
+def assert_cache_holds_rows(kv_dev, k_rows, v_rows, nb, npos, b0, pos0, what=""):
+    """Wiring check of the layer calls' cache write.  k_rows, v_rows: DEVICE FP16 tensors
+    [nb * npos, h1], the K/V rows the device computed for this call.  The cache rows b0.., pos0..
+    must hold, bit for bit, what the library's standalone quantizer (fg_quantize_groupwise, itself
+    bit-exact against the oracle on seeded inputs and on every FP16 bit pattern, tests/test_gpu_kernels.py)
+    makes of those rows, in the cache's [sequence, head, position] order; an FP16 cache holds the rows
+    themselves.  Together with the comparison of the rows against the oracle's under the activation
+    tolerance this replaces a direct cache-to-cache comparison, which would mostly measure how often an
+    FP16 ulp of difference straddles a rounding boundary (a whole quantization step each time)."""
     nh = kv_dev.k_codes.shape[1]
+    h1 = k_rows.shape[1]
     dh = h1 // nh
-    tmp = O.KVCache.empty(nb, nh, npos, dh, kv_dev.quantized, getattr(kv_dev, "meta_f16", False))
-    tmp.store(0, 0, k16, v16)
     sl = (slice(b0, b0 + nb), slice(None), slice(pos0, pos0 + npos))
-    if kv_dev.quantized:
-        bits = np.uint16 if tmp.meta_f16 else np.uint32
-        for name, codes, meta, rc, rm in (("K", kv_dev.k_codes, kv_dev.k_meta, tmp.k_codes, tmp.k_meta),
-                                          ("V", kv_dev.v_codes, kv_dev.v_meta, tmp.v_codes, tmp.v_meta)):
-            assert np.array_equal(host(codes[sl]), rc), "%s %s cache: codes differ" % (what, name)
-            assert np.array_equal(host(meta[sl]).view(bits), rm.view(bits)), "%s %s cache: pairs differ" % (what, name)
-    else:
-        assert np.array_equal(host(kv_dev.k_codes[sl]), tmp.k_f16), what + " K cache (FP16)"
-        assert np.array_equal(host(kv_dev.v_codes[sl]), tmp.v_f16), what + " V cache (FP16)"
+    for name, rows, codes_dev, meta_dev in (("K", k_rows, kv_dev.k_codes, kv_dev.k_meta),
+                                            ("V", v_rows, kv_dev.v_codes, kv_dev.v_meta)):
+        rows = rows.contiguous()
+        if kv_dev.quantized:
+            mf16 = bool(getattr(kv_dev, "meta_f16", False))
+            codes, meta = B.fg_quantize_groupwise(rows, meta_f16=mf16)
+            bits = np.uint16 if mf16 else np.uint32
+            want_c = host(codes).reshape(nb, npos, nh, dh // 2).transpose(0, 2, 1, 3)
+            want_m = host(meta).view(bits).reshape(nb, npos, nh, dh // 64, 2).transpose(0, 2, 1, 3, 4)
+            assert np.array_equal(host(codes_dev[sl]), want_c), "%s %s cache: codes differ" % (what, name)
+            assert np.array_equal(host(meta_dev[sl]).view(bits), want_m), "%s %s cache: pairs differ" % (what, name)
+        else:
+            want = host(rows).reshape(nb, npos, nh, dh).transpose(0, 2, 1, 3)
+            assert np.array_equal(host(codes_dev[sl]), want), "%s %s cache (FP16)" % (what, name)
 
 
 def upload_cache(kv_dev, okv):
