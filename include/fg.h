@@ -205,6 +205,20 @@ int fg_linear(const fg_mat* w, const void* bias_f16, const void* x_f16, int64_t 
               void* stream);
 size_t fg_linear_workspace_bytes(const fg_mat* w, int64_t m);
 
+/* fg_linear for callers that cannot allocate device memory or pass a workspace along: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same kernels
+ * and bit-identical results as fg_linear, but the partial sums live in an array of
+ * fg_linear_static_scratch_bytes() = 80 MiB of device memory that the library itself owns (one copy
+ * per GPU, held from the loading of the library until the process ends).  The call allocates and frees
+ * nothing.  A call whose fg_linear_workspace_bytes(w, m) exceeds that size returns FG_ERR_WORKSPACE and
+ * launches nothing: every projection of up to 320 rows fits (the decode phase), the 256-row-tile
+ * prefill shape does not.  All calls on one GPU share the one array: calls that may overlap in time
+ * on one GPU (different streams, different threads) race on it and must be serialised by the caller;
+ * calls in one stream are ordered and safe. */
+int fg_linear_static(const fg_mat* w, const void* bias_f16, const void* x_f16, int64_t m,
+                     const void* residual_f16, int relu, void* out_f16, void* stream);
+size_t fg_linear_static_scratch_bytes(void);
+
 /* Store K and V token rows into a layer's cache (Section 3 "Concat", Section 5 storage):
  * k, v are FP16 [b, s, h1] views whose consecutive rows are row_stride elements apart
  * (so they may be column slices of a [b*s, 3*h1] QKV buffer).  Rows land at cache rows

@@ -75,6 +75,9 @@ EXPORTS = {
     "fg_linear": (C.c_int, [C.POINTER(fg_mat), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_void_p,
                             C.c_void_p, C.c_size_t, C.c_void_p]),
     "fg_linear_workspace_bytes": (C.c_size_t, [C.POINTER(fg_mat), C.c_int64]),
+    "fg_linear_static": (C.c_int, [C.POINTER(fg_mat), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_void_p,
+                                   C.c_void_p]),
+    "fg_linear_static_scratch_bytes": (C.c_size_t, []),
     "fg_kv_append": (C.c_int, [C.POINTER(fg_model_cfg), C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
                                C.POINTER(fg_kv_cache), C.c_int32, C.c_int32, C.c_void_p]),
     "fg_decode_attention": (C.c_int, [C.POINTER(fg_model_cfg), C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
@@ -348,6 +351,15 @@ def fg_linear(w: Mat, bias: Optional[torch.Tensor], x: torch.Tensor, residual: O
     ws = _ws(nws)
     _check(lib().fg_linear(C.byref(w.c), _p(bias), _p(x), m, _p(residual), int(relu), _p(out), _p(ws), nws,
                            _stream()), "fg_linear")
+    return out
+
+
+def fg_linear_static(w: Mat, bias: Optional[torch.Tensor], x: torch.Tensor, residual: Optional[torch.Tensor],
+                     relu: bool, out: torch.Tensor) -> torch.Tensor:
+    """fg_linear on the library's own scratch array: the caller passes inputs and the output, nothing
+    is allocated here or in the library."""
+    _check(lib().fg_linear_static(C.byref(w.c), _p(bias), _p(x), x.shape[0], _p(residual), int(relu), _p(out),
+                                  _stream()), "fg_linear_static")
     return out
 
 

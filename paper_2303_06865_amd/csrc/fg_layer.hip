@@ -410,6 +410,60 @@ extern "C" int fg_linear(const fg_mat* w, const void* bias_f16, const void* x_f1
                        ws, ws_bytes, as_stream(stream));
 }
 
+// ---------------------------------------------------------------- fg_linear without a workspace argument
+// For callers that can neither allocate device memory nor carry a workspace through their call chain
+// (code under HIP graph capture, tight serving loops): the partial sums of the split contraction go
+// to a fixed array in device memory that belongs to the library.  Every GPU the library runs on holds
+// its own copy of the array, at its own address, from the moment the code object is loaded until the
+// process ends.
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)80 << 20;   // the decode-shape projections (up to 320 rows) need at most this
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, looked up once per device
+bool g_scratch_known[kMaxDevices];
+
+// In host code the array's name is only a handle for the runtime, not a device address: the address is
+// asked for once per device, with that device current, and that is what the kernels are given.
+int static_scratch(void** ptr) {
+  int dev = -1;
+  FG_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return FG_ERR_UNSUPPORTED;
+  if (!g_scratch_known[dev]) {
+    void* p = nullptr;
+    FG_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return FG_ERR_DEVICE;
+    g_scratch_ptr[dev] = p;
+    g_scratch_known[dev] = true;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return FG_OK;
+}
+}  // namespace
+
+extern "C" size_t fg_linear_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" int fg_linear_static(const fg_mat* w, const void* bias_f16, const void* x_f16, int64_t m,
+                                const void* residual_f16, int relu, void* out_f16, void* stream) {
+  if (!w) return FG_ERR_NULL;
+  int rc = check_mat(w);
+  if (rc) return rc;
+  if (m < 0 || m > 0x7fffffff) return FG_ERR_SHAPE;
+  if (m == 0) return FG_OK;
+  if (!x_f16 || !out_f16) return FG_ERR_NULL;
+  if (!aligned16(x_f16) || !aligned16(out_f16)) return FG_ERR_SHAPE;
+  const size_t need = linear_workspace_bytes(w->dtype, w->rows, w->cols, m);
+  if (need > kStaticScratchBytes) return FG_ERR_WORKSPACE;   // beyond what the library's own scratch array holds
+  void* ws = nullptr;
+  if ((rc = static_scratch(&ws))) return rc;
+  // Nothing in the scratch has to start at zero: every partial-sum slot that the reduction pass reads
+  // was written by the contraction kernel of the same call.
+  return linear_launch(make_linear(*w, bias_f16, reinterpret_cast<const half_t*>(x_f16), w->cols, m,
+                                   reinterpret_cast<const half_t*>(residual_f16), w->rows, relu,
+                                   reinterpret_cast<half_t*>(out_f16), w->rows),
+                       ws, kStaticScratchBytes, as_stream(stream));
+}
+
 extern "C" size_t fg_lm_head_workspace_bytes(const fg_model_cfg* cfg, int64_t rows) {
   if (!cfg || rows <= 0 || check_cfg(cfg)) return 0;
   return carve_head_ws(*cfg, rows, nullptr).total;
