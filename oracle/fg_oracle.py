@@ -398,11 +398,14 @@ def prefill_layer(cfg: ModelCfg, w: LayerWeights, x16: np.ndarray, kv: KVCache,
 
 
 def decode_layer(cfg: ModelCfg, w: LayerWeights, x16: np.ndarray, t: int, kv: KVCache,
-                 batch_offset: int = 0) -> np.ndarray:
+                 batch_offset: int = 0, topk: int = 0) -> np.ndarray:
     """Decode phase of one layer (Section 3).  x16 [b, h1] FP16 is the current
     token's activation; t rows are already cached.  The new K/V row is appended
     at row t in the storage format, then the query attends to rows 0..t as read
-    back from the cache (so it sees its own row dequantized)."""
+    back from the cache (so it sees its own row dequantized).
+
+    topk > 0: the attention is the sparse one of Section 5 (attn_decode_topk): of the t + 1 rows only
+    the min(topk, t + 1) with the largest attention weights contribute their V rows."""
     b, h1 = x16.shape
     nh, dh = cfg.nh, cfg.dh
     x = x16.astype(np.float64)
@@ -416,7 +419,10 @@ def decode_layer(cfg: ModelCfg, w: LayerWeights, x16: np.ndarray, t: int, kv: KV
     for bi in range(b):
         for h in range(nh):
             kh, vh = kv.load(batch_offset + bi, h, t + 1)
-            o[bi, h] = attn_decode(q[bi, h], kh, vh)
+            if topk > 0 and topk < t + 1:
+                o[bi, h] = attn_decode_topk(q[bi, h], kh, vh, topk)[0]
+            else:
+                o[bi, h] = attn_decode(q[bi, h], kh, vh)
     o = round_f16(o.reshape(b, h1))
     return _ffn_and_residual(cfg, w, o, x).astype(np.float16)
 
@@ -509,15 +515,23 @@ class PagedKVCache:
     n_pages: int
     table: np.ndarray                      # int32 [n_seqs, max_pages_per_seq]; -1 = no page
     meta_f16: bool = False
+    quantized: bool = True                 # False: the pages hold plain FP16 rows [n_pages, nh, 64, dh]
     k_codes: np.ndarray = field(default=None)
     k_meta: np.ndarray = field(default=None)
     v_codes: np.ndarray = field(default=None)
     v_meta: np.ndarray = field(default=None)
+    k_f16: np.ndarray = field(default=None)
+    v_f16: np.ndarray = field(default=None)
 
     @staticmethod
-    def empty(nh: int, dh: int, n_pages: int, table: np.ndarray, meta_f16: bool = False) -> "PagedKVCache":
+    def empty(nh: int, dh: int, n_pages: int, table: np.ndarray, meta_f16: bool = False,
+              quantized: bool = True) -> "PagedKVCache":
         assert dh % GROUP == 0
-        c = PagedKVCache(nh, dh, n_pages, np.asarray(table, np.int32), meta_f16)
+        c = PagedKVCache(nh, dh, n_pages, np.asarray(table, np.int32), meta_f16 and quantized, quantized)
+        if not quantized:
+            c.k_f16 = np.zeros((n_pages, nh, PAGE_ROWS, dh), np.float16)
+            c.v_f16 = np.zeros((n_pages, nh, PAGE_ROWS, dh), np.float16)
+            return c
         mt = np.float16 if meta_f16 else np.float32
         c.k_codes = np.zeros((n_pages, nh, PAGE_ROWS, dh // 2), np.uint8)
         c.v_codes = np.zeros((n_pages, nh, PAGE_ROWS, dh // 2), np.uint8)
@@ -532,9 +546,18 @@ class PagedKVCache:
 
     def store(self, b0: int, pos0: int, k16: np.ndarray, v16: np.ndarray) -> None:
         """FP16 K/V rows [nb, npos, h1] of sequences b0.. at positions pos0..: each token row is
-        quantized along its hidden dimension and written row by row through the page table."""
+        quantized along its hidden dimension (or kept as FP16) and written row by row through the
+        page table."""
         nb, npos, h1 = k16.shape
         assert h1 == self.nh * self.dh
+        if not self.quantized:
+            for name, x16 in (("k", k16), ("v", v16)):
+                x = np.ascontiguousarray(x16, np.float16).reshape(nb, npos, self.nh, self.dh)
+                for i in range(nb):
+                    for p in range(npos):
+                        page, r = self._where(b0 + i, pos0 + p)
+                        getattr(self, name + "_f16")[page, :, r] = x[i, p]
+            return
         quant = quantize_groupwise_h16 if self.meta_f16 else quantize_groupwise
         for name, x16 in (("k", k16), ("v", v16)):
             codes, meta = quant(np.ascontiguousarray(x16, np.float16).reshape(nb * npos, h1))
@@ -551,6 +574,13 @@ class PagedKVCache:
         page table, converted back from the stored format."""
         out = []
         for name in ("k", "v"):
+            if not self.quantized:
+                x = np.empty((rows, self.dh), np.float16)
+                for p in range(rows):
+                    page, r = self._where(b, p)
+                    x[p] = getattr(self, name + "_f16")[page, head, r]
+                out.append(x.astype(np.float64))
+                continue
             codes = np.empty((rows, self.dh // 2), np.uint8)
             meta = np.empty((rows, self.dh // GROUP, 2), self.k_meta.dtype)
             for p in range(rows):
@@ -561,14 +591,15 @@ class PagedKVCache:
         return out[0], out[1]
 
 
-def decode_layer_ragged(cfg: ModelCfg, w: LayerWeights, x16: np.ndarray, seq_ids, pos, kv) -> np.ndarray:
+def decode_layer_ragged(cfg: ModelCfg, w: LayerWeights, x16: np.ndarray, seq_ids, pos, kv, topk: int = 0) -> np.ndarray:
     """A decode step in which row i belongs to sequence seq_ids[i] and sits at its own position pos[i]
     (pos[i] rows already cached), as in the diagonal block schedule, where the GPU batches of a block
     are at different token steps.  Section 3 treats every sequence on its own, so this is decode_layer
-    applied to each row with its own t.  kv: a KVCache or a PagedKVCache.  x16 [b, h1] FP16."""
+    applied to each row with its own t (and, with topk > 0, its own min(topk, t + 1) kept rows).
+    kv: a KVCache or a PagedKVCache.  x16 [b, h1] FP16."""
     out = np.empty_like(np.asarray(x16, np.float16))
     for i in range(out.shape[0]):
-        out[i] = decode_layer(cfg, w, x16[i:i + 1], int(pos[i]), kv, batch_offset=int(seq_ids[i]))[0]
+        out[i] = decode_layer(cfg, w, x16[i:i + 1], int(pos[i]), kv, batch_offset=int(seq_ids[i]), topk=topk)[0]
     return out
 
 

@@ -427,6 +427,28 @@ __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
 
 }  // namespace
 
+// Waves per (sequence, head): 1, 2 or 4.  A stream of c chunks costs a wave ceil(c / WPH) chunk times plus
+// about half a chunk time of set-up and reduction, so one wave per head wastes the least; but the chip
+// holds 768 workgroups of four waves at once, and a launch of fewer than four such rounds runs in
+// whole rounds: 1024 workgroups take as long as 1536.  The cheapest of the three under that model.
+static int pick_waves_per_head(int64_t heads, int rows, int rows_per_chunk) {
+  const int64_t slots = 256 * 3;
+  const int chunks = (rows + rows_per_chunk - 1) / rows_per_chunk;
+  int best = 1;
+  double best_cost = 0.0;
+  for (int wph = 1; wph <= 4; wph *= 2) {
+    const double wgs = (double)ceil_div(heads * wph, 4);
+    double rounds = wgs / slots;
+    if (rounds < 4.0) rounds = (double)ceil_div((int64_t)wgs, slots);
+    const double cost = rounds * ((chunks + wph - 1) / wph + 0.5 + (wph > 1 ? 0.25 : 0.0));
+    if (wph == 1 || cost < best_cost) {
+      best = wph;
+      best_cost = cost;
+    }
+  }
+  return best;
+}
+
 int decode_attention_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_stride, int32_t b,
                             int32_t rows, const fg_kv_cache& kv, int32_t batch_offset, half_t* out,
                             hipStream_t stream) {
@@ -448,13 +470,11 @@ int decode_attention_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_
   a.n_heads = b * cfg.nh;
   a.page_table = a.seq_ids = a.seq_rows = nullptr;
   a.table_stride = a.n_seqs = a.n_pages = a.rows_bias = 0;
-  // Waves per head: one wave per head wastes the least (a stream of c chunks costs ceil(c / WPH) chunk
-  // times), but the chip wants at least ~8 waves on each of its 256 CUs.
   const int64_t heads = (int64_t)b * cfg.nh;
-  const int wph = heads >= 2048 ? 1 : (heads >= 1024 ? 2 : 4);
-  const dim3 grid((unsigned)ceil_div(heads * wph, 4));
   const bool q4 = kv.dtype == FG_Q4G64 || kv.dtype == FG_Q4G64_H16;
   const bool h16 = kv.dtype == FG_Q4G64_H16;
+  const int wph = pick_waves_per_head(heads, rows, q4 ? 8192 / dh : 64);
+  const dim3 grid((unsigned)ceil_div(heads * wph, 4));
   ProfScope prof(FG_K_ATTN_DECODE, stream);
 #define FG_ATTN_LAUNCH(DH_, ...)                                                                      \
   do {                                                                                                \

@@ -59,6 +59,65 @@ def test_paged_cache_is_a_relocation_of_the_contiguous_cache(meta_f16):
         paged.load(1, 0, 65)                      # sequence 1 has no second page
 
 
+def test_fp16_pages_are_a_relocation_of_the_contiguous_fp16_cache():
+    """Unquantized pages: the rows come back bit for bit, and land where the page layout says."""
+    nh, dh, h1 = 2, 64, 128
+    lens = [70, 3, 64]
+    table = np.array([[3, 0], [4, -1], [1, -1]], np.int32)
+    paged = O.PagedKVCache.empty(nh, dh, 5, table, quantized=False)
+    flat = O.KVCache.empty(3, nh, 80, dh, False)
+    for q, ln in enumerate(lens):
+        k, v = _rows16((1, ln, h1), 1.0, 60 + q), _rows16((1, ln, h1), 0.5, 70 + q)
+        paged.store(q, 0, k, v)
+        flat.store(q, 0, k, v)
+        for h in range(nh):
+            kp, vp = paged.load(q, h, ln)
+            assert np.array_equal(kp, k[0, :, h * dh:(h + 1) * dh].astype(np.float64))
+            assert np.array_equal(vp, flat.load(q, h, ln)[1])
+    assert np.array_equal(paged.k_f16[0, 1, 5], flat.k_f16[0, 1, 69])      # position 69 = row 5 of its second page
+    assert not paged.k_f16[2].any() and not paged.v_f16[4, :, 3:].any()   # page 2 is nobody's; rows past the end
+
+
+def test_decode_layer_with_topk_is_the_layer_around_sparse_attention():
+    """decode_layer(topk=k) must be the dense layer with the attention of every (sequence, head)
+    replaced by Section 5's sparse form.  Checked without the oracle's own top-k routine: the kept rows
+    are found by a plain Python sort of (score descending, row ascending), the layer around it is
+    re-assembled from the pinned pieces; and topk >= rows is the dense layer itself."""
+    sh, cfg, layers, _ = _tiny_model(l=1)
+    w = layers[0]
+    b, t, k_keep = 2, 37, 5
+    kv = O.KVCache.empty(b, sh.nh, t + 1, sh.dh, True)
+    kv.store(0, 0, _rows16((b, t, sh.h1), 1.0, 80), _rows16((b, t, sh.h1), 1.0, 81))
+    import copy
+    kv_dense, kv_all = copy.deepcopy(kv), copy.deepcopy(kv)
+    x = _rows16((b, sh.h1), 0.5, 82)
+    got = O.decode_layer(cfg, w, x, t, kv, topk=k_keep)
+    dense = O.decode_layer(cfg, w, x, t, kv_dense)
+    assert np.array_equal(O.decode_layer(cfg, w, x, t, kv_all, topk=t + 1), dense)
+    assert not np.array_equal(got, dense)
+    assert np.array_equal(kv.k_codes, kv_dense.k_codes)                    # the cache write does not depend on topk
+    # by hand
+    y = O.round_f16(O.layernorm(x.astype(np.float64), w.ln1_g, w.ln1_b, cfg.ln_eps))
+    qkv = O.round_f16(O.linear(y, w.wqkv, w.bqkv))
+    o = np.zeros((b, sh.nh, sh.dh))
+    for bi in range(b):
+        for h in range(sh.nh):
+            kh, vh = kv.load(bi, h, t + 1)
+            q = qkv[bi, h * sh.dh:(h + 1) * sh.dh]
+            sc = [float(sum(q[d] * kh[j, d] for d in range(sh.dh))) / np.sqrt(sh.dh) for j in range(t + 1)]
+            keep = sorted(sorted(range(t + 1), key=lambda j: (-sc[j], j))[:k_keep])
+            mx = max(sc)
+            den = sum(np.exp(v - mx) for v in sc)                          # the FULL softmax denominator
+            for j in keep:
+                o[bi, h] += np.exp(sc[j] - mx) / den * vh[j]
+    o = O.round_f16(o.reshape(b, sh.h1))
+    x1 = O.round_f16(O.linear(o, w.wo, w.bo) + x.astype(np.float64))
+    y2 = O.round_f16(O.layernorm(x1, w.ln2_g, w.ln2_b, cfg.ln_eps))
+    a = O.round_f16(np.maximum(O.linear(y2, w.w1, w.b1), 0.0))
+    ref = O.round_f16(O.linear(a, w.w2, w.b2) + x1).astype(np.float16)
+    assert np.array_equal(got, ref)
+
+
 def _tiny_model(l=2, seed=0, max_pos=96):
     sh = synth.Shape(h1=128, nh=2, h2=256, vocab=211, max_pos=max_pos, l=l)
     cfg = O.ModelCfg(sh.h1, sh.nh, sh.h2, sh.vocab, sh.max_pos)
