@@ -116,12 +116,13 @@ typedef struct {
  * sequence).  A pool of n_pages pages; a page holds FG_PAGE_ROWS = 64 consecutive positions of ONE
  * sequence for all heads:
  *   k_codes/v_codes [n_pages][nh][64][dh/2] bytes, k_meta/v_meta [n_pages][nh][64][dh/64] pairs
- * (8-byte pairs for FG_Q4G64, 4-byte FP16 pairs for FG_Q4G64_H16; FG_F16 is not supported in pages).
- * Rows are quantized exactly as in fg_kv_cache; only their place differs. */
+ * (8-byte pairs for FG_Q4G64, 4-byte FP16 pairs for FG_Q4G64_H16).  FG_F16 pages hold plain FP16 rows,
+ * k_codes/v_codes [n_pages][nh][64][dh] halves, metas NULL.
+ * Rows are stored exactly as in fg_kv_cache; only their place differs. */
 #define FG_PAGE_ROWS 64
 typedef struct {
   void *k_codes, *k_meta, *v_codes, *v_meta; /* device */
-  int32_t dtype;                             /* FG_Q4G64 or FG_Q4G64_H16 */
+  int32_t dtype;                             /* FG_Q4G64, FG_Q4G64_H16 or FG_F16 */
   int32_t n_pages;
 } fg_kv_pages;
 
@@ -276,10 +277,13 @@ int fg_prefill_layer(const fg_model_cfg* cfg, const fg_layer_weights* wts, const
 /* Decode: x_in [b, h1] FP16 is the current token; t rows are already cached (0 <= t < cap).
  * Appends the new K/V row at row t in the storage format, attends to rows 0..t read back from
  * the cache, then output projection, residual, MLP, residual.  x_out [b, h1] may alias x_in.
+ * topk = 0: dense attention.  topk > 0: the sparse attention of Section 5 as in
+ * fg_decode_attention_topk, keeping min(topk, t + 1) rows of V per head (4-bit caches only:
+ * FG_ERR_UNSUPPORTED otherwise, and where the scores of one head no longer fit on chip).
  * ws >= fg_layer_workspace_bytes(cfg, wts, b). */
 int fg_decode_layer(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in, int32_t b,
-                    int32_t t, const fg_kv_cache* kv, int32_t batch_offset, void* x_out, void* ws,
-                    size_t ws_bytes, void* stream);
+                    int32_t t, int32_t topk, const fg_kv_cache* kv, int32_t batch_offset, void* x_out,
+                    void* ws, size_t ws_bytes, void* stream);
 size_t fg_layer_workspace_bytes(const fg_model_cfg* cfg, const fg_layer_weights* wts, int64_t rows);
 
 /* ---- Sections 3-4: generation of a block -----------------------------------------------
@@ -313,11 +317,19 @@ int fg_decode_attention_paged(const fg_model_cfg* cfg, const void* q_f16, int64_
                               const fg_kv_pages* pages, const fg_ragged* seqs, int32_t rows_bias,
                               void* out_f16, void* stream);
 
+/* Top-K sparse attention (Section 5) over a paged cache with a length per sequence: as
+ * fg_decode_attention_paged, but row i keeps only its min(topk, rows of row i) highest-weighted rows of
+ * V.  kept_rows (device int32 [b, nh, topk] or NULL) receives the kept positions in ascending order,
+ * padded with -1.  4-bit pages only; 64 * table_stride (rounded up to 128) + topk may not exceed 36864. */
+int fg_decode_attention_topk_paged(const fg_model_cfg* cfg, const void* q_f16, int64_t q_row_stride, int32_t b,
+                                   int32_t topk, const fg_kv_pages* pages, const fg_ragged* seqs,
+                                   int32_t rows_bias, void* out_f16, int32_t* kept_rows, void* stream);
+
 /* fg_decode_layer for rows at different steps over a paged cache: row i belongs to sequence
- * seq_ids[i], appends its K/V row at position pos[i] and attends positions 0 .. pos[i].
- * ws >= fg_layer_workspace_bytes(cfg, wts, b). */
+ * seq_ids[i], appends its K/V row at position pos[i] and attends positions 0 .. pos[i]; topk as in
+ * fg_decode_layer, per row.  ws >= fg_layer_workspace_bytes(cfg, wts, b). */
 int fg_decode_layer_paged(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in, int32_t b,
-                          const fg_kv_pages* pages, const fg_ragged* seqs, void* x_out, void* ws,
+                          int32_t topk, const fg_kv_pages* pages, const fg_ragged* seqs, void* x_out, void* ws,
                           size_t ws_bytes, void* stream);
 
 /* fg_prefill_layer storing the s K/V rows of sequence seq_ids[i] at positions 0 .. s-1 of its pages

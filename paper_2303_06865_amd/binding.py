@@ -97,7 +97,7 @@ EXPORTS = {
                                    C.c_int32, C.POINTER(fg_kv_cache), C.c_int32, C.c_void_p, C.c_void_p,
                                    C.c_size_t, C.c_void_p]),
     "fg_decode_layer": (C.c_int, [C.POINTER(fg_model_cfg), C.POINTER(fg_layer_weights), C.c_void_p, C.c_int32,
-                                  C.c_int32, C.POINTER(fg_kv_cache), C.c_int32, C.c_void_p, C.c_void_p,
+                                  C.c_int32, C.c_int32, C.POINTER(fg_kv_cache), C.c_int32, C.c_void_p, C.c_void_p,
                                   C.c_size_t, C.c_void_p]),
     "fg_layer_workspace_bytes": (C.c_size_t, [C.POINTER(fg_model_cfg), C.POINTER(fg_layer_weights), C.c_int64]),
     "fg_generate": (C.c_int, [C.POINTER(fg_model_cfg), C.c_int32, C.POINTER(fg_layer_weights), C.c_void_p,
@@ -112,8 +112,11 @@ EXPORTS = {
                                             C.POINTER(fg_kv_pages), C.POINTER(fg_ragged), C.c_int32, C.c_void_p,
                                             C.c_void_p]),
     "fg_decode_layer_paged": (C.c_int, [C.POINTER(fg_model_cfg), C.POINTER(fg_layer_weights), C.c_void_p, C.c_int32,
-                                        C.POINTER(fg_kv_pages), C.POINTER(fg_ragged), C.c_void_p, C.c_void_p,
+                                        C.c_int32, C.POINTER(fg_kv_pages), C.POINTER(fg_ragged), C.c_void_p, C.c_void_p,
                                         C.c_size_t, C.c_void_p]),
+    "fg_decode_attention_topk_paged": (C.c_int, [C.POINTER(fg_model_cfg), C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
+                                                 C.POINTER(fg_kv_pages), C.POINTER(fg_ragged), C.c_int32, C.c_void_p,
+                                                 C.c_void_p, C.c_void_p]),
     "fg_prefill_layer_paged": (C.c_int, [C.POINTER(fg_model_cfg), C.POINTER(fg_layer_weights), C.c_void_p, C.c_int32,
                                          C.c_int32, C.POINTER(fg_kv_pages), C.POINTER(fg_ragged), C.c_void_p,
                                          C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -277,10 +280,18 @@ class KVPages:
     """One layer's 4-bit cache as a pool of pages of 64 positions: [n_pages, nh, 64, dh/2] codes and
     [n_pages, nh, 64, dh/64, 2] {min, scale} pairs (binary32, or FP16 with meta_f16)."""
 
-    def __init__(self, cfg: Cfg, n_pages: int, meta_f16: bool = False, device="cuda", zero: bool = True):
-        self.n_pages, self.meta_f16 = n_pages, bool(meta_f16)
+    def __init__(self, cfg: Cfg, n_pages: int, meta_f16: bool = False, device="cuda", zero: bool = True,
+                 quantized: bool = True):
+        """quantized = False: the pages hold plain FP16 rows [n_pages, nh, 64, dh] (FG_F16)."""
+        self.n_pages, self.meta_f16, self.quantized = n_pages, bool(meta_f16 and quantized), quantized
         mk = torch.zeros if zero else torch.empty
         nh, dh = cfg.nh, cfg.dh
+        if not quantized:
+            self.k_codes = mk((n_pages, nh, PAGE_ROWS, dh), dtype=torch.float16, device=device)
+            self.v_codes = mk((n_pages, nh, PAGE_ROWS, dh), dtype=torch.float16, device=device)
+            self.k_meta = self.v_meta = None
+            self.c = fg_kv_pages(_p(self.k_codes), None, _p(self.v_codes), None, FG_F16, n_pages)
+            return
         mt = torch.float16 if meta_f16 else torch.float32
         self.k_codes = mk((n_pages, nh, PAGE_ROWS, dh // 2), dtype=torch.uint8, device=device)
         self.v_codes = mk((n_pages, nh, PAGE_ROWS, dh // 2), dtype=torch.uint8, device=device)
@@ -290,7 +301,8 @@ class KVPages:
                              FG_Q4G64_H16 if meta_f16 else FG_Q4G64, n_pages)
 
     def nbytes(self) -> int:
-        return 2 * (self.k_codes.numel() + self.k_meta.numel() * self.k_meta.element_size())
+        n = 2 * self.k_codes.numel() * self.k_codes.element_size()
+        return n if self.k_meta is None else n + 2 * self.k_meta.numel() * self.k_meta.element_size()
 
 
 class Ragged:
@@ -429,14 +441,14 @@ def fg_prefill_layer(cfg: Cfg, w: LayerWeights, x: torch.Tensor, kv: KVCache, ba
 
 
 def fg_decode_layer(cfg: Cfg, w: LayerWeights, x: torch.Tensor, t: int, kv: KVCache, batch_offset: int = 0,
-                    ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                    ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None, topk: int = 0) -> torch.Tensor:
     x = _f16(x)
     b = x.shape[0]
     if out is None:
         out = torch.empty_like(x)
     if ws is None:
         ws = _ws(lib().fg_layer_workspace_bytes(C.byref(cfg.c), C.byref(w.c), b))
-    _check(lib().fg_decode_layer(C.byref(cfg.c), C.byref(w.c), _p(x), b, t, C.byref(kv.c), batch_offset, _p(out),
+    _check(lib().fg_decode_layer(C.byref(cfg.c), C.byref(w.c), _p(x), b, t, topk, C.byref(kv.c), batch_offset, _p(out),
                                  _p(ws), ws.numel(), _stream()), "fg_decode_layer")
     return out
 
@@ -455,15 +467,27 @@ def fg_decode_attention_paged(cfg: Cfg, q: torch.Tensor, q_row_stride: int, b: i
     return out
 
 
+def fg_decode_attention_topk_paged(cfg: Cfg, q: torch.Tensor, q_row_stride: int, b: int, topk: int, pages: KVPages,
+                                   seqs: Ragged, rows_bias: int = 0, want_rows: bool = False):
+    """Returns out [b, h1] (and the kept positions int32 [b, nh, topk], -1 padded, if want_rows)."""
+    out = torch.empty((b, cfg.h1), dtype=torch.float16, device=q.device)
+    kept = torch.empty((b, cfg.nh, topk), dtype=torch.int32, device=q.device) if want_rows else None
+    _check(lib().fg_decode_attention_topk_paged(C.byref(cfg.c), _p(q), q_row_stride, b, topk, C.byref(pages.c),
+                                                C.byref(seqs.c), rows_bias, _p(out), _p(kept), _stream()),
+           "fg_decode_attention_topk_paged")
+    return (out, kept) if want_rows else out
+
+
 def fg_decode_layer_paged(cfg: Cfg, w: LayerWeights, x: torch.Tensor, pages: KVPages, seqs: Ragged,
-                          ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+                          ws: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                          topk: int = 0) -> torch.Tensor:
     x = _f16(x)
     b = x.shape[0]
     if out is None:
         out = torch.empty_like(x)
     if ws is None:
         ws = _ws(lib().fg_layer_workspace_bytes(C.byref(cfg.c), C.byref(w.c), b))
-    _check(lib().fg_decode_layer_paged(C.byref(cfg.c), C.byref(w.c), _p(x), b, C.byref(pages.c), C.byref(seqs.c),
+    _check(lib().fg_decode_layer_paged(C.byref(cfg.c), C.byref(w.c), _p(x), b, topk, C.byref(pages.c), C.byref(seqs.c),
                                        _p(out), _p(ws), ws.numel(), _stream()), "fg_decode_layer_paged")
     return out
 

@@ -303,7 +303,9 @@ __global__ __launch_bounds__(256, 3) void attn_decode_q4_kernel(AttnArgs a) {
 
 // FP16 cache: the same streaming structure without the unpacking.  K rows are the B operand
 // directly (lane = row, 8 consecutive head dimensions per lane).
-template <int DH, int WPH>
+// PAGED: a chunk of 64 rows is exactly one page of the sequence (FG_PAGE_ROWS = 64), found through the
+// page table; every sequence has its own length.
+template <int DH, int WPH, bool PAGED = false>
 __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
   constexpr int NU = DH / 32;        // 32-wide head-dimension blocks
   constexpr int HPB = 4 / WPH;       // heads per workgroup
@@ -319,10 +321,30 @@ __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
   const int hid = hl < heads_valid ? hid0 + hl : hid0;
   const int seq = hid / a.nh, head = hid - seq * a.nh;
   const int r = lane & 15, q4 = lane >> 4;
-  const int64_t hrow = ((int64_t)(a.batch_offset + seq) * a.nh + head) * a.cap;
+  const int64_t hrow = PAGED ? 0 : ((int64_t)(a.batch_offset + seq) * a.nh + head) * a.cap;
   const half_t* kp = reinterpret_cast<const half_t*>(a.k_codes) + hrow * DH;
   const half_t* vp = reinterpret_cast<const half_t*>(a.v_codes) + hrow * DH;
-  const int n_chunks = (a.rows + 63) >> 6;
+  int n_rows = a.rows;
+  const int32_t* tbl = nullptr;
+  if constexpr (PAGED) {
+    int sid = a.seq_ids ? a.seq_ids[seq] : seq;
+    sid = sid < 0 ? 0 : (sid >= a.n_seqs ? a.n_seqs - 1 : sid);
+    tbl = a.page_table + (int64_t)sid * a.table_stride;
+    n_rows = a.seq_rows[seq] + a.rows_bias;
+    n_rows = n_rows < 0 ? 0 : n_rows;
+    n_rows = n_rows > a.table_stride * FG_PAGE_ROWS ? a.table_stride * FG_PAGE_ROWS : n_rows;
+  }
+  const int n_chunks = (n_rows + 63) >> 6;
+  // first cache row (in rows of DH elements) of chunk c of this head's stream
+  auto chunk_row0 = [&](int c) -> int64_t {
+    if constexpr (!PAGED) {
+      return (int64_t)c << 6;
+    } else {
+      int pg = tbl[c];                                             // c < n_chunks <= table_stride
+      pg = pg < 0 ? 0 : (pg >= a.n_pages ? a.n_pages - 1 : pg);   // a bad entry reads some page of the pool
+      return ((int64_t)pg * a.nh + head) * FG_PAGE_ROWS;
+    }
+  };
 
   half_t* my_q = sm_q + hl * DH;
   if (part == 0 && lane < DH / 8)
@@ -351,18 +373,20 @@ __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
 
   for (int chunk = part; chunk < n_chunks; chunk += WPH) {
     const int rbase = chunk << 6;
+    const int64_t crow0 = chunk_row0(chunk);
+    const int last = n_rows - 1 - rbase;   // rows of the chunk past the end re-read its last valid row
     f4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      int row = rbase + 16 * i + r;
-      row = row < a.rows ? row : a.rows - 1;
+      int row = 16 * i + r;
+      row = row < last ? row : last;
 #pragma unroll
       for (int u = 0; u < NU; ++u) {
-        const h8_t kv = *reinterpret_cast<const h8_t*>(kp + (int64_t)row * DH + 32 * u + 8 * q4);
+        const h8_t kv = *reinterpret_cast<const h8_t*>(kp + (crow0 + row) * DH + 32 * u + 8 * q4);
         acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qop[i][u], kv, acc, 0, 0, 0);
       }
     }
-    const float sc = (rbase + lane) < a.rows ? acc[0] * a.scale : -INFINITY;
+    const float sc = (rbase + lane) < n_rows ? acc[0] * a.scale : -INFINITY;
     const float cmax = wave_max(sc);
     const float m_new = fmaxf(m_run, cmax);
     if (m_new > m_run) {
@@ -376,12 +400,12 @@ __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
     l_run += p;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      int row = rbase + 16 * i + r;
-      row = row < a.rows ? row : a.rows - 1;
+      int row = 16 * i + r;
+      row = row < last ? row : last;
       const float w = __shfl(p, 16 * i + r, 64);
 #pragma unroll
       for (int u = 0; u < NU; ++u) {
-        const h8_t vv = *reinterpret_cast<const h8_t*>(vp + (int64_t)row * DH + 32 * u + 8 * q4);
+        const h8_t vv = *reinterpret_cast<const h8_t*>(vp + (crow0 + row) * DH + 32 * u + 8 * q4);
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[8 * u + e] += w * (float)vv[e];
       }
@@ -401,7 +425,7 @@ __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
   half_t* out0 = a.out + (int64_t)hid0 * DH;
   if (WPH == 1) {
     if (r == 0 && hl < heads_valid) {
-      const float inv = 1.0f / lw;
+      const float inv = lw > 0.f ? 1.0f / lw : 0.f;   // no rows attended (paged, empty sequence): zeros
 #pragma unroll
       for (int u = 0; u < NU; ++u) {
         h8_t pk;
@@ -543,6 +567,21 @@ int decode_attention_paged_launch(const fg_model_cfg& cfg, const half_t* q, int6
   const dim3 grid((unsigned)ceil_div(heads * wph, 4));
   const bool h16 = pages.dtype == FG_Q4G64_H16;
   ProfScope prof(FG_K_ATTN_DECODE, stream);
+  if (pages.dtype == FG_F16) {
+#define FG_PAGED_F16(DH_)                                                                                     \
+  do {                                                                                                        \
+    if (wph == 1)                                                                                             \
+      hipLaunchKernelGGL((attn_decode_f16_kernel<DH_, 1, true>), grid, dim3(256), 0, stream, a);              \
+    else if (wph == 2)                                                                                        \
+      hipLaunchKernelGGL((attn_decode_f16_kernel<DH_, 2, true>), grid, dim3(256), 0, stream, a);              \
+    else                                                                                                      \
+      hipLaunchKernelGGL((attn_decode_f16_kernel<DH_, 4, true>), grid, dim3(256), 0, stream, a);              \
+  } while (0)
+    if (dh == 128) FG_PAGED_F16(128); else FG_PAGED_F16(64);
+#undef FG_PAGED_F16
+    FG_LAUNCH_CHECK();
+    return FG_OK;
+  }
 #define FG_PAGED_LAUNCH(DH_, WPH_)                                                                          \
   do {                                                                                                      \
     if (h16)                                                                                                \

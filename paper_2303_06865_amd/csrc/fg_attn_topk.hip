@@ -30,6 +30,12 @@ struct TopkArgs {
   int nh, cap, rows, topk, batch_offset;
   int rows_pad;      // rows rounded up to whole chunks: size of the score array in LDS
   float scale;       // 1/sqrt(dh)
+  // paged cache (PAGED kernels): k/v pointers are the page pools; cap, rows, batch_offset are unused.
+  // Row i attends seq_rows[i] + rows_bias rows and keeps min(topk, that many) of them.
+  const int32_t* page_table;   // [n_seqs][table_stride]
+  const int32_t* seq_ids;      // [b] or nullptr
+  const int32_t* seq_rows;     // [b]
+  int table_stride, n_seqs, n_pages, rows_bias;
 };
 
 __device__ __forceinline__ uint32_t order_key(float s) {
@@ -57,7 +63,7 @@ __device__ __forceinline__ int block_excl_scan(int v, int* s_wave, int* total) {
   return base + incl - v;
 }
 
-template <int DH, bool H16>
+template <int DH, bool H16, bool PAGED = false>
 __global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
   using meta_t = typename MetaRaw<H16>::type;
   constexpr int GPR = DH / 64;       // quantization groups per row
@@ -81,15 +87,43 @@ __global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
   const int hid = blockIdx.x;
   const int seq = hid / a.nh, head = hid - seq * a.nh;
   const int r = lane & 15, q4 = lane >> 4, h = q4 >> 1, half = q4 & 1;
-  const int n = a.rows;
+  int n = a.rows, topk = a.topk;
+  const int32_t* tbl = nullptr;
+  if constexpr (PAGED) {
+    int sid = a.seq_ids ? a.seq_ids[seq] : seq;
+    sid = sid < 0 ? 0 : (sid >= a.n_seqs ? a.n_seqs - 1 : sid);
+    tbl = a.page_table + (int64_t)sid * a.table_stride;
+    n = a.seq_rows[seq] + a.rows_bias;
+    n = n < 0 ? 0 : n;
+    n = n > a.table_stride * FG_PAGE_ROWS ? a.table_stride * FG_PAGE_ROWS : n;   // never read past the table
+    topk = topk < n ? topk : n;
+    if (n == 0) {   // nothing to attend (uniform over the workgroup): zeros, no kept rows
+      if (tid < DH) a.out[(int64_t)hid * DH + tid] = (half_t)0.f;
+      if (a.sel_out)
+        for (int e = tid; e < a.topk; e += 256) a.sel_out[(int64_t)hid * a.topk + e] = -1;
+      return;
+    }
+  }
 
-  const int64_t hrow = ((int64_t)(a.batch_offset + seq) * a.nh + head) * a.cap;   // first cache row
-  const uint8_t* kc = a.k_codes + hrow * (DH / 2);
-  const uint8_t* vc = a.v_codes + hrow * (DH / 2);
-  const meta_t* km = reinterpret_cast<const meta_t*>(a.k_meta) + hrow * GPR;
-  const meta_t* vm = reinterpret_cast<const meta_t*>(a.v_meta) + hrow * GPR;
+  // cache row (in rows of DH elements) that holds position `row` of this head's stream
+  const int64_t hrow = PAGED ? 0 : ((int64_t)(a.batch_offset + seq) * a.nh + head) * a.cap;
+  auto rowidx = [&](int row) -> int64_t {
+    if constexpr (!PAGED) {
+      return hrow + row;
+    } else {
+      int pg = tbl[row >> 6];
+      pg = pg < 0 ? 0 : (pg >= a.n_pages ? a.n_pages - 1 : pg);   // a bad entry reads some page, never outside the pool
+      return ((int64_t)pg * a.nh + head) * FG_PAGE_ROWS + (row & (FG_PAGE_ROWS - 1));
+    }
+  };
+  const uint8_t* kc = a.k_codes;
+  const uint8_t* vc = a.v_codes;
+  const meta_t* km = reinterpret_cast<const meta_t*>(a.k_meta);
+  const meta_t* vm = reinterpret_cast<const meta_t*>(a.v_meta);
   const int G = n * GPR;
   const int n_chunks = (G + 127) >> 7;
+  // index, in quantization groups, of group g (< G) of the stream
+  auto gidx = [&](int g) -> int64_t { return rowidx(g / GPR) * GPR + (g & (GPR - 1)); };
 
   struct Buf {
     u4_t kq[4];
@@ -101,11 +135,11 @@ __global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
     for (int i = 0; i < 4; ++i) {
       int g = gbase + 32 * i + 2 * r + h;
       g = g < G ? g : G - 1;
-      b.kq[i] = *reinterpret_cast<const u4_t*>(kc + (int64_t)g * 32 + half * 16);
+      b.kq[i] = *reinterpret_cast<const u4_t*>(kc + gidx(g) * 32 + half * 16);
     }
     const int g0 = gbase + 2 * lane, g1 = g0 + 1;
-    b.km0 = km[g0 < G ? g0 : G - 1];
-    b.km1 = km[g1 < G ? g1 : G - 1];
+    b.km0 = km[gidx(g0 < G ? g0 : G - 1)];
+    b.km1 = km[gidx(g1 < G ? g1 : G - 1)];
   };
   Buf b0, b1;
   if (wave < n_chunks) load(b0, wave);
@@ -167,7 +201,7 @@ __global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
   // ---- phase 2: radix select of the topk-th largest key, most significant byte first
   if (tid == 0) {
     s_prefix = 0u;
-    s_need = a.topk;
+    s_need = topk;
   }
   uint32_t mask = 0u;
 #pragma unroll 1
@@ -239,7 +273,7 @@ __global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
   }
   __syncthreads();
   if (a.sel_out)
-    for (int e = tid; e < a.topk; e += 256) a.sel_out[(int64_t)hid * a.topk + e] = s_sel[e];
+    for (int e = tid; e < a.topk; e += 256) a.sel_out[(int64_t)hid * a.topk + e] = e < topk ? s_sel[e] : -1;
 
   // ---- phase 3: gather the kept V rows.  Lane = (row slot rs, 8-byte piece pc of the row).
   const int rs = lane / LPR, pc = lane - rs * LPR;
@@ -247,13 +281,14 @@ __global__ __launch_bounds__(256) void attn_decode_topk_q4_kernel(TopkArgs a) {
 #pragma unroll
   for (int e = 0; e < 16; ++e) o[e] = 0.f;
   float mterm = 0.f;
-  for (int e0 = wave * RPI; e0 < a.topk; e0 += 4 * RPI) {
+  for (int e0 = wave * RPI; e0 < topk; e0 += 4 * RPI) {
     const int e = e0 + rs;
-    const bool valid = e < a.topk;
-    const int row = s_sel[valid ? e : a.topk - 1];
+    const bool valid = e < topk;
+    const int row = s_sel[valid ? e : topk - 1];
     const float p = valid ? fast_exp2((s_sc[row] - M) * kLog2e) * inv_den : 0.f;
-    const uint2 cw = *reinterpret_cast<const uint2*>(vc + (int64_t)row * (DH / 2) + pc * 8);
-    const float2 mt = meta_f32(vm[(int64_t)row * GPR + (pc >> 2)]);
+    const int64_t ri = rowidx(row);
+    const uint2 cw = *reinterpret_cast<const uint2*>(vc + ri * (DH / 2) + pc * 8);
+    const float2 mt = meta_f32(vm[ri * GPR + (pc >> 2)]);
     const float w = p * mt.y;
     const float w24 = w * 16777216.0f, w20 = w * 1048576.0f;   // nibbles are read as FP16 subnormals
     mterm += p * mt.x;
@@ -296,6 +331,29 @@ constexpr int kMaxLdsWords = 36 * 1024;   // score array + index list, 4 bytes e
 
 }  // namespace
 
+static int topk_launch(TopkArgs& a, int dh, bool h16, bool paged, int64_t heads, hipStream_t stream) {
+  if ((int64_t)a.rows_pad + a.topk > kMaxLdsWords) return FG_ERR_UNSUPPORTED;
+  const size_t smem = ((size_t)a.rows_pad + a.topk) * 4;
+  const dim3 grid((unsigned)heads);
+  const int variant = (paged ? 4 : 0) + (dh == 128 ? 2 : 0) + (h16 ? 1 : 0);
+  typedef void (*kernel_t)(TopkArgs);
+  static const kernel_t kernels[8] = {
+      attn_decode_topk_q4_kernel<64, false>,        attn_decode_topk_q4_kernel<64, true>,
+      attn_decode_topk_q4_kernel<128, false>,       attn_decode_topk_q4_kernel<128, true>,
+      attn_decode_topk_q4_kernel<64, false, true>,  attn_decode_topk_q4_kernel<64, true, true>,
+      attn_decode_topk_q4_kernel<128, false, true>, attn_decode_topk_q4_kernel<128, true, true>};
+  static bool attr_done[8] = {false, false, false, false, false, false, false, false};
+  if (!attr_done[variant]) {
+    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernels[variant]),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsWords * 4));
+    attr_done[variant] = true;
+  }
+  ProfScope prof(FG_K_ATTN_DECODE, stream);
+  hipLaunchKernelGGL(kernels[variant], grid, dim3(256), smem, stream, a);
+  FG_LAUNCH_CHECK();
+  return FG_OK;
+}
+
 int decode_attention_topk_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_stride, int32_t b, int32_t rows,
                                  int32_t topk, const fg_kv_cache& kv, int32_t batch_offset, half_t* out,
                                  int32_t* sel_out, hipStream_t stream) {
@@ -318,24 +376,43 @@ int decode_attention_topk_launch(const fg_model_cfg& cfg, const half_t* q, int64
   a.batch_offset = batch_offset;
   a.rows_pad = (int)(ceil_div(rows, rpc) * rpc);
   a.scale = 1.0f / sqrtf((float)dh);
-  if ((int64_t)a.rows_pad + topk > kMaxLdsWords) return FG_ERR_UNSUPPORTED;
-  const size_t smem = ((size_t)a.rows_pad + topk) * 4;
-  const dim3 grid((unsigned)(b * cfg.nh));
-  const bool h16 = kv.dtype == FG_Q4G64_H16;
-  const int variant = (dh == 128 ? 2 : 0) + (h16 ? 1 : 0);
-  typedef void (*kernel_t)(TopkArgs);
-  static const kernel_t kernels[4] = {attn_decode_topk_q4_kernel<64, false>, attn_decode_topk_q4_kernel<64, true>,
-                                      attn_decode_topk_q4_kernel<128, false>, attn_decode_topk_q4_kernel<128, true>};
-  static bool attr_done[4] = {false, false, false, false};
-  if (!attr_done[variant]) {
-    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kernels[variant]),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsWords * 4));
-    attr_done[variant] = true;
-  }
-  ProfScope prof(FG_K_ATTN_DECODE, stream);
-  hipLaunchKernelGGL(kernels[variant], grid, dim3(256), smem, stream, a);
-  FG_LAUNCH_CHECK();
-  return FG_OK;
+  a.page_table = a.seq_ids = a.seq_rows = nullptr;
+  a.table_stride = a.n_seqs = a.n_pages = a.rows_bias = 0;
+  return topk_launch(a, dh, kv.dtype == FG_Q4G64_H16, false, (int64_t)b * cfg.nh, stream);
+}
+
+// Paged cache, a length per sequence: the score array in LDS is sized for the longest sequence the page
+// table can address.
+int decode_attention_topk_paged_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_stride, int32_t b,
+                                       int32_t topk, const fg_kv_pages& pages, const fg_ragged& seqs,
+                                       int32_t rows_bias, half_t* out, int32_t* sel_out, hipStream_t stream) {
+  if (b == 0) return FG_OK;
+  const int dh = cfg.h1 / cfg.nh;
+  const int rpc = dh == 128 ? 64 : 128;
+  TopkArgs a;
+  a.q = q;
+  a.q_stride = q_stride;
+  a.k_codes = reinterpret_cast<const uint8_t*>(pages.k_codes);
+  a.v_codes = reinterpret_cast<const uint8_t*>(pages.v_codes);
+  a.k_meta = pages.k_meta;
+  a.v_meta = pages.v_meta;
+  a.out = out;
+  a.sel_out = sel_out;
+  a.nh = cfg.nh;
+  a.cap = 0;
+  a.rows = 0;
+  a.topk = topk;
+  a.batch_offset = 0;
+  a.rows_pad = (int)(ceil_div((int64_t)seqs.table_stride * FG_PAGE_ROWS, rpc) * rpc);
+  a.scale = 1.0f / sqrtf((float)dh);
+  a.page_table = seqs.page_table;
+  a.seq_ids = seqs.seq_ids;
+  a.seq_rows = seqs.pos;
+  a.table_stride = seqs.table_stride;
+  a.n_seqs = seqs.n_seqs;
+  a.n_pages = pages.n_pages;
+  a.rows_bias = rows_bias;
+  return topk_launch(a, dh, pages.dtype == FG_Q4G64_H16, true, (int64_t)b * cfg.nh, stream);
 }
 
 }  // namespace fg
@@ -359,4 +436,24 @@ extern "C" int fg_decode_attention_topk(const fg_model_cfg* cfg, const void* q_f
   if (!q_f16 || !out_f16) return FG_ERR_NULL;
   return decode_attention_topk_launch(*cfg, reinterpret_cast<const half_t*>(q_f16), q_row_stride, b, rows, topk, *kv,
                                       batch_offset, reinterpret_cast<half_t*>(out_f16), kept_rows, as_stream(stream));
+}
+
+extern "C" int fg_decode_attention_topk_paged(const fg_model_cfg* cfg, const void* q_f16, int64_t q_row_stride,
+                                              int32_t b, int32_t topk, const fg_kv_pages* pages,
+                                              const fg_ragged* seqs, int32_t rows_bias, void* out_f16,
+                                              int32_t* kept_rows, void* stream) {
+  if (!cfg) return FG_ERR_NULL;
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  rc = check_pages(cfg, pages, seqs);
+  if (rc) return rc;
+  if (pages->dtype != FG_Q4G64 && pages->dtype != FG_Q4G64_H16) return FG_ERR_UNSUPPORTED;
+  if (!seqs->pos) return FG_ERR_NULL;
+  if (b < 0 || rows_bias < 0 || topk < 1) return FG_ERR_SHAPE;
+  if (q_row_stride < cfg->h1 || q_row_stride % 8 != 0) return FG_ERR_SHAPE;
+  if (b == 0) return FG_OK;
+  if (!q_f16 || !out_f16) return FG_ERR_NULL;
+  return decode_attention_topk_paged_launch(*cfg, reinterpret_cast<const half_t*>(q_f16), q_row_stride, b, topk, *pages,
+                                            *seqs, rows_bias, reinterpret_cast<half_t*>(out_f16), kept_rows,
+                                            as_stream(stream));
 }

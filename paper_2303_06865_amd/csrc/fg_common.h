@@ -113,6 +113,13 @@ int decode_attention_paged_launch(const fg_model_cfg& cfg, const half_t* q, int6
                                   const fg_kv_pages& pages, const fg_ragged& seqs, int32_t rows_bias, half_t* out,
                                   hipStream_t stream);
 int check_pages(const fg_model_cfg* cfg, const fg_kv_pages* pages, const fg_ragged* seqs);
+// Top-K sparse decode attention (4-bit caches): contiguous cache, and paged cache with a length per row
+int decode_attention_topk_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_stride, int32_t b, int32_t rows,
+                                 int32_t topk, const fg_kv_cache& kv, int32_t batch_offset, half_t* out,
+                                 int32_t* sel_out, hipStream_t stream);
+int decode_attention_topk_paged_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_stride, int32_t b,
+                                       int32_t topk, const fg_kv_pages& pages, const fg_ragged& seqs,
+                                       int32_t rows_bias, half_t* out, int32_t* sel_out, hipStream_t stream);
 
 // validation helpers (host only)
 int check_cfg(const fg_model_cfg* cfg);

@@ -95,13 +95,14 @@ int check_kv(const fg_model_cfg* cfg, const fg_kv_cache* kv) {
 int check_pages(const fg_model_cfg* cfg, const fg_kv_pages* pages, const fg_ragged* seqs) {
   (void)cfg;
   if (!pages || !seqs) return FG_ERR_NULL;
-  if (pages->dtype != FG_Q4G64 && pages->dtype != FG_Q4G64_H16) return FG_ERR_UNSUPPORTED;
+  const bool q4 = pages->dtype == FG_Q4G64 || pages->dtype == FG_Q4G64_H16;
+  if (!q4 && pages->dtype != FG_F16) return FG_ERR_UNSUPPORTED;
   if (pages->n_pages <= 0 || seqs->table_stride <= 0 || seqs->n_seqs <= 0) return FG_ERR_SHAPE;
   if ((int64_t)seqs->table_stride * FG_PAGE_ROWS > 0x7fffffff) return FG_ERR_SHAPE;
-  if (!pages->k_codes || !pages->v_codes || !pages->k_meta || !pages->v_meta || !seqs->page_table) return FG_ERR_NULL;
-  if (!aligned16(pages->k_codes) || !aligned16(pages->v_codes) || !aligned16(pages->k_meta) ||
-      !aligned16(pages->v_meta))
-    return FG_ERR_SHAPE;
+  if (!pages->k_codes || !pages->v_codes || !seqs->page_table) return FG_ERR_NULL;
+  if (q4 && (!pages->k_meta || !pages->v_meta)) return FG_ERR_NULL;
+  if (!aligned16(pages->k_codes) || !aligned16(pages->v_codes)) return FG_ERR_SHAPE;
+  if (q4 && (!aligned16(pages->k_meta) || !aligned16(pages->v_meta))) return FG_ERR_SHAPE;
   return FG_OK;
 }
 
@@ -215,7 +216,7 @@ struct PagedKv {
 };
 static int run_layer(const fg_model_cfg& c, const fg_layer_weights& w, const half_t* x_in, int32_t b, int32_t s,
                      bool prefill, int32_t t, const fg_kv_cache& kv, int32_t batch_offset, half_t* x_out,
-                     void* ws, size_t ws_bytes, hipStream_t st, const PagedKv* paged = nullptr) {
+                     void* ws, size_t ws_bytes, hipStream_t st, const PagedKv* paged = nullptr, int32_t topk = 0) {
   const int64_t rows = (int64_t)b * (prefill ? s : 1);
   const int64_t h1 = c.h1;
   LayerWs L = carve_layer_ws(c, w, rows, ws);
@@ -239,15 +240,24 @@ static int run_layer(const fg_model_cfg& c, const fg_layer_weights& w, const hal
       if ((rc = kv_append_paged_launch(c, L.qkv + h1, L.qkv + 2 * h1, 3 * h1, b, 1, *paged->pages, *paged->seqs,
                                        true, st)))
         return rc;
-      if ((rc = decode_attention_paged_launch(c, L.qkv, 3 * h1, b, *paged->pages, *paged->seqs, 1, L.o, st)))
-        return rc;
+      // Section 5, sparse attention: every row keeps its min(topk, rows) highest-weighted V rows
+      if (topk > 0)
+        rc = decode_attention_topk_paged_launch(c, L.qkv, 3 * h1, b, topk, *paged->pages, *paged->seqs, 1, L.o,
+                                                nullptr, st);
+      else
+        rc = decode_attention_paged_launch(c, L.qkv, 3 * h1, b, *paged->pages, *paged->seqs, 1, L.o, st);
+      if (rc) return rc;
     }
   } else if (prefill) {
     if ((rc = prefill_attention_launch(c, L.qkv, b, s, L.o, st))) return rc;
     if ((rc = kv_append_launch(c, L.qkv + h1, L.qkv + 2 * h1, 3 * h1, b, s, kv, batch_offset, 0, st))) return rc;
   } else {
     if ((rc = kv_append_launch(c, L.qkv + h1, L.qkv + 2 * h1, 3 * h1, b, 1, kv, batch_offset, t, st))) return rc;
-    if ((rc = decode_attention_launch(c, L.qkv, 3 * h1, b, t + 1, kv, batch_offset, L.o, st))) return rc;
+    if (topk > 0 && topk < t + 1)   // Section 5, sparse attention (with topk >= rows it IS the dense one)
+      rc = decode_attention_topk_launch(c, L.qkv, 3 * h1, b, t + 1, topk, kv, batch_offset, L.o, nullptr, st);
+    else
+      rc = decode_attention_launch(c, L.qkv, 3 * h1, b, t + 1, kv, batch_offset, L.o, st);
+    if (rc) return rc;
   }
   if ((rc = linear_launch(make_linear(w.wo, w.bo, L.o, h1, rows, x_in, h1, 0, L.x1, h1), L.gemm, L.gemm_bytes,
                           st)))
@@ -524,11 +534,13 @@ extern "C" int fg_prefill_layer(const fg_model_cfg* cfg, const fg_layer_weights*
 }
 
 extern "C" int fg_decode_layer(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in, int32_t b,
-                               int32_t t, const fg_kv_cache* kv, int32_t batch_offset, void* x_out, void* ws,
-                               size_t ws_bytes, void* stream) {
+                               int32_t t, int32_t topk, const fg_kv_cache* kv, int32_t batch_offset, void* x_out,
+                               void* ws, size_t ws_bytes, void* stream) {
   int rc = check_layer_call(cfg, wts, x_in, kv, x_out);
   if (rc) return rc;
-  if (b < 0 || t < 0 || batch_offset < 0 || b > 65535) return FG_ERR_SHAPE;
+  if (b < 0 || t < 0 || batch_offset < 0 || b > 65535 || topk < 0) return FG_ERR_SHAPE;
+  if (topk > 0 && kv->dtype != FG_Q4G64 && kv->dtype != FG_Q4G64_H16) return FG_ERR_UNSUPPORTED;
+  if (topk > 0 && topk < t + 1 && (int64_t)(t + 1 + 127) / 128 * 128 + topk > 36864) return FG_ERR_UNSUPPORTED;
   if ((int64_t)batch_offset + b > kv->batch || t >= kv->cap) return FG_ERR_SHAPE;
   if (b == 0) return FG_OK;
   if (!x_in || !x_out) return FG_ERR_NULL;
@@ -537,19 +549,21 @@ extern "C" int fg_decode_layer(const fg_model_cfg* cfg, const fg_layer_weights* 
   if (!ws || ws_bytes < need) return FG_ERR_WORKSPACE;
   if (!aligned16(ws)) return FG_ERR_SHAPE;
   return run_layer(*cfg, *wts, reinterpret_cast<const half_t*>(x_in), b, 1, false, t, *kv, batch_offset,
-                   reinterpret_cast<half_t*>(x_out), ws, ws_bytes, as_stream(stream));
+                   reinterpret_cast<half_t*>(x_out), ws, ws_bytes, as_stream(stream), nullptr, topk);
 }
 
 static int paged_layer_entry(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in, int32_t b,
                              int32_t s, bool prefill, const fg_kv_pages* pages, const fg_ragged* seqs, void* x_out,
-                             void* ws, size_t ws_bytes, void* stream) {
+                             void* ws, size_t ws_bytes, void* stream, int32_t topk = 0) {
   if (!cfg || !wts) return FG_ERR_NULL;
   int rc = check_cfg(cfg);
   if (rc) return rc;
   if ((rc = check_layer(cfg, wts))) return rc;
   if ((rc = check_pages(cfg, pages, seqs))) return rc;
   if (!prefill && !seqs->pos) return FG_ERR_NULL;
-  if (b < 0 || s < 0 || b > 65535 || (int64_t)b * s > 0x7fffffff) return FG_ERR_SHAPE;
+  if (b < 0 || s < 0 || b > 65535 || (int64_t)b * s > 0x7fffffff || topk < 0) return FG_ERR_SHAPE;
+  if (topk > 0 && pages->dtype != FG_Q4G64 && pages->dtype != FG_Q4G64_H16) return FG_ERR_UNSUPPORTED;
+  if (topk > 0 && ((int64_t)seqs->table_stride * FG_PAGE_ROWS + 127) / 128 * 128 + topk > 36864) return FG_ERR_UNSUPPORTED;
   if (prefill && s > (int64_t)seqs->table_stride * FG_PAGE_ROWS) return FG_ERR_SHAPE;
   if (b == 0 || s == 0) return FG_OK;
   if (!x_in || !x_out) return FG_ERR_NULL;
@@ -560,13 +574,13 @@ static int paged_layer_entry(const fg_model_cfg* cfg, const fg_layer_weights* wt
   const PagedKv pk = {pages, seqs};
   const fg_kv_cache none = {};
   return run_layer(*cfg, *wts, reinterpret_cast<const half_t*>(x_in), b, s, prefill, 0, none, 0,
-                   reinterpret_cast<half_t*>(x_out), ws, ws_bytes, as_stream(stream), &pk);
+                   reinterpret_cast<half_t*>(x_out), ws, ws_bytes, as_stream(stream), &pk, topk);
 }
 
 extern "C" int fg_decode_layer_paged(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in,
-                                     int32_t b, const fg_kv_pages* pages, const fg_ragged* seqs, void* x_out,
-                                     void* ws, size_t ws_bytes, void* stream) {
-  return paged_layer_entry(cfg, wts, x_in, b, 1, false, pages, seqs, x_out, ws, ws_bytes, stream);
+                                     int32_t b, int32_t topk, const fg_kv_pages* pages, const fg_ragged* seqs,
+                                     void* x_out, void* ws, size_t ws_bytes, void* stream) {
+  return paged_layer_entry(cfg, wts, x_in, b, 1, false, pages, seqs, x_out, ws, ws_bytes, stream, topk);
 }
 
 extern "C" int fg_prefill_layer_paged(const fg_model_cfg* cfg, const fg_layer_weights* wts, const void* x_in,
@@ -887,9 +901,10 @@ extern "C" int fg_generate_diagonal(const fg_model_cfg* cfg, int32_t l, const fg
   const int gbs = gpu_batch_size;
   for (int j = 0; j < l; ++j) {
     if ((rc = check_layer(cfg, &layers[j]))) return rc;
-    if (pages[j].dtype != FG_Q4G64 && pages[j].dtype != FG_Q4G64_H16) return FG_ERR_UNSUPPORTED;
+    const bool q4 = pages[j].dtype == FG_Q4G64 || pages[j].dtype == FG_Q4G64_H16;
+    if (!q4 && pages[j].dtype != FG_F16) return FG_ERR_UNSUPPORTED;
     if (pages[j].n_pages != pages[0].n_pages || pages[j].n_pages <= 0) return FG_ERR_SHAPE;
-    if (!pages[j].k_codes || !pages[j].v_codes || !pages[j].k_meta || !pages[j].v_meta) return FG_ERR_NULL;
+    if (!pages[j].k_codes || !pages[j].v_codes || (q4 && (!pages[j].k_meta || !pages[j].v_meta))) return FG_ERR_NULL;
     if (layers[j].wqkv.dtype != layers[0].wqkv.dtype || layers[j].wo.dtype != layers[0].wo.dtype ||
         layers[j].w1.dtype != layers[0].w1.dtype || layers[j].w2.dtype != layers[0].w2.dtype)
       return FG_ERR_UNSUPPORTED;

@@ -223,7 +223,7 @@ __global__ __launch_bounds__(256) void kv_append_f16_kernel(KvAppendArgs a) {
     const int64_t bi = row / a.s;
     const u4_t v = *reinterpret_cast<const u4_t*>(x + row * a.ld + (int64_t)ci * 8);
     const int64_t crow = kv_dest_row(a, bi, head, (int)(row - bi * a.s));
-    *reinterpret_cast<u4_t*>(dst + crow * a.dh + ch * 8) = v;
+    if (crow >= 0) *reinterpret_cast<u4_t*>(dst + crow * a.dh + ch * 8) = v;
   }
 }
 
@@ -301,6 +301,13 @@ int kv_append_paged_launch(const fg_model_cfg& cfg, const half_t* k, const half_
   a.n_seqs = seqs.n_seqs;
   a.n_pages = pages.n_pages;
   ProfScope prof(FG_K_KV_APPEND, stream);
+  if (pages.dtype == FG_F16) {
+    const int64_t chunks = (int64_t)b * s * cfg.h1 / 8;
+    dim3 grid(grid_for(chunks, 256), 2);
+    hipLaunchKernelGGL(kv_append_f16_kernel, grid, dim3(256), 0, stream, a);
+    FG_LAUNCH_CHECK();
+    return FG_OK;
+  }
   const int gpr = cfg.h1 / kGroup;
   dim3 grid((unsigned)ceil_div(b * ceil_div(s, kKvPosPerWave), 4), (unsigned)ceil_div(gpr, 8), 2);
   if (pages.dtype == FG_Q4G64_H16)

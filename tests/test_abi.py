@@ -73,8 +73,8 @@ def test_layer_argument_errors_need_no_gpu():
                            a, a, a, a)
     kv = B.fg_kv_cache(a, a, a, a, B.FG_Q4G64, 4, 40, 0)
     ws = C.c_void_p(a)
-    call = lambda cfg_, w_, kv_, b=4, t=32, ws_=ws, nws=1 << 40: L.fg_decode_layer(
-        C.byref(cfg_), C.byref(w_), a, b, t, C.byref(kv_), 0, a, ws_, nws, None)
+    call = lambda cfg_, w_, kv_, b=4, t=32, ws_=ws, nws=1 << 40, topk=0: L.fg_decode_layer(
+        C.byref(cfg_), C.byref(w_), a, b, t, topk, C.byref(kv_), 0, a, ws_, nws, None)
     assert call(_cfg(nh=5), w, kv) == B.FG_ERR_SHAPE            # h1 % nh != 0
     assert call(_cfg(h1=768, nh=3), w, kv) == B.FG_ERR_UNSUPPORTED   # head size 256
     assert call(cfg, w, kv, t=40) == B.FG_ERR_SHAPE             # t >= cap
@@ -89,7 +89,10 @@ def test_layer_argument_errors_need_no_gpu():
     assert call(cfg, bad, kv) == B.FG_ERR_UNSUPPORTED
     nometa = B.fg_kv_cache(a, None, a, a, B.FG_Q4G64, 4, 40, 0)
     assert call(cfg, w, nometa) == B.FG_ERR_NULL
-    assert L.fg_decode_layer(None, C.byref(w), a, 4, 0, C.byref(kv), 0, a, ws, 1 << 40, None) == B.FG_ERR_NULL
+    assert L.fg_decode_layer(None, C.byref(w), a, 4, 0, 0, C.byref(kv), 0, a, ws, 1 << 40, None) == B.FG_ERR_NULL
+    assert call(cfg, w, kv, topk=-1) == B.FG_ERR_SHAPE
+    f16kv = B.fg_kv_cache(a, None, a, None, B.FG_F16, 4, 40, 0)
+    assert call(cfg, w, f16kv, topk=3) == B.FG_ERR_UNSUPPORTED      # sparse attention reads 4-bit caches only
     assert L.fg_prefill_layer(C.byref(cfg), C.byref(w), a, 4, 41, C.byref(kv), 0, a, ws, 1 << 40, None) == B.FG_ERR_SHAPE
     # generate: block must fit the caches, positions must exist
     larr = (B.fg_layer_weights * 1)(w)
@@ -148,7 +151,8 @@ def test_paged_and_diagonal_argument_errors_need_no_gpu():
     ws = C.c_void_p(a)
     att = lambda pg=pages, sq=seqs, b=4, bias=1, stride=2304: L.fg_decode_attention_paged(
         C.byref(cfg), a, stride, b, C.byref(pg), C.byref(sq), bias, a, None)
-    assert att(pg=B.fg_kv_pages(a, a, a, a, B.FG_F16, 8)) == B.FG_ERR_UNSUPPORTED     # pages hold 4-bit rows only
+    assert att(pg=B.fg_kv_pages(a, a, a, a, 7, 8)) == B.FG_ERR_UNSUPPORTED            # unknown storage format
+    assert att(pg=B.fg_kv_pages(a, None, a, None, B.FG_F16, 8), b=0) == B.FG_OK       # FP16 pages carry no pairs
     assert att(pg=B.fg_kv_pages(a, a, a, a, B.FG_Q4G64, 0)) == B.FG_ERR_SHAPE
     assert att(pg=B.fg_kv_pages(a, None, a, a, B.FG_Q4G64, 8)) == B.FG_ERR_NULL
     assert att(sq=B.fg_ragged(None, None, a, 2, 4)) == B.FG_ERR_NULL                  # no page table
@@ -159,8 +163,16 @@ def test_paged_and_diagonal_argument_errors_need_no_gpu():
     assert att(b=0) == B.FG_OK
     assert L.fg_kv_append_paged(C.byref(cfg), a, a, 2304, 4, -1, C.byref(pages), C.byref(seqs), None) == B.FG_ERR_SHAPE
     assert L.fg_kv_append_paged(C.byref(cfg), None, a, 2304, 4, 1, C.byref(pages), C.byref(seqs), None) == B.FG_ERR_NULL
-    lay = lambda sq=seqs, nws=1 << 40: L.fg_decode_layer_paged(C.byref(cfg), C.byref(w), a, 4, C.byref(pages),
-                                                               C.byref(sq), a, ws, nws, None)
+    lay = lambda sq=seqs, nws=1 << 40, topk=0, pg=pages: L.fg_decode_layer_paged(
+        C.byref(cfg), C.byref(w), a, 4, topk, C.byref(pg), C.byref(sq), a, ws, nws, None)
+    assert lay(topk=-2) == B.FG_ERR_SHAPE
+    assert lay(topk=3, pg=B.fg_kv_pages(a, None, a, None, B.FG_F16, 8)) == B.FG_ERR_UNSUPPORTED
+    tk = lambda topk=3, pg=pages, sq=seqs, b=4: L.fg_decode_attention_topk_paged(
+        C.byref(cfg), a, 2304, b, topk, C.byref(pg), C.byref(sq), 1, a, None, None)
+    assert tk(topk=0) == B.FG_ERR_SHAPE
+    assert tk(pg=B.fg_kv_pages(a, None, a, None, B.FG_F16, 8)) == B.FG_ERR_UNSUPPORTED
+    assert tk(sq=B.fg_ragged(a, None, None, 2, 4)) == B.FG_ERR_NULL
+    assert tk(b=0) == B.FG_OK
     assert lay(nws=8) == B.FG_ERR_WORKSPACE
     assert lay(sq=B.fg_ragged(a, None, None, 2, 4)) == B.FG_ERR_NULL                  # decode needs positions
     # a prompt longer than the page table can address
