@@ -204,8 +204,11 @@ TILED_CASES = [
     (17, 2304, 768, True, False, False),
     (36, 992, 832, True, False, True),       # ragged column block (992 = 31 tiles of 32)
     (48, 288, 192, False, True, False),
+    (70, 512, 640, True, True, True),        # five 16-row tiles
     (100, 544, 1024, True, False, False),
+    (112, 36864, 256, False, False, True),   # 144 whole tiles of seven 16-row tiles: no reduction pass at all
     (144, 1024, 12288, True, False, True),   # 4 tiles over 256 workgroups: 64 contributors per tile in the reduction pass
+    (288, 1280, 512, True, False, True),     # two row blocks of nine 16-row tiles
     (150, 768, 768, False, False, False),
     (200, 512, 256, True, True, True),       # two row blocks
     (300, 800, 448, True, False, True),
