@@ -451,26 +451,17 @@ __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
 
 }  // namespace
 
-// Waves per (sequence, head): 1, 2 or 4.  A stream of c chunks costs a wave ceil(c / WPH) chunk times plus
-// about half a chunk time of set-up and reduction, so one wave per head wastes the least; but the chip
-// holds 768 workgroups of four waves at once, and a launch of fewer than four such rounds runs in
-// whole rounds: 1024 workgroups take as long as 1536.  The cheapest of the three under that model.
+// Waves per (sequence, head): 1, 2 or 4.  A stream of c chunks costs a wave ceil(c / WPH) chunk times
+// plus the merge, so one wave per head wastes the least, and measured it is the fastest from a few
+// thousand heads up even where the launch is only one or two rounds of workgroups (4096 heads x 528
+// rows: 4.6 / 4.4 / 4.2 TB/s with 1 / 2 / 4 waves per head; 13824 heads: 5.4 / 4.9 / 4.3).  Fewer
+// heads than that get more waves each, so that the chip is not left empty, but never more waves than
+// the stream has chunks.
 static int pick_waves_per_head(int64_t heads, int rows, int rows_per_chunk) {
-  const int64_t slots = 256 * 3;
   const int chunks = (rows + rows_per_chunk - 1) / rows_per_chunk;
-  int best = 1;
-  double best_cost = 0.0;
-  for (int wph = 1; wph <= 4; wph *= 2) {
-    const double wgs = (double)ceil_div(heads * wph, 4);
-    double rounds = wgs / slots;
-    if (rounds < 4.0) rounds = (double)ceil_div((int64_t)wgs, slots);
-    const double cost = rounds * ((chunks + wph - 1) / wph + 0.5 + (wph > 1 ? 0.25 : 0.0));
-    if (wph == 1 || cost < best_cost) {
-      best = wph;
-      best_cost = cost;
-    }
-  }
-  return best;
+  int wph = heads >= 2048 ? 1 : (heads >= 1024 ? 2 : 4);
+  while (wph > 1 && chunks < wph) wph >>= 1;
+  return wph;
 }
 
 int decode_attention_launch(const fg_model_cfg& cfg, const half_t* q, int64_t q_stride, int32_t b,
