@@ -554,7 +554,9 @@ int decode_attention_paged_launch(const fg_model_cfg& cfg, const half_t* q, int6
   a.n_pages = pages.n_pages;
   a.rows_bias = rows_bias;
   const int64_t heads = (int64_t)b * cfg.nh;
-  const int wph = heads >= 2048 ? 1 : (heads >= 1024 ? 2 : 4);   // as in the contiguous launch
+  // as in the contiguous launch, with the longest sequence the page table can address standing in for the
+  // lengths, which only the device knows
+  const int wph = pick_waves_per_head(heads, seqs.table_stride * FG_PAGE_ROWS, pages.dtype == FG_F16 ? 64 : 8192 / dh);
   const dim3 grid((unsigned)ceil_div(heads * wph, 4));
   const bool h16 = pages.dtype == FG_Q4G64_H16;
   ProfScope prof(FG_K_ATTN_DECODE, stream);

@@ -589,6 +589,429 @@ __global__ __launch_bounds__(512) void gemm_stream_finish_kernel(StreamArgs a, i
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Decode shape on 16-row tiles.  The 32 x 32 tiles above round a block of rows up to a multiple of 32:
+// the 144 rows of a 4 x 36 block are computed as 160, a tenth of the matrix-core time for nothing.
+// This kernel is the same pipeline (same stages, copies, tile walk, stream-K ranges and partial-sum
+// scheme) on v_mfma_f32_16x16x32_f16: MT16 = ceil(rows / 16) row tiles, each wave all rows x 64 columns
+// as four column tiles of 16.  It is used where the row count fills an odd number of 16-row tiles.
+//   A operand  lane (i = l % 16, g = l / 16): row 16 m + i, the 8 halves of logical chunk 4 s + g of the
+//              64-wide K step (s = 0, 1: the two K slices of 32); one ds_read_b128, conflict-free under
+//              the stage's XOR swizzle.
+//   B operand  lane (j = l % 16, g): column 16 c + j of a 32-column weight tile, codes 32 s + 8 g .. + 8:
+//              word g of the 16-byte piece (column, half s) of the tiled layout, i.e. one ds_read_b32 at
+//              16 (32 s + 16 c + j) + 4 g (64 distinct banks), dequantized exactly as above.
+//   K step     slice 0: its 9 x 4 MFMAs with the reads of slice 1's A operands and the dequantization of
+//              slice 1's weights between them; then this wave's copies of the next step have landed
+//              (vmcnt) and a barrier: every wave's have, and nobody reads this stage any more;
+//              slice 1: copies for step ks + kNST into this stage, the next stage's A operands, code
+//              words and {min, scale}, and the dequantization of its first slice, between the MFMAs.
+// acc += A . B on v_mfma_f32_16x16x32_f16 with the accumulator updated IN PLACE in accumulation
+// registers.  Written as an instruction because the register allocator, given 36 four-register
+// accumulators per wave through the builtin, keeps rotating them through other registers (three
+// register moves and wait states per MFMA); an in-place operand leaves it nothing to rotate.
+__device__ __forceinline__ void mfma16_inplace(f4_t& acc, const h8_t& a, const h8_t& b) {
+  __asm__ volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+template <int MT16, bool H16M>
+struct Dec16Cfg {
+  static constexpr int kMT32 = (MT16 + 1) / 2;
+  static constexpr int kRowsLds = kMT32 * 32;             // rows of the activation tile in a stage (copied in 8-row pieces)
+  static constexpr int kRows = MT16 * 16;                 // rows computed
+  static constexpr int kAStage = kRowsLds * kKS * 2;
+  static constexpr int kStageBytes = kAStage + kBStageQ4;
+  static constexpr int kNST = kLdsBytes / kStageBytes > 5 ? 5 : kLdsBytes / kStageBytes;
+  static constexpr int kACopies = kRowsLds / 8 / 4;
+  static constexpr int kCopies = kACopies + 4;
+};
+
+template <int MT16, bool H16M>
+__global__ __launch_bounds__(256) void gemm_decode16_kernel(StreamArgs a) {
+  using C = Dec16Cfg<MT16, H16M>;
+  constexpr int kAStage = C::kAStage, kStageBytes = C::kStageBytes, kNST = C::kNST;
+  constexpr int kACopies = C::kACopies, kCopies = C::kCopies;
+  constexpr int kWait = (kNST - 2) * kCopies;
+  constexpr int kNM = MT16 * 4;                 // MFMAs per K slice
+  constexpr int NW = 4;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, g4 = lane >> 4;
+
+  const int p = (blockIdx.x & 7) * (a.grid >> 3) + (blockIdx.x >> 3);
+  const int64_t rem_begin = work_begin(a.rem_work, a.grid, p), rem_end = work_begin(a.rem_work, a.grid, p + 1);
+  int64_t pos = rem_begin;
+  int round = 0, seg = 0;
+
+  // operand read offsets inside a stage
+  int a_off[2];
+#pragma unroll
+  for (int sl = 0; sl < 2; ++sl) a_off[sl] = (l16 * kKS + swz(l16, 4 * sl + g4) * 8) * 2;
+  // code word of (column tile ct, slice sl): + (ct >> 1) * 1024 + (ct & 1) * 256 + sl * 512
+  const int bq_off = kAStage + wave * 2 * 1024 + l16 * 16 + g4 * 4;
+  // {min, scale} of column tile ct: + (ct >> 1) * 256 + (ct & 1) * 16 * (H16M ? 4 : 8)
+  const int bm_off = kAStage + 8 * 1024 + wave * 2 * 256 + l16 * (H16M ? 4 : 8);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
+
+  while (round < a.rounds || pos < rem_end) {
+    int64_t tile;
+    int ks0, ks1;
+    const bool whole_round = round < a.rounds;
+    if (whole_round) {
+      tile = (int64_t)round * a.grid + p;
+      ks0 = 0;
+      ks1 = a.ksteps;
+    } else {
+      const int64_t t = pos / a.ksteps;
+      tile = (int64_t)a.rounds * a.grid + t;
+      ks0 = (int)(pos - t * a.ksteps);
+      const int64_t left = rem_end - pos;
+      ks1 = (int)((int64_t)(a.ksteps - ks0) < left ? a.ksteps : ks0 + left);
+    }
+    int mblk, n_tile;
+    tile_coords(tile, a.m_blocks, a.n_tiles, mblk, n_tile);
+    const int m0 = mblk * C::kRows;
+    const int nt0 = n_tile * 8 + wave * 2;   // first 32-column tile of this wave
+
+    f4_t acc[MT16][4];
+#pragma unroll
+    for (int m = 0; m < MT16; ++m)
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) acc[m][ct] = (f4_t){0.f, 0.f, 0.f, 0.f};
+
+    const half_t* a_src[kACopies];
+#pragma unroll
+    for (int i = 0; i < kACopies; ++i) {
+      const int c = wave + NW * i;
+      const int prow = 8 * c + (lane >> 3);
+      int row = m0 + prow;
+      row = row < a.M ? row : a.M - 1;
+      a_src[i] = a.x + (int64_t)row * a.ldx + swz(prow, lane & 7) * 8;
+    }
+    const uint8_t* w_src[2];
+    const float* m_src[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      int nt = nt0 + j;
+      nt = nt < a.n32 ? nt : a.n32 - 1;   // ragged last column block: load valid data, never store it
+      w_src[j] = a.w + (int64_t)nt * a.ksteps * 1024 + lane * 16;
+      m_src[j] = reinterpret_cast<const float*>(a.meta) +
+                 (H16M ? (int64_t)nt * a.ksteps * 32 + (lane & 31) : (int64_t)nt * a.ksteps * 64 + lane);
+    }
+    auto copy_one = [&](int c, int ks, int stage) {
+      const int kc = ks < ks1 ? ks : ks1 - 1;
+      unsigned char* st = smem + stage * kStageBytes;
+      if (c < kACopies) {
+        __builtin_amdgcn_global_load_lds((gptr_t)(a_src[c] + kc * kKS), (lptr_t)(st + (wave + NW * c) * 8 * kKS * 2), 16,
+                                         0, 0);
+      } else {
+        const int b = c - kACopies, j = b >> 1;
+        if ((b & 1) == 0)
+          __builtin_amdgcn_global_load_lds((gptr_t)(w_src[j] + (int64_t)kc * 1024),
+                                           (lptr_t)(st + kAStage + (wave * 2 + j) * 1024), 16, 0, 0);
+        else
+          __builtin_amdgcn_global_load_lds((gptr_t)(m_src[j] + (int64_t)kc * (H16M ? 32 : 64)),
+                                           (lptr_t)(st + kAStage + 8 * 1024 + (wave * 2 + j) * 256), 4, 0, 0);
+      }
+    };
+
+    h8_t aop[2][MT16];
+    u4_t bop[2][4];
+    uint32_t cw[2][4];     // raw code words [slice][column tile] of the current stage
+    float2 cm[4];
+    uint32_t cmh[4];
+    float s24[4], s20[4], mn[4];
+    auto read_a = [&](uint32_t st, int sl, h8_t* dst) {
+      const uint32_t ad = st + a_off[sl];
+      static_for<0, MT16>([&](auto m) __attribute__((always_inline)) {
+        constexpr int off = decltype(m)::value * 16 * kKS * 2;
+        dst[decltype(m)::value] = __builtin_bit_cast(h8_t, lds_read128<off>(ad));
+      });
+    };
+    auto read_b = [&](int stage) {
+      const uint32_t st = lds0 + stage * kStageBytes;
+      static_for<0, 4>([&](auto CT) __attribute__((always_inline)) {
+        constexpr int ct = decltype(CT)::value;
+        constexpr int qoff = (ct >> 1) * 1024 + (ct & 1) * 256;
+        cw[0][ct] = lds_read32<qoff>(st + bq_off);
+        cw[1][ct] = lds_read32<qoff + 512>(st + bq_off);
+        constexpr int moff = (ct >> 1) * 256 + (ct & 1) * 16 * (H16M ? 4 : 8);
+        if constexpr (H16M) cmh[ct] = lds_read32<moff>(st + bm_off); else cm[ct] = lds_read64<moff>(st + bm_off);
+      });
+    };
+    auto landed_b = [&]() {
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        lds_landed(cw[0][ct]);
+        lds_landed(cw[1][ct]);
+        if constexpr (H16M) lds_landed(cmh[ct]); else lds_landed(cm[ct]);
+      }
+    };
+    auto set_meta = [&]() {
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        if constexpr (H16M) {
+          const h2_t pr = __builtin_bit_cast(h2_t, cmh[ct]);
+          cm[ct].x = (float)pr.x;
+          cm[ct].y = (float)pr.y;
+        }
+        s24[ct] = cm[ct].y * 16777216.0f;
+        s20[ct] = cm[ct].y * 1048576.0f;
+        mn[ct] = cm[ct].x;
+      }
+    };
+    // Exact dequantization of one code word (fg_common.h: dequant8_exact) into the B operand of
+    // (slice, ct), cut into four pieces of two to four VALU instructions so that it can be spread
+    // between MFMAs of 16 cycles: 0, 1 = nibble masks, 2 = operand registers 0 and 1 (weights 0..3),
+    // 3 = registers 2 and 3 (weights 4..7); the two halves of one register are never written back to back.
+    // Every piece ends in an empty volatile statement on its result: the MFMAs here are volatile
+    // instructions too, so a piece stays where it is written, between the same two MFMAs, instead of
+    // being sunk next to its consumer.  That matters for correctness, not only for speed: the compiler
+    // does not know that the consumer is an MFMA and puts no wait state between a VALU write of an
+    // operand register and the MFMA that reads it in the next cycle (seen: wrong sums in one column tile).
+    uint32_t msk[4];
+    auto dq_piece = [&](int sl, int ct, int buf, int piece) {
+      if (piece == 0) {
+        const uint32_t x = cw[sl][ct];
+        msk[0] = x & 0x000F000Fu;
+        msk[1] = x & 0x00F000F0u;
+        __asm__ volatile("" : "+v"(msk[0]), "+v"(msk[1]));
+      } else if (piece == 1) {
+        const uint32_t y = cw[sl][ct] >> 8;
+        msk[2] = y & 0x000F000Fu;
+        msk[3] = y & 0x00F000F0u;
+        __asm__ volatile("" : "+v"(msk[2]), "+v"(msk[3]));
+      } else {
+        const h2_t ha = __builtin_bit_cast(h2_t, msk[0]), hb = __builtin_bit_cast(h2_t, msk[1]);
+        const h2_t hc = __builtin_bit_cast(h2_t, msk[2]), hd = __builtin_bit_cast(h2_t, msk[3]);
+        h2_t q0, q1;
+        if (piece == 2) {
+          q0 = (h2_t){(half_t)__builtin_fmaf((float)ha.x, s24[ct], mn[ct]), (half_t)__builtin_fmaf((float)hb.x, s20[ct], mn[ct])};
+          q1 = (h2_t){(half_t)__builtin_fmaf((float)hc.x, s24[ct], mn[ct]), (half_t)__builtin_fmaf((float)hd.x, s20[ct], mn[ct])};
+        } else {
+          q0 = (h2_t){(half_t)__builtin_fmaf((float)ha.y, s24[ct], mn[ct]), (half_t)__builtin_fmaf((float)hb.y, s20[ct], mn[ct])};
+          q1 = (h2_t){(half_t)__builtin_fmaf((float)hc.y, s24[ct], mn[ct]), (half_t)__builtin_fmaf((float)hd.y, s20[ct], mn[ct])};
+        }
+        uint32_t r0 = __builtin_bit_cast(uint32_t, q0), r1 = __builtin_bit_cast(uint32_t, q1);
+        __asm__ volatile("" : "+v"(r0), "+v"(r1));
+        bop[buf][ct][2 * (piece - 2)] = r0;
+        bop[buf][ct][2 * (piece - 2) + 1] = r1;
+      }
+    };
+    constexpr int kPieces = 16;   // 4 column tiles x 4 pieces per K slice
+
+    __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < kNST; ++t)
+#pragma unroll
+      for (int c = 0; c < kCopies; ++c) copy_one(c, ks0 + t, t);
+    __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"((kNST - 1) * kCopies) : "memory");
+    __builtin_amdgcn_s_barrier();
+    read_a(lds0, 0, aop[0]);
+    read_b(0);
+    lds_wait();
+#pragma unroll
+    for (int m = 0; m < MT16; ++m) lds_landed(aop[0][m]);
+    landed_b();
+    set_meta();
+#pragma unroll
+    for (int q = 0; q < kPieces; ++q) dq_piece(0, q / 4, 0, q % 4);
+
+    int stage = 0;
+    for (int ks = ks0; ks < ks1; ++ks) {
+      const int stage1 = stage + 1 == kNST ? 0 : stage + 1;
+      const uint32_t At = lds0 + stage * kStageBytes;
+      // ---- slice 0
+      read_a(At, 1, aop[1]);
+      __builtin_amdgcn_sched_barrier(0);
+      static_for<0, kNM>([&](auto I) __attribute__((always_inline)) {
+        constexpr int i = decltype(I)::value;
+        constexpr int ct = i / MT16, m = i - ct * MT16;
+        mfma16_inplace(acc[m][ct], aop[0][m], __builtin_bit_cast(h8_t, bop[0][ct]));
+        __builtin_amdgcn_sched_barrier(0);
+        // the dequantization of slice 1, spread evenly over the MFMAs
+        static_for<i * kPieces / kNM, (i + 1) * kPieces / kNM>([&](auto Q) __attribute__((always_inline)) {
+          constexpr int q = decltype(Q)::value;
+          dq_piece(1, q / 4, 1, q % 4);
+        });
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      lds_wait();
+#pragma unroll
+      for (int m = 0; m < MT16; ++m) lds_landed(aop[1][m]);
+      __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"(kWait) : "memory");
+      __builtin_amdgcn_s_barrier();   // bare barrier: no fence, the copies in flight stay in flight
+      __builtin_amdgcn_sched_barrier(0);
+      // ---- slice 1
+      read_a(lds0 + stage1 * kStageBytes, 0, aop[0]);
+      read_b(stage1);
+      __builtin_amdgcn_sched_barrier(0);
+      constexpr int kH = kNM / 2;
+      static_for<0, kNM>([&](auto I) __attribute__((always_inline)) {
+        constexpr int i = decltype(I)::value;
+        constexpr int ct = i / MT16, m = i - ct * MT16;
+        mfma16_inplace(acc[m][ct], aop[1][m], __builtin_bit_cast(h8_t, bop[1][ct]));
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (i < kH) {
+          static_for<i * kCopies / kH, (i + 1) * kCopies / kH>([&](auto CC) __attribute__((always_inline)) {
+            copy_one(decltype(CC)::value, ks + kNST, stage);
+          });
+          if constexpr (i == kH - 1) {
+            lds_wait();
+#pragma unroll
+            for (int mm = 0; mm < MT16; ++mm) lds_landed(aop[0][mm]);
+            landed_b();
+            set_meta();
+          }
+        } else {
+          // the dequantization of the next step's slice 0, spread over the second half
+          constexpr int r = i - kH, n2 = kNM - kH;
+          static_for<r * kPieces / n2, (r + 1) * kPieces / n2>([&](auto Q) __attribute__((always_inline)) {
+            constexpr int q = decltype(Q)::value;
+            dq_piece(0, q / 4, 0, q % 4);
+          });
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      stage = stage1;
+    }
+
+    // The MFMAs above are opaque instructions to the compiler, so it does not know that the last of them
+    // are still in the matrix pipe (16 cycles each) when the accumulators are read below: wait them out.
+    __asm__ volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+    for (int m = 0; m < MT16; ++m)
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) __asm__ volatile("" : "+a"(acc[m][ct]));
+    // ---- epilogue: lane holds column l16 of each 16 x 16 tile, rows 4 * g4 + 0..3
+    const bool full = (ks0 == 0) && (ks1 == a.ksteps);
+    if (full) {
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        const int col = (nt0 + (ct >> 1)) * 32 + (ct & 1) * 16 + l16;
+        if (nt0 + (ct >> 1) < a.n32) {
+          const float bvv = a.bias ? (float)a.bias[col] : 0.f;
+#pragma unroll
+          for (int m = 0; m < MT16; ++m) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int row = m0 + 16 * m + 4 * g4 + r;
+              if (row < a.M && row < m0 + C::kRows) {
+                float v = acc[m][ct][r] + bvv;
+                if (a.relu) v = fmaxf(v, 0.f);
+                if (a.residual) v += (float)a.residual[(int64_t)row * a.ldr + col];
+                if (a.out32)
+                  a.out32[(int64_t)row * a.ldo + col] = v;
+                else
+                  a.out16[(int64_t)row * a.ldo + col] = (half_t)v;
+              }
+            }
+          }
+        }
+      }
+    } else {
+      // partial sums in register order: float4 number (m * 4 + ct) of thread tid holds rows
+      // 16 m + 4 g4 + 0..3 of one column -> every store is 1 KiB contiguous per wave
+      float4* dst = reinterpret_cast<float4*>(a.partial + ((int64_t)p * 2 + (seg == 0 ? 0 : 1)) * ((int64_t)C::kRows * kBN)) + tid;
+#pragma unroll
+      for (int m = 0; m < MT16; ++m)
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+          *dst = make_float4(acc[m][ct][0], acc[m][ct][1], acc[m][ct][2], acc[m][ct][3]);
+          dst += NW * 64;
+        }
+    }
+    if (whole_round) {
+      ++round;
+    } else {
+      pos += ks1 - ks0;
+      ++seg;
+    }
+  }
+  __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// Reduction pass for gemm_decode16_kernel: thread tid of a block adds, in ascending K order, the float4s
+// that thread tid of the contributing workgroups wrote, then applies the epilogue.  blockIdx.x counts the
+// tiles after the whole rounds, blockIdx.y spreads a thread's MT16 * 4 items.
+__global__ __launch_bounds__(256) void gemm_decode16_finish_kernel(StreamArgs a, int mt16) {
+  const int64_t t = blockIdx.x;
+  const int64_t w0 = t * a.ksteps, w1 = w0 + a.ksteps;
+  int p_lo = (int)((w0 * a.grid) / a.rem_work);
+  while (p_lo + 1 < a.grid && work_begin(a.rem_work, a.grid, p_lo + 1) <= w0) ++p_lo;
+  while (p_lo > 0 && work_begin(a.rem_work, a.grid, p_lo) > w0) --p_lo;
+  if (work_begin(a.rem_work, a.grid, p_lo + 1) >= w1) return;   // one workgroup owned the whole tile
+  int p_hi = p_lo;
+  while (p_hi + 1 < a.grid && work_begin(a.rem_work, a.grid, p_hi + 1) < w1) ++p_hi;
+
+  int mblk, n_tile;
+  tile_coords((int64_t)a.rounds * a.grid + t, a.m_blocks, a.n_tiles, mblk, n_tile);
+  const int rows_t = mt16 * 16;
+  const int m0 = mblk * rows_t;
+  const int64_t slot = (int64_t)rows_t * kBN;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l16 = lane & 15, g4 = lane >> 4;
+  const int n_items = mt16 * 4;
+  float4 v[kFinishItems];
+#pragma unroll
+  for (int i = 0; i < kFinishItems; ++i) v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  int p = p_lo;
+  while (p <= p_hi) {
+    const float4* src[kFinishParts];
+    int n = 0;
+    for (; p <= p_hi && n < kFinishParts; ++p) {
+      const int64_t pb = work_begin(a.rem_work, a.grid, p);
+      if (work_begin(a.rem_work, a.grid, p + 1) == pb) continue;
+      const int s = pb >= w0 ? 0 : 1;
+      src[n++] = reinterpret_cast<const float4*>(a.partial + ((int64_t)p * 2 + s) * slot) + tid;
+    }
+    float4 x[kFinishParts][kFinishItems];
+#pragma unroll
+    for (int c = 0; c < kFinishParts; ++c)
+#pragma unroll
+      for (int i = 0; i < kFinishItems; ++i) {
+        const int e = blockIdx.y + i * gridDim.y;
+        x[c][i] = (c < n && e < n_items) ? src[c < n ? c : 0][(int64_t)e * 256] : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+    for (int c = 0; c < kFinishParts; ++c)
+      if (c < n) {
+#pragma unroll
+        for (int i = 0; i < kFinishItems; ++i) {
+          v[i].x += x[c][i].x;
+          v[i].y += x[c][i].y;
+          v[i].z += x[c][i].z;
+          v[i].w += x[c][i].w;
+        }
+      }
+  }
+#pragma unroll
+  for (int i = 0; i < kFinishItems; ++i) {
+    const int e = blockIdx.y + i * gridDim.y;
+    if (e >= n_items) break;
+    const int m = e >> 2, ct = e & 3;
+    const int row0 = m0 + 16 * m + 4 * g4;
+    const int col = n_tile * kBN + wave * 64 + ct * 16 + l16;
+    if (col >= a.N) continue;
+    const float o[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+    const float bvv = a.bias ? (float)a.bias[col] : 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int row = row0 + r;
+      if (row >= a.M || row >= m0 + rows_t) break;
+      float x = o[r] + bvv;
+      if (a.relu) x = fmaxf(x, 0.f);
+      if (a.residual) x += (float)a.residual[(int64_t)row * a.ldr + col];
+      if (a.out32)
+        a.out32[(int64_t)row * a.ldo + col] = x;
+      else
+        a.out16[(int64_t)row * a.ldo + col] = (half_t)x;
+    }
+  }
+}
+
 // canonical [N][K/2] codes + [N][K/64] meta  ->  tiled: one thread per 16-byte piece
 template <class PairT>   // float2, or uint32_t for a pair of FP16 numbers
 __global__ __launch_bounds__(256) void pack_weights_kernel(const uint8_t* __restrict__ codes,
@@ -646,6 +1069,21 @@ int launch_t(const StreamArgs& a, hipStream_t stream) {
   return FG_OK;
 }
 
+template <int MT16, bool H16M>
+int launch_dec16(const StreamArgs& a, hipStream_t stream) {
+  using C = Dec16Cfg<MT16, H16M>;
+  const size_t smem = (size_t)C::kNST * C::kStageBytes;
+  static bool attr_done = false;
+  if (!attr_done) {
+    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_decode16_kernel<MT16, H16M>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((gemm_decode16_kernel<MT16, H16M>), dim3(a.grid), dim3(256), smem, stream, a);
+  FG_LAUNCH_CHECK();
+  return FG_OK;
+}
+
 }  // namespace
 
 size_t gemm_stream_workspace(int64_t n, int64_t k, int64_t m) {
@@ -694,6 +1132,37 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
     if (rem_tiles > 0) {
       hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, finish_y(sh)), dim3(sh.nw * 64), 0, stream, a, sh.mt,
                          sh.nt, sh.wm);
+      FG_LAUNCH_CHECK();
+    }
+    return FG_OK;
+  }
+  // 4-bit weights, rows that fill an odd number of 16-row tiles (e.g. 144 = 9 x 16): the 16-row-tile
+  // kernel computes no padding rows, where the 32-row tiles would compute 16 of them
+  const int rows_blk = sh.rows() < (int)la.m ? (int)ceil_div(la.m, a.m_blocks) : (int)la.m;
+  const int mt16 = (int)ceil_div(rows_blk, 16);
+  if (la.dtype != FG_F16 && (mt16 & 1) && mt16 <= 9 && ceil_div(la.m, mt16 * 16) == a.m_blocks) {
+    const bool h16m = la.dtype == FG_Q4G64_H16_TILED;
+    {
+      ProfScope prof(FG_K_GEMM_SMALL_M, stream);
+      int rc = FG_ERR_UNSUPPORTED;
+#define FG_DEC16_CASE(MT)                                                                          \
+  case MT:                                                                                         \
+    rc = h16m ? launch_dec16<MT, true>(a, stream) : launch_dec16<MT, false>(a, stream);            \
+    break;
+      switch (mt16) {
+        FG_DEC16_CASE(1)
+        FG_DEC16_CASE(3)
+        FG_DEC16_CASE(5)
+        FG_DEC16_CASE(7)
+        FG_DEC16_CASE(9)
+      }
+#undef FG_DEC16_CASE
+      if (rc) return rc;
+    }
+    if (rem_tiles > 0) {
+      ProfScope prof(FG_K_GEMM_SMALL_M_FINISH, stream);
+      hipLaunchKernelGGL(gemm_decode16_finish_kernel, dim3((unsigned)rem_tiles, (unsigned)ceil_div(mt16 * 4, kFinishItems)),
+                         dim3(256), 0, stream, a, mt16);
       FG_LAUNCH_CHECK();
     }
     return FG_OK;
