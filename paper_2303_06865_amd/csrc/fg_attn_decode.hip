@@ -352,17 +352,18 @@ __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
         *reinterpret_cast<const u4_t*>(a.q + (int64_t)seq * a.q_stride + head * DH + lane * 8);
   __syncthreads();
 
-  h8_t qop[4][NU];
+  // A operand: the query in rows 0, 4, 8, 12 of the 16 x 32 tile, zeros elsewhere.  Lane (n = l % 16,
+  // g = l / 16) of the result holds D[4g][n] in its first register, so with the query in all four of
+  // those rows every lane group g gets q . k_n of the 16 keys at hand; group g keeps the product of
+  // keys 16 g .. 16 g + 15, which leaves lane l the score of row l of the chunk.
+  h8_t qop[NU];
   {
     const int m = lane & 15;
 #pragma unroll
     for (int u = 0; u < NU; ++u) {
       const u4_t raw = *reinterpret_cast<const u4_t*>(my_q + 32 * u + 8 * q4);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const u4_t z = {0u, 0u, 0u, 0u};
-        qop[i][u] = __builtin_bit_cast(h8_t, (m == 4 * i) ? raw : z);
-      }
+      const u4_t z = {0u, 0u, 0u, 0u};
+      qop[u] = __builtin_bit_cast(h8_t, (m & 3) == 0 ? raw : z);
     }
   }
 
@@ -371,22 +372,40 @@ __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
 #pragma unroll
   for (int e = 0; e < 8 * NU; ++e) o[e] = 0.f;
 
-  for (int chunk = part; chunk < n_chunks; chunk += WPH) {
-    const int rbase = chunk << 6;
+  // Two register sets, one for a chunk's K rows and one for its V rows (16 KiB each at DH = 128).  The V
+  // rows of a chunk are requested before its scores are computed and the K rows of the wave's next
+  // chunk right after them, so a wave has 16 to 32 KiB on their way all the time instead of waiting
+  // out one load latency for K and another for V in every chunk.
+  h8_t kreg[4][NU], vreg[4][NU];
+  auto load_rows = [&](const half_t* base, int chunk, h8_t (&dst)[4][NU]) {
     const int64_t crow0 = chunk_row0(chunk);
-    const int last = n_rows - 1 - rbase;   // rows of the chunk past the end re-read its last valid row
-    f4_t acc = {0.f, 0.f, 0.f, 0.f};
+    const int last = n_rows - 1 - (chunk << 6);   // rows of the chunk past the end re-read its last valid row
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       int row = 16 * i + r;
       row = row < last ? row : last;
 #pragma unroll
-      for (int u = 0; u < NU; ++u) {
-        const h8_t kv = *reinterpret_cast<const h8_t*>(kp + (crow0 + row) * DH + 32 * u + 8 * q4);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qop[i][u], kv, acc, 0, 0, 0);
-      }
+      for (int u = 0; u < NU; ++u)
+        dst[i][u] = *reinterpret_cast<const h8_t*>(base + (crow0 + row) * DH + 32 * u + 8 * q4);
     }
-    const float sc = (rbase + lane) < n_rows ? acc[0] * a.scale : -INFINITY;
+  };
+  if (part < n_chunks) load_rows(kp, part, kreg);
+  for (int chunk = part; chunk < n_chunks; chunk += WPH) {
+    const int rbase = chunk << 6;
+    load_rows(vp, chunk, vreg);
+    __builtin_amdgcn_sched_barrier(0);
+    float sc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      f4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int u = 0; u < NU; ++u) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(qop[u], kreg[i][u], acc, 0, 0, 0);
+      sc = q4 == i ? acc[0] : sc;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (chunk + WPH < n_chunks) load_rows(kp, chunk + WPH, kreg);
+    __builtin_amdgcn_sched_barrier(0);
+    sc = (rbase + lane) < n_rows ? sc * a.scale : -INFINITY;
     const float cmax = wave_max(sc);
     const float m_new = fmaxf(m_run, cmax);
     if (m_new > m_run) {
@@ -400,14 +419,11 @@ __global__ __launch_bounds__(256) void attn_decode_f16_kernel(AttnArgs a) {
     l_run += p;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      int row = 16 * i + r;
-      row = row < last ? row : last;
       const float w = __shfl(p, 16 * i + r, 64);
 #pragma unroll
       for (int u = 0; u < NU; ++u) {
-        const h8_t vv = *reinterpret_cast<const h8_t*>(vp + (crow0 + row) * DH + 32 * u + 8 * q4);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) o[8 * u + e] += w * (float)vv[e];
+        for (int e = 0; e < 8; ++e) o[8 * u + e] += w * (float)vreg[i][u][e];
       }
     }
   }
