@@ -18,6 +18,7 @@ SOURCES = [
     "fg_gemm_small_m.hip",
     "fg_gemm_large_m.hip",
     "fg_gemm_stream.hip",
+    "fg_gemm_f16w.hip",
     "fg_attn_decode.hip",
     "fg_attn_topk.hip",
     "fg_attn_prefill.hip",

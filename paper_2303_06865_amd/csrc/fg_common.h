@@ -81,6 +81,10 @@ size_t gemm_small_m_workspace(int dtype, int64_t n, int64_t k, int64_t m);
 int gemm_small_m_launch(const LinearArgs& a, void* ws, size_t ws_bytes, hipStream_t stream);
 int gemm_large_m_launch(const LinearArgs& a, hipStream_t stream);
 // tiled 4-bit weights: weight-streaming kernel for few rows, and the repacking kernel
+// row-major FP16 weights, up to 128 rows (csrc/fg_gemm_f16w.hip); pick_cols returns 0 for shapes it does not take
+int gemm_f16w_pick_cols(int64_t n, int64_t k, int64_t m);
+size_t gemm_f16w_workspace(int64_t n, int64_t k, int64_t m);
+int gemm_f16w_launch(const LinearArgs& a, void* ws, size_t ws_bytes, hipStream_t stream);
 size_t gemm_stream_workspace(int64_t n, int64_t k, int64_t m);
 int gemm_stream_launch(const LinearArgs& a, void* ws, size_t ws_bytes, hipStream_t stream);
 int pack_weights_launch(const void* codes, const void* meta, bool meta_f16, int64_t n, int64_t k, void* codes_out, void* meta_out,

@@ -27,6 +27,7 @@
 //     in L2; the remaining tiles are cut stream-K fashion into equal contiguous ranges with a
 //     deterministic second-pass reduction.  The grid is always 256 workgroups, one per CU.
 #include "fg_common.h"
+#include "fg_async_lds.h"
 
 namespace fg {
 
@@ -62,9 +63,6 @@ struct StreamArgs {
   float* partial;       // [grid][2][block rows][256]
 };
 
-__device__ __forceinline__ int64_t work_begin(int64_t total, int grid, int p) { return (total * p) / grid; }
-__device__ __forceinline__ int swz(int row, int kc) { return kc ^ ((row >> 1) & 7); }
-
 // linear tile number -> (row block, column block): groups of kGroupM row blocks, inside a group the
 // row block runs fastest, so 32 consecutive tiles (one XCD's share of a round) form a patch of 4 row blocks x 8 column
 // blocks: per K step the 32 workgroups then fetch 4 activation tiles (32 KiB each) and 8 weight tiles
@@ -78,51 +76,6 @@ __device__ __forceinline__ void tile_coords(int64_t t, int m_blocks, int n_tiles
   mblk = first + r % gm;
   n_tile = r / gm;
 }
-
-typedef const __attribute__((address_space(1))) void* gptr_t;
-typedef __attribute__((address_space(3))) void* lptr_t;
-
-// The compiler orders every LDS read it can see behind ALL outstanding asynchronous global -> LDS
-// copies (it cannot tell which copy an address belongs to), which would drain the prefetch queue on
-// every step.  The stages are therefore read with hand-placed ds_read instructions; the explicit
-// vmcnt wait plus the barrier at the top of each step are what make the data visible.
-template <int OFF>
-__device__ __forceinline__ u4_t lds_read128(uint32_t addr) {
-  u4_t r;
-  __asm__ volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-  return r;
-}
-template <int OFF>
-__device__ __forceinline__ float2 lds_read64(uint32_t addr) {
-  float2 r;
-  __asm__ volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-  return r;
-}
-template <int OFF>
-__device__ __forceinline__ uint32_t lds_read32(uint32_t addr) {
-  uint32_t r;
-  __asm__ volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-  return r;
-}
-// all ds_reads issued so far have landed
-__device__ __forceinline__ void lds_wait() { __asm__ volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-// makes later uses of v depend on a point after the preceding lds_wait()
-template <class T>
-__device__ __forceinline__ void lds_landed(T& v) {
-  __asm__ volatile("" : "+v"(v));
-}
-template <int I>
-struct IdxC {
-  static constexpr int value = I;
-};
-template <int B, int E, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (B < E) {
-    f(IdxC<B>{});
-    static_for<B + 1, E>(f);
-  }
-}
-
 
 // F16W: the weights are plain row-major FP16 (no repacking needed: a [256 columns][64 k] block of W is
 // copied and read exactly like the activation tile) instead of tiled 4-bit codes.

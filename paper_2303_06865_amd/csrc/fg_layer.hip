@@ -129,13 +129,20 @@ static bool use_stream(int dtype, int64_t n, int64_t m) {
   return dtype == FG_F16 && m <= 320 && n % 32 == 0;
 }
 
+// Row-major FP16 weights with up to 128 rows: the narrow-tile weight streamer, where it takes the shape.
+static bool use_f16w(int dtype, int64_t n, int64_t k, int64_t m) {
+  return dtype == FG_F16 && use_stream(dtype, n, m) && gemm_f16w_pick_cols(n, k, m) != 0;
+}
+
 size_t linear_workspace_bytes(int dtype, int64_t n, int64_t k, int64_t m) {
+  if (use_f16w(dtype, n, k, m)) return gemm_f16w_workspace(n, k, m);
   if (use_stream(dtype, n, m)) return gemm_stream_workspace(n, k, m);
   if (m > kSmallMLimit) return 0;
   return gemm_small_m_workspace(dtype, n, k, m);
 }
 
 int linear_launch(const LinearArgs& a, void* ws, size_t ws_bytes, hipStream_t stream) {
+  if (use_f16w(a.dtype, a.n, a.k, a.m)) return gemm_f16w_launch(a, ws, ws_bytes, stream);
   if (use_stream(a.dtype, a.n, a.m)) return gemm_stream_launch(a, ws, ws_bytes, stream);
   if (a.m > kSmallMLimit) return gemm_large_m_launch(a, stream);
   return gemm_small_m_launch(a, ws, ws_bytes, stream);

@@ -185,6 +185,34 @@ def test_linear_small_m(m, n, k, bias, relu, residual, quant):
     assert_close(got, ref, "linear m=%d n=%d k=%d q=%s" % (m, n, k, quant))
 
 
+# Row-major FP16 weights with up to 128 rows take the narrow-tile weight streamer (csrc/fg_gemm_f16w.hip).
+# `cols` fixes its tile width (16 * cols columns; 0 = the library's own choice), so that every width is run
+# on whole tiles, on tiles split along K with the reduction pass, on more than one round of tiles, on
+# contractions shorter and longer than the copy ring, and on every row-tile count.
+F16W_CASES = [
+    # m, n, k, bias, relu, residual
+    (1, 192, 64, False, False, False),        # one K step, 3..12 tiles
+    (128, 768, 256, True, False, True),       # fewer (tile, K step) units than workgroups: empty ranges
+    (100, 1536, 1024, True, True, False),
+    (128, 12288, 256, False, False, True),    # 256 whole tiles of 48 columns; 3 rounds of 16; 192 split tiles of 64
+    (33, 3072, 2048, True, False, True),      # 32 K steps: longer than the 12-step weight ring
+    (64, 6144, 192, True, False, False),
+    (77, 6144, 448, False, True, True),       # three 32-row tiles, ragged
+    (17, 16384, 128, True, False, False),     # 1024 tiles of 16: four whole rounds
+]
+
+
+@pytest.mark.parametrize("cols", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("m,n,k,bias,relu,residual", F16W_CASES)
+def test_linear_f16_weights_narrow_tiles(m, n, k, bias, relu, residual, cols, monkeypatch):
+    if cols:
+        monkeypatch.setenv("FG_F16W_COLS", str(cols))
+    else:
+        monkeypatch.delenv("FG_F16W_COLS", raising=False)
+    got, ref = _linear_case(m, n, k, False, bias, relu, residual, seed=m + n + k + cols)
+    assert_close(got, ref, "linear f16w m=%d n=%d k=%d cols=%d" % (m, n, k, cols))
+
+
 @pytest.mark.parametrize("quant", [True, False])
 @pytest.mark.parametrize("m,n,k,bias,relu,residual", [
     (600, 768, 768, True, False, True),
