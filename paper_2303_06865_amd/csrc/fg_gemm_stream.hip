@@ -567,6 +567,13 @@ __device__ __forceinline__ void mfma16_inplace(f4_t& acc, const h8_t& a, const h
   __asm__ volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 
+// The same with the accumulator in an ordinary vector register: a kernel with two waves per SIMD has 256
+// registers per lane in all, of either kind, and keeping the accumulators among the ordinary ones spares
+// it every move between the two files where the sums are finished.
+__device__ __forceinline__ void mfma16_inplace_v(f4_t& acc, const h8_t& a, const h8_t& b) {
+  __asm__ volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+
 template <int MT16, bool H16M>
 struct Dec16Cfg {
   static constexpr int kMT32 = (MT16 + 1) / 2;
@@ -887,6 +894,360 @@ __global__ __launch_bounds__(256) void gemm_decode16_kernel(StreamArgs a) {
   __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
+// One half of d = nearest FP16 of (FP16 half SEL of x) * s + b, computed in FP32 with a single rounding; the
+// other half of d is kept.  Written as instructions so that the two halves of an operand register can be
+// produced in different gaps between MFMAs (the compiler would merge separately computed halves with
+// extra moves), and, being volatile, they stay where they are written.
+template <int SEL>
+__device__ __forceinline__ void fma_mixlo(uint32_t& d, uint32_t x, float s, float b) {
+  // (output only: the high half of d is whatever it was, and the caller overwrites it next)
+  if constexpr (SEL == 0)
+    __asm__ volatile("v_fma_mixlo_f16 %0, %1, %2, %3 op_sel_hi:[1,0,0]" : "=v"(d) : "v"(x), "v"(s), "v"(b));
+  else
+    __asm__ volatile("v_fma_mixlo_f16 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(x), "v"(s), "v"(b));
+}
+template <int SEL>
+__device__ __forceinline__ void fma_mixhi(uint32_t& d, uint32_t x, float s, float b) {
+  if constexpr (SEL == 0)
+    __asm__ volatile("v_fma_mixhi_f16 %0, %1, %2, %3 op_sel_hi:[1,0,0]" : "+v"(d) : "v"(x), "v"(s), "v"(b));
+  else
+    __asm__ volatile("v_fma_mixhi_f16 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(d) : "v"(x), "v"(s), "v"(b));
+}
+
+// pieces [spread7(i, n), spread7(i + 1, n)) of seven go behind item i of n (none behind items >= n)
+constexpr int spread7(int i, int n) { return i * 7 / n > 7 ? 7 : i * 7 / n; }
+
+// The same tiles on eight waves, two per SIMD.  Measured on the four-wave kernel above, everything that is
+// not an MFMA adds to the time instead of hiding behind the matrix pipe (per 144 x 36864 launch: MFMAs
+// alone 79 us of 177; the exact dequantization +41, the operand reads +24, the copies +34, the barrier
+// +12): a wave issues in order, and a 16-cycle MFMA covers only four to eight cycles of the same wave's
+// other work.  Here wave w = (column group w & 3, K slice w >> 2): the two waves of a SIMD work on the two
+// 32-wide K slices of the same 64 columns, so nothing is read or dequantized twice, each wave's 36 MFMAs
+// per step fall into four groups of nine (one column tile each) with the next column tile's
+// dequantization spread one or two instructions per MFMA between them, and one wave's waits (LDS,
+// copies, barrier) are the other wave's matrix time.  The activation operands are single-buffered: a
+// row tile's register is reloaded for the next step right after its last MFMA of this step.  The two
+// K-slice sums of a column group are added through LDS once per tile segment (each wave finishes two of
+// the four column tiles), so the partial-sum layout and the reduction pass are those of the kernel above.
+template <int MT16, bool H16M>
+__global__ __launch_bounds__(512) void gemm_decode16x2_kernel(StreamArgs a) {
+  using C = Dec16Cfg<MT16, H16M>;
+  constexpr int kAStage = C::kAStage, kStageBytes = C::kStageBytes, kNST = C::kNST;
+  constexpr int kPieces = C::kRowsLds / 8;                          // 8-row activation pieces per stage
+  constexpr int kAC0 = (kPieces + 7) / 8, kAC1 = kPieces / 8;       // activation copies per step: waves 0..3, waves 4..7
+  constexpr int kDqSpan = MT16 > 2 ? MT16 - 2 : 1;
+  static_assert(MT16 * 16 * 1024 <= kNST * kStageBytes, "the exchange of the K-slice sums needs 16 KiB per row tile");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int cg = wave & 3, sl = wave >> 2;
+  const int l16 = lane & 15, g4 = lane >> 4;
+
+  const int p = (blockIdx.x & 7) * (a.grid >> 3) + (blockIdx.x >> 3);
+  const int64_t rem_begin = work_begin(a.rem_work, a.grid, p), rem_end = work_begin(a.rem_work, a.grid, p + 1);
+  int64_t pos = rem_begin;
+  int round = 0, seg = 0;
+
+  // operand read offsets inside a stage (see the kernel above), for this wave's K slice
+  const int a_off = (l16 * kKS + swz(l16, 4 * sl + g4) * 8) * 2;
+  const int bq_off = kAStage + cg * 2 * 1024 + l16 * 16 + g4 * 4 + sl * 512;
+  const int bm_off = kAStage + 8 * 1024 + cg * 2 * 256 + l16 * (H16M ? 4 : 8);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
+
+  while (round < a.rounds || pos < rem_end) {
+    int64_t tile;
+    int ks0, ks1;
+    const bool whole_round = round < a.rounds;
+    if (whole_round) {
+      tile = (int64_t)round * a.grid + p;
+      ks0 = 0;
+      ks1 = a.ksteps;
+    } else {
+      const int64_t t = pos / a.ksteps;
+      tile = (int64_t)a.rounds * a.grid + t;
+      ks0 = (int)(pos - t * a.ksteps);
+      const int64_t left = rem_end - pos;
+      ks1 = (int)((int64_t)(a.ksteps - ks0) < left ? a.ksteps : ks0 + left);
+    }
+    int mblk, n_tile;
+    tile_coords(tile, a.m_blocks, a.n_tiles, mblk, n_tile);
+    const int m0 = mblk * C::kRows;
+    const int nt0 = n_tile * 8 + cg * 2;   // first 32-column tile of this wave's column group
+
+    f4_t acc[MT16][4];
+#pragma unroll
+    for (int m = 0; m < MT16; ++m)
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) acc[m][ct] = (f4_t){0.f, 0.f, 0.f, 0.f};
+
+    // this wave's copies per step: activation pieces wave, wave + 8, (wave + 16), and weight tile `wave`
+    // of the block's eight (codes + {min, scale})
+    const half_t* a_src[kAC0];
+#pragma unroll
+    for (int i = 0; i < kAC0; ++i) {
+      const int prow = 8 * (wave + 8 * i) + (lane >> 3);
+      int row = m0 + prow;
+      row = row < a.M ? row : a.M - 1;
+      a_src[i] = a.x + (int64_t)row * a.ldx + swz(prow, lane & 7) * 8;
+    }
+    const uint8_t* w_src;
+    const float* m_src;
+    {
+      int nt = n_tile * 8 + wave;
+      nt = nt < a.n32 ? nt : a.n32 - 1;   // ragged last column block: load valid data, never store it
+      w_src = a.w + (int64_t)nt * a.ksteps * 1024 + lane * 16;
+      m_src = reinterpret_cast<const float*>(a.meta) +
+              (H16M ? (int64_t)nt * a.ksteps * 32 + (lane & 31) : (int64_t)nt * a.ksteps * 64 + lane);
+    }
+    // copy number c (0 .. kAC0 + 1) of a step; waves 4..7 have no activation piece number kAC1 where
+    // the pieces do not divide by eight
+    auto copy_one = [&](int c, int ks, int stage) {
+      const int kc = ks < ks1 ? ks : ks1 - 1;   // past the end the last step is fetched again
+      unsigned char* st = smem + stage * kStageBytes;
+      if (c < kAC0) {
+        if (c < kAC1 || wave < 4)
+          __builtin_amdgcn_global_load_lds((gptr_t)(a_src[c] + kc * kKS), (lptr_t)(st + (wave + 8 * c) * 8 * kKS * 2), 16, 0, 0);
+      } else if (c == kAC0) {
+        __builtin_amdgcn_global_load_lds((gptr_t)(w_src + (int64_t)kc * 1024), (lptr_t)(st + kAStage + wave * 1024), 16, 0, 0);
+      } else {
+        __builtin_amdgcn_global_load_lds((gptr_t)(m_src + (int64_t)kc * (H16M ? 32 : 64)),
+                                         (lptr_t)(st + kAStage + 8 * 1024 + wave * 256), 4, 0, 0);
+      }
+    };
+    constexpr int kCopies = kAC0 + 2;
+    // this wave's copies have landed, all but those of the newest N steps
+    auto wait_steps = [&](auto N_) {
+      constexpr int n = decltype(N_)::value;
+      if (kAC0 == kAC1 || wave < 4)
+        __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"(n * (kAC0 + 2)) : "memory");
+      else
+        __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"(n * (kAC1 + 2)) : "memory");
+    };
+
+    h8_t aop[MT16];
+    u4_t bop[2];           // B operands of two column tiles in turn
+    uint32_t cw[4];        // this wave's code words of the step, one per column tile
+    float2 cm[4];
+    uint32_t cmh[4];
+    auto read_a_tile = [&](uint32_t st, auto M_) __attribute__((always_inline)) {
+      constexpr int m = decltype(M_)::value;
+      aop[m] = __builtin_bit_cast(h8_t, lds_read128<m * 16 * kKS * 2>(st + a_off));
+    };
+    auto read_b = [&](uint32_t st) {
+      static_for<0, 4>([&](auto CT) __attribute__((always_inline)) {
+        constexpr int ct = decltype(CT)::value;
+        constexpr int qoff = (ct >> 1) * 1024 + (ct & 1) * 256;
+        cw[ct] = lds_read32<qoff>(st + bq_off);
+        constexpr int moff = (ct >> 1) * 256 + (ct & 1) * 16 * (H16M ? 4 : 8);
+        if constexpr (H16M) cmh[ct] = lds_read32<moff>(st + bm_off); else cm[ct] = lds_read64<moff>(st + bm_off);
+      });
+    };
+    auto landed_b = [&]() {
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        lds_landed(cw[ct]);
+        if constexpr (H16M) lds_landed(cmh[ct]); else lds_landed(cm[ct]);
+      }
+    };
+    // Exact dequantization of column tile ct's code word into bop[ct & 1] in seven pieces of two or
+    // three VALU instructions (0: FMA constants, 1 and 2: nibble masks, 3..6: two weights each into two
+    // different registers), every piece pinned where it is written (see dq_piece above).
+    float s24, s20, mn;
+    uint32_t msk[4], r01[2];
+    auto dq7 = [&](int ct, int piece) {
+      if (piece == 0) {
+        float2 m2 = cm[ct];
+        if constexpr (H16M) {
+          const h2_t pr = __builtin_bit_cast(h2_t, cmh[ct]);
+          m2.x = (float)pr.x;
+          m2.y = (float)pr.y;
+        }
+        s24 = m2.y * 16777216.0f;
+        s20 = m2.y * 1048576.0f;
+        mn = m2.x;
+        __asm__ volatile("" : "+v"(s24), "+v"(s20), "+v"(mn));
+      } else if (piece == 1) {
+        msk[0] = cw[ct] & 0x000F000Fu;
+        msk[1] = cw[ct] & 0x00F000F0u;
+        __asm__ volatile("" : "+v"(msk[0]), "+v"(msk[1]));
+      } else if (piece == 2) {
+        const uint32_t y = cw[ct] >> 8;
+        msk[2] = y & 0x000F000Fu;
+        msk[3] = y & 0x00F000F0u;
+        __asm__ volatile("" : "+v"(msk[2]), "+v"(msk[3]));
+      } else if (piece == 3) {   // weights 0 and 2: low halves of operand registers 0 and 1
+        fma_mixlo<0>(r01[0], msk[0], s24, mn);
+        fma_mixlo<0>(r01[1], msk[2], s24, mn);
+      } else if (piece == 4) {   // weights 1 and 3: high halves; registers 0 and 1 are complete
+        fma_mixhi<0>(r01[0], msk[1], s20, mn);
+        fma_mixhi<0>(r01[1], msk[3], s20, mn);
+        bop[ct & 1][0] = r01[0];
+        bop[ct & 1][1] = r01[1];
+      } else if (piece == 5) {   // weights 4 and 6
+        fma_mixlo<1>(r01[0], msk[0], s24, mn);
+        fma_mixlo<1>(r01[1], msk[2], s24, mn);
+      } else {                   // weights 5 and 7; registers 2 and 3 are complete
+        fma_mixhi<1>(r01[0], msk[1], s20, mn);
+        fma_mixhi<1>(r01[1], msk[3], s20, mn);
+        bop[ct & 1][2] = r01[0];
+        bop[ct & 1][3] = r01[1];
+      }
+    };
+
+    __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < kNST; ++t)
+#pragma unroll
+      for (int c = 0; c < kCopies; ++c) copy_one(c, ks0 + t, t);
+    wait_steps(IdxC<kNST - 1>{});   // step ks0 has landed
+    __builtin_amdgcn_s_barrier();
+    static_for<0, MT16>([&](auto M_) __attribute__((always_inline)) { read_a_tile(lds0, M_); });
+    read_b(lds0);
+    lds_wait();
+    landed_b();
+#pragma unroll
+    for (int q = 0; q < 7; ++q) dq7(0, q);
+
+    int stage = 0;
+    for (int ks = ks0; ks < ks1; ++ks) {
+      const int stage1 = stage + 1 == kNST ? 0 : stage + 1;
+      const uint32_t Nt = lds0 + stage1 * kStageBytes;
+      lds_wait();   // the activation operands of this step, requested during the last step
+#pragma unroll
+      for (int m = 0; m < MT16; ++m) lds_landed(aop[m]);
+      __builtin_amdgcn_sched_barrier(0);
+      // ---- column tiles 0, 1, 2: MFMAs with the dequantization of the next column tile between them
+      static_for<0, 3 * MT16>([&](auto I) __attribute__((always_inline)) {
+        constexpr int i = decltype(I)::value;
+        constexpr int ct = i / MT16, m = i - ct * MT16;
+        mfma16_inplace_v(acc[m][ct], aop[m], __builtin_bit_cast(h8_t, bop[ct & 1]));
+        __builtin_amdgcn_sched_barrier(0);
+        // seven pieces over the first MT16 - 2 MFMAs of the group: the last two MFMAs separate the
+        // last register write from the first MFMA that reads it
+        static_for<spread7(m, kDqSpan), spread7(m + 1, kDqSpan)>(
+            [&](auto Q) __attribute__((always_inline)) { dq7(ct + 1, decltype(Q)::value); });
+        if constexpr (MT16 < 3 && m == MT16 - 1) __asm__ volatile("s_nop 3");
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      // every wave's copies of step ks + 1 have landed, and nobody reads the stage of step ks any more
+      wait_steps(IdxC<kNST - 2>{});
+      __builtin_amdgcn_s_barrier();   // bare barrier: no fence, the copies in flight stay in flight
+      __builtin_amdgcn_sched_barrier(0);
+      // ---- column tile 3: the next step's code words and {min, scale} first, its copies between the
+      // first MFMAs, then the reloads of the activation operands and the dequantization of the next
+      // step's column tile 0
+      read_b(Nt);
+      __builtin_amdgcn_sched_barrier(0);
+      constexpr int kH = MT16 / 2;   // MFMAs before the wait for the code words
+      static_for<0, MT16>([&](auto M_) __attribute__((always_inline)) {
+        constexpr int m = decltype(M_)::value;
+        mfma16_inplace_v(acc[m][3], aop[m], __builtin_bit_cast(h8_t, bop[1]));
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (m < kH || MT16 == 1) {
+          static_for<m * kCopies / (kH > 0 ? kH : 1), (MT16 == 1 ? kCopies : (m + 1) * kCopies / kH)>(
+              [&](auto CC) __attribute__((always_inline)) { copy_one(decltype(CC)::value, ks + kNST, stage); });
+        }
+        if constexpr (m == kH || MT16 == 1) {
+          lds_wait();
+          landed_b();
+          static_for<0, (MT16 == 1 ? 1 : kH + 1)>([&](auto R_) __attribute__((always_inline)) { read_a_tile(Nt, R_); });
+        }
+        if constexpr (m > kH) read_a_tile(Nt, M_);
+        if constexpr (MT16 == 1) {
+          static_for<0, 7>([&](auto Q) __attribute__((always_inline)) { dq7(0, decltype(Q)::value); });
+          __asm__ volatile("s_nop 3");
+        } else if constexpr (m >= kH && m < MT16 - 1) {
+          constexpr int r = m - kH, n2 = MT16 - 1 - kH;
+          static_for<r * 7 / n2, (r + 1) * 7 / n2>([&](auto Q) __attribute__((always_inline)) { dq7(0, decltype(Q)::value); });
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      stage = stage1;
+    }
+
+    // The MFMAs are opaque instructions to the compiler: wait out the last of them (16 cycles each)
+    // before the accumulators are read.
+    __asm__ volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+    for (int m = 0; m < MT16; ++m)
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) __asm__ volatile("" : "+v"(acc[m][ct]));
+    // ---- the two K-slice sums of a column group meet in LDS: the wave of slice 1 hands over column
+    // tiles 0 and 1, the wave of slice 0 column tiles 2 and 3, and each finishes the two it keeps
+    lds_wait();
+    __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    float4* xb = reinterpret_cast<float4*>(smem);
+    // (the accumulator array is only ever indexed with constants: each K slice has its own copy of the code)
+    auto hand_over = [&](auto SL_) __attribute__((always_inline)) {
+      constexpr int give = decltype(SL_)::value == 0 ? 2 : 0;
+#pragma unroll
+      for (int m = 0; m < MT16; ++m)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const f4_t v = acc[m][give + c];
+          xb[(wave * (MT16 * 2) + m * 2 + c) * 64 + lane] = make_float4(v[0], v[1], v[2], v[3]);
+          __builtin_amdgcn_sched_barrier(0);   // one tile at a time: this code must not raise the kernel's register count
+        }
+    };
+    const bool full = (ks0 == 0) && (ks1 == a.ksteps);
+    // adds the partner's sums to the two column tiles this wave keeps and stores them: lane holds
+    // column l16, rows 4 g4 + 0..3 of each 16 x 16 tile
+    auto finish_kept = [&](auto SL_) __attribute__((always_inline)) {
+      constexpr int keep = decltype(SL_)::value == 0 ? 0 : 2;
+      const int partner = wave ^ 4;
+      float4* pdst = reinterpret_cast<float4*>(a.partial + ((int64_t)p * 2 + (seg == 0 ? 0 : 1)) * ((int64_t)C::kRows * kBN)) +
+                     (cg * 64 + lane);
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        constexpr int dummy = 0;
+        (void)dummy;
+        const int ct = keep + c;
+        const int col = (nt0 + (ct >> 1)) * 32 + (ct & 1) * 16 + l16;
+        const bool col_ok = nt0 + (ct >> 1) < a.n32;
+        const float bvv = (full && col_ok && a.bias) ? (float)a.bias[col] : 0.f;
+#pragma unroll
+        for (int m = 0; m < MT16; ++m) {
+          const float4 o = xb[(partner * (MT16 * 2) + m * 2 + c) * 64 + lane];
+          const f4_t mine = acc[m][keep + c];
+          const float v4[4] = {mine[0] + o.x, mine[1] + o.y, mine[2] + o.z, mine[3] + o.w};
+          if (!full) {
+            // partial sums in the order of the four-wave kernel: float4 number (m * 4 + ct) of thread cg * 64 + lane
+            pdst[(m * 4 + ct) * 256] = make_float4(v4[0], v4[1], v4[2], v4[3]);
+          } else if (col_ok) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const int row = m0 + 16 * m + 4 * g4 + r;
+              if (row < a.M && row < m0 + C::kRows) {
+                float v = v4[r] + bvv;
+                if (a.relu) v = fmaxf(v, 0.f);
+                if (a.residual) v += (float)a.residual[(int64_t)row * a.ldr + col];
+                if (a.out32)
+                  a.out32[(int64_t)row * a.ldo + col] = v;
+                else
+                  a.out16[(int64_t)row * a.ldo + col] = (half_t)v;
+              }
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    };
+    if (sl == 0) hand_over(IdxC<0>{}); else hand_over(IdxC<1>{});
+    __syncthreads();
+    if (sl == 0) finish_kept(IdxC<0>{}); else finish_kept(IdxC<1>{});
+    if (whole_round) {
+      ++round;
+    } else {
+      pos += ks1 - ks0;
+      ++seg;
+    }
+  }
+  __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
 // Reduction pass for gemm_decode16_kernel: thread tid of a block adds, in ascending K order, the float4s
 // that thread tid of the contributing workgroups wrote, then applies the epilogue.  blockIdx.x counts the
 // tiles after the whole rounds, blockIdx.y spreads a thread's MT16 * 4 items.
@@ -1022,17 +1383,30 @@ int launch_t(const StreamArgs& a, hipStream_t stream) {
   return FG_OK;
 }
 
+// Eight waves from five row tiles up (measured against four waves in one run, 144 rows: QKV 162-167 vs
+// 176-178 us, FFN1 210-218 vs 225-229, FFN2 219-221 vs 227-230; 112 rows 135-144 vs 151; level at 48 rows,
+// 3-7 % slower at 4 and 16 rows, where a wave has too few MFMAs per step to spread anything between).
 template <int MT16, bool H16M>
 int launch_dec16(const StreamArgs& a, hipStream_t stream) {
   using C = Dec16Cfg<MT16, H16M>;
   const size_t smem = (size_t)C::kNST * C::kStageBytes;
+  constexpr bool kEight = MT16 >= 5;
   static bool attr_done = false;
-  if (!attr_done) {
-    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_decode16_kernel<MT16, H16M>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    attr_done = true;
+  if constexpr (kEight) {
+    if (!attr_done) {
+      FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_decode16x2_kernel<MT16, H16M>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      attr_done = true;
+    }
+    hipLaunchKernelGGL((gemm_decode16x2_kernel<MT16, H16M>), dim3(a.grid), dim3(512), smem, stream, a);
+  } else {
+    if (!attr_done) {
+      FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_decode16_kernel<MT16, H16M>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      attr_done = true;
+    }
+    hipLaunchKernelGGL((gemm_decode16_kernel<MT16, H16M>), dim3(a.grid), dim3(256), smem, stream, a);
   }
-  hipLaunchKernelGGL((gemm_decode16_kernel<MT16, H16M>), dim3(a.grid), dim3(256), smem, stream, a);
   FG_LAUNCH_CHECK();
   return FG_OK;
 }
