@@ -1463,11 +1463,13 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
     }
     return FG_OK;
   }
-  // 4-bit weights, rows that fill an odd number of 16-row tiles (e.g. 144 = 9 x 16): the 16-row-tile
-  // kernel computes no padding rows, where the 32-row tiles would compute 16 of them
+  // 4-bit weights on 16-row tiles: where the rows fill an odd number of them (e.g. 144 = 9 x 16) the
+  // 32-row tiles would compute 16 padding rows, and from six tiles up the eight-wave kernel is the faster
+  // one at even counts too (measured in one run, 128 rows: 55-71 vs 56-73 us on the OPT-30B shapes, 150
+  // vs 160 us at 36864 x 12288; two blocks of 128: 97-101 vs 106-109 us)
   const int rows_blk = sh.rows() < (int)la.m ? (int)ceil_div(la.m, a.m_blocks) : (int)la.m;
   const int mt16 = (int)ceil_div(rows_blk, 16);
-  if (la.dtype != FG_F16 && (mt16 & 1) && mt16 <= 9 && ceil_div(la.m, mt16 * 16) == a.m_blocks) {
+  if (la.dtype != FG_F16 && ((mt16 & 1) || mt16 >= 6) && mt16 <= 9 && ceil_div(la.m, mt16 * 16) == a.m_blocks) {
     const bool h16m = la.dtype == FG_Q4G64_H16_TILED;
     {
       ProfScope prof(FG_K_GEMM_SMALL_M, stream);
@@ -1480,7 +1482,9 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
         FG_DEC16_CASE(1)
         FG_DEC16_CASE(3)
         FG_DEC16_CASE(5)
+        FG_DEC16_CASE(6)
         FG_DEC16_CASE(7)
+        FG_DEC16_CASE(8)
         FG_DEC16_CASE(9)
       }
 #undef FG_DEC16_CASE

@@ -233,7 +233,10 @@ TILED_CASES = [
     (36, 992, 832, True, False, True),       # ragged column block (992 = 31 tiles of 32)
     (48, 288, 192, False, True, False),
     (70, 512, 640, True, True, True),        # five 16-row tiles
+    (96, 512, 640, True, False, True),       # six 16-row tiles (eight-wave kernel at an even count)
     (100, 544, 1024, True, False, False),
+    (128, 1280, 512, False, True, False),    # eight 16-row tiles
+    (250, 768, 256, True, False, True),      # two blocks of eight 16-row tiles, ragged
     (112, 36864, 256, False, False, True),   # 144 whole tiles of seven 16-row tiles: no reduction pass at all
     (144, 1024, 12288, True, False, True),   # 4 tiles over 256 workgroups: 64 contributors per tile in the reduction pass
     (288, 1280, 512, True, False, True),     # two row blocks of nine 16-row tiles
