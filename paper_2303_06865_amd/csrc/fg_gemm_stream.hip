@@ -92,7 +92,9 @@ struct StreamCfg {
   static constexpr int kCopies = kACopies + kBCopies;
   static_assert(kWN * NT == 8, "a workgroup covers 8 column tiles of 32");
   static_assert(kACopies * 8 * NW == kRows, "activation rows must split evenly over the waves");
-  static_assert(kNST >= 3, "needs three stages");
+  // (two stages: the 256 x 256 tile pair of FP16 weights, 64 KiB per stage; its operands come from L2,
+  // one K step of look-ahead covers that)
+  static_assert(kNST >= 2, "needs two stages");
 };
 
 // H16M: the {min, scale} pairs of the tiled 4-bit weights are two FP16 numbers (4 bytes) instead of two
@@ -1452,9 +1454,10 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   if (!ws || ws_bytes < need) return FG_ERR_WORKSPACE;
   if (sh.nw == 8) {   // prefill shape: GEMM and reduction of the last partial round are one profile record
     ProfScope prof(FG_K_GEMM_LARGE_M, stream);
-    if (la.dtype != FG_Q4G64_TILED && la.dtype != FG_Q4G64_H16_TILED) return FG_ERR_UNSUPPORTED;
-    const int rc = la.dtype == FG_Q4G64_H16_TILED ? launch_t<8, 1, 1, 8, false, true>(a, stream)
-                                                  : launch_t<8, 1, 1, 8, false>(a, stream);
+    if (la.dtype != FG_Q4G64_TILED && la.dtype != FG_Q4G64_H16_TILED && la.dtype != FG_F16) return FG_ERR_UNSUPPORTED;
+    const int rc = la.dtype == FG_F16               ? launch_t<8, 1, 1, 8, true>(a, stream)
+                   : la.dtype == FG_Q4G64_H16_TILED ? launch_t<8, 1, 1, 8, false, true>(a, stream)
+                                                    : launch_t<8, 1, 1, 8, false>(a, stream);
     if (rc) return rc;
     if (rem_tiles > 0) {
       hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, finish_y(sh)), dim3(sh.nw * 64), 0, stream, a, sh.mt,
