@@ -35,7 +35,8 @@ def _sample(n, edges, k, seed):
 
 
 # (rows, out features, in features, quantized): the four projection shapes of the OPT-175B workload in
-# the decode phase (144 rows) and in the prefill phase (36 x 512 rows), and the FP16 LM head
+# the decode phase (144 rows) and in the prefill phase (36 x 512 rows), the FP16 LM head, and (below) the
+# uncompressed workload's shapes
 FULL_LINEAR = [
     (144, 36864, 12288, True),
     (144, 12288, 49152, True),
@@ -45,6 +46,14 @@ FULL_LINEAR = [
     (144, 50272, 12288, False),
     (144, 36864, 12288, "h16"),      # 4-bit weights with FP16 {min, scale} pairs
     (18432, 12288, 49152, "h16"),
+    # the uncompressed workload (OPT-6.7B, FP16 weights, 4 x 32 sequences): decode projections (128 rows:
+    # whole tiles of 48, 16 and 64 columns, and 64-column tiles split along K) and two prefill projections
+    (128, 12288, 4096, False),
+    (128, 4096, 4096, False),
+    (128, 16384, 4096, False),
+    (128, 4096, 16384, False),
+    (16384, 12288, 4096, False),
+    (16384, 4096, 16384, False),
 ]
 
 
