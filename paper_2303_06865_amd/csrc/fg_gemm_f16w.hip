@@ -10,9 +10,10 @@
 //     256 of 64; 4096 x 4096: 256 of 16): every CU then owns one tile over the whole contraction, nothing
 //     is split along K, no partial sums are written and no reduction pass runs.  Narrow tiles have a
 //     price: every workgroup pulls the whole activation block through its L1 (rows / BN times the bytes
-//     of its weights), so for a long contraction (4096 x 16384) wider tiles cut stream-K fashion into
-//     256 equal ranges, with a small deterministic reduction pass, are cheaper; the choice is made with a
-//     two-term cost model (L1 bytes per CU against HBM time, plus the reduction pass).
+//     of its weights), and a CU takes in only 45..55 GB/s of asynchronous copies; so for a long
+//     contraction (4096 x 16384) wider tiles cut stream-K fashion into 256 equal ranges, with a small
+//     deterministic reduction pass, are cheaper, and long ragged matrices (an LM head) stay on the
+//     256-column kernel.  The choice is made with a cost model fitted to measurements (pick_cols).
 //   * Both operands are [rows][64 k] tiles of 128-byte rows, copied global -> LDS asynchronously and
 //     read back as MFMA operands with one ds_read_b128 each (XOR swizzle, conflict-free).  The weight
 //     tiles, which come from HBM, sit in a ring of up to 10 K steps; the activation tiles, which come
