@@ -1250,6 +1250,328 @@ __global__ __launch_bounds__(512) void gemm_decode16x2_kernel(StreamArgs a) {
   __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
+// ---------------------------------------------------------------------------------------------
+// Prefill shape on v_mfma_f32_16x16x32_f16.  With random operands the chip is limited by power, not by
+// issue slots, and the 16 x 16 x 32 instruction delivers more flops per joule than the 32 x 32 x 16 one
+// (MFMAs alone, random FP16 operands, every CU busy: 1.88 against 1.62 PFLOP/s), so the 256 x 256 tile of
+// the prefill projections is computed on the small shape.
+//   Wave w of eight: all 256 rows (16 row tiles) x the 32 columns of weight tile w (two column tiles of 16):
+//   32 accumulators of four registers, kept in ordinary vector registers and updated in place.
+//   Activations: three stages of 32 KiB, copied by all waves, one barrier per K step (as in the kernel
+//   above).  Weights: a wave copies, reads and dequantizes only its own tile, so its codes and {min, scale}
+//   pairs sit in a ring of five slots private to the wave in effect: its own vmcnt wait is all the
+//   synchronisation they need, and the code words of step ks + 1 are read in the middle of step ks, which
+//   leaves half a K step to dequantize them between MFMAs.
+//   A K step is eight phases (K slice s = 0, 1) x (four groups of four row tiles); a phase issues the LDS
+//   reads of the next phase's four A operands, then its 8 MFMAs (column tile 0: four row tiles, column
+//   tile 1: the same four) with dequantization pieces and, in the last phase, the copies between them.
+//     phases 0..3: dequantize slice 1 of this step;  phase 4: read the code words of step ks + 1;
+//     phases 5..7: dequantize slice 0 of step ks + 1;  end of phase 6: vmcnt + barrier (stage ks + 1 has
+//     landed for everyone, nobody reads stage ks any more);  phase 7: copies for ks + 3 (activations) and
+//     ks + 5 (weights), A operands of the next step's first phase.
+//   Copies are issued weights first, then activations, so that the one vmcnt count that guarantees the
+//   activations of step ks + 1 also covers the weights of step ks + 2.
+constexpr int kP16AStages = 3, kP16WSlots = 5, kP16Rows = 256;
+constexpr int kP16AStage = kP16Rows * kKS * 2;
+constexpr int kP16WBase = kP16AStages * kP16AStage;
+constexpr int kP16Lds = kP16WBase + kP16WSlots * kBStageQ4;
+constexpr int kP16Copies = 6;   // per wave per K step: codes, {min, scale}, four 8-row activation pieces
+static_assert(kP16Lds <= kLdsBytes, "stages must fit in LDS");
+
+// position (MFMA number within the K step, 0..63) behind which dequantization piece p of 14 goes: slice 1 of
+// this step over MFMAs 0..29, slice 0 of the next step over MFMAs 41..61
+constexpr int p16_pos_cur(int p) { return p * 30 / 14; }
+constexpr int p16_pos_nxt(int p) { return 41 + p * 21 / 14; }
+
+template <bool H16M>
+__global__ __launch_bounds__(512) void gemm_prefill16_kernel(StreamArgs a) {
+  constexpr int NW = 8, RH = 4;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, g4 = lane >> 4;
+
+  const int p = (blockIdx.x & 7) * (a.grid >> 3) + (blockIdx.x >> 3);
+  const int64_t rem_begin = work_begin(a.rem_work, a.grid, p), rem_end = work_begin(a.rem_work, a.grid, p + 1);
+  int64_t pos = rem_begin;
+  int round = 0, seg = 0;
+
+  // A operand of (row tile m, slice sl): + m * 16 * kKS * 2
+  int a_off[2];
+#pragma unroll
+  for (int sl = 0; sl < 2; ++sl) a_off[sl] = (l16 * kKS + swz(l16, 4 * sl + g4) * 8) * 2;
+  // code word of (column tile ct, slice sl) in a weight slot: + ct * 256 + sl * 512
+  const int bq_off = kP16WBase + wave * 1024 + l16 * 16 + g4 * 4;
+  // {min, scale} of column tile ct: + ct * 16 * (H16M ? 4 : 8)
+  const int bm_off = kP16WBase + 8 * 1024 + wave * 256 + l16 * (H16M ? 4 : 8);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
+
+  while (round < a.rounds || pos < rem_end) {
+    int64_t tile;
+    int ks0, ks1;
+    const bool whole_round = round < a.rounds;
+    if (whole_round) {
+      tile = (int64_t)round * a.grid + p;
+      ks0 = 0;
+      ks1 = a.ksteps;
+    } else {
+      const int64_t t = pos / a.ksteps;
+      tile = (int64_t)a.rounds * a.grid + t;
+      ks0 = (int)(pos - t * a.ksteps);
+      const int64_t left = rem_end - pos;
+      ks1 = (int)((int64_t)(a.ksteps - ks0) < left ? a.ksteps : ks0 + left);
+    }
+    int mblk, n_tile;
+    tile_coords(tile, a.m_blocks, a.n_tiles, mblk, n_tile);
+    const int m0 = mblk * kP16Rows;
+    const int nt0 = n_tile * 8 + wave;   // this wave's 32-column weight tile
+
+    f4_t acc[16][2];
+#pragma unroll
+    for (int m = 0; m < 16; ++m)
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) acc[m][ct] = (f4_t){0.f, 0.f, 0.f, 0.f};
+
+    // this wave's four activation pieces per step: piece c = wave + 8 i covers rows 8 c .. 8 c + 7
+    const half_t* a_src[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = wave + NW * i;
+      const int prow = 8 * c + (lane >> 3);
+      int row = m0 + prow;
+      row = row < a.M ? row : a.M - 1;
+      a_src[i] = a.x + (int64_t)row * a.ldx + swz(prow, lane & 7) * 8;
+    }
+    const uint8_t* w_src;
+    const float* m_src;
+    {
+      int nt = nt0 < a.n32 ? nt0 : a.n32 - 1;   // ragged last column block: load valid data, never store it
+      w_src = a.w + (int64_t)nt * a.ksteps * 1024 + lane * 16;
+      m_src = reinterpret_cast<const float*>(a.meta) +
+              (H16M ? (int64_t)nt * a.ksteps * 32 + (lane & 31) : (int64_t)nt * a.ksteps * 64 + lane);
+    }
+    // copy c of step ks: 0 = codes, 1 = {min, scale} (into weight slot wslot), 2..5 = activation pieces
+    // (into stage).  Past the end of the segment the last step is fetched again: harmless, and it keeps
+    // the VMEM counts uniform.
+    auto copy_one = [&](int c, int ks_w, int wslot, int ks_a, int stage) {
+      if (c == 0) {
+        const int kc = ks_w < ks1 ? ks_w : ks1 - 1;
+        __builtin_amdgcn_global_load_lds((gptr_t)(w_src + (int64_t)kc * 1024),
+                                         (lptr_t)(smem + kP16WBase + wslot * kBStageQ4 + wave * 1024), 16, 0, 0);
+      } else if (c == 1) {
+        const int kc = ks_w < ks1 ? ks_w : ks1 - 1;
+        __builtin_amdgcn_global_load_lds((gptr_t)(m_src + (int64_t)kc * (H16M ? 32 : 64)),
+                                         (lptr_t)(smem + kP16WBase + wslot * kBStageQ4 + 8 * 1024 + wave * 256), 4, 0, 0);
+      } else {
+        const int kc = ks_a < ks1 ? ks_a : ks1 - 1;
+        __builtin_amdgcn_global_load_lds((gptr_t)(a_src[c - 2] + kc * kKS),
+                                         (lptr_t)(smem + stage * kP16AStage + (wave + NW * (c - 2)) * 8 * kKS * 2), 16, 0, 0);
+      }
+    };
+
+    h8_t aop[2][RH];
+    u4_t bop[2][2];        // [slice][column tile]
+    uint32_t cw[2][2];     // raw code words [slice][column tile]
+    float2 cm[2];
+    uint32_t cmh[2];
+    float s24, s20, mn;
+    uint32_t msk[4], r01[2];
+    // A operands of phase q (slice q / 4, row tiles 4 (q % 4) .. + 3) of the stage at st
+    auto read_a = [&](uint32_t st, auto Q_, h8_t* dst) {
+      constexpr int q = decltype(Q_)::value;
+      const uint32_t ad = st + a_off[q >> 2];
+      static_for<0, RH>([&](auto M_) __attribute__((always_inline)) {
+        constexpr int off = ((q & 3) * RH + decltype(M_)::value) * 16 * kKS * 2;
+        dst[decltype(M_)::value] = __builtin_bit_cast(h8_t, lds_read128<off>(ad));
+      });
+    };
+    auto read_b = [&](int wslot) {
+      const uint32_t st = lds0 + wslot * kBStageQ4;
+      static_for<0, 2>([&](auto CT) __attribute__((always_inline)) {
+        constexpr int ct = decltype(CT)::value;
+        cw[0][ct] = lds_read32<ct * 256>(st + bq_off);
+        cw[1][ct] = lds_read32<ct * 256 + 512>(st + bq_off);
+        constexpr int moff = ct * 16 * (H16M ? 4 : 8);
+        if constexpr (H16M) cmh[ct] = lds_read32<moff>(st + bm_off); else cm[ct] = lds_read64<moff>(st + bm_off);
+      });
+    };
+    auto landed_b = [&]() {
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) {
+        lds_landed(cw[0][ct]);
+        lds_landed(cw[1][ct]);
+        if constexpr (H16M) lds_landed(cmh[ct]); else lds_landed(cm[ct]);
+      }
+    };
+    // Exact dequantization (fg_common.h: dequant8_exact) of code word (sl, ct) into bop[sl][ct], in seven
+    // pieces of one to three instructions that stay where they are written (see gemm_decode16_kernel).
+    auto dq7 = [&](int sl, int ct, int piece) {
+      if (piece == 0) {
+        float2 m2 = cm[ct];
+        if constexpr (H16M) {
+          const h2_t pr = __builtin_bit_cast(h2_t, cmh[ct]);
+          m2.x = (float)pr.x;
+          m2.y = (float)pr.y;
+        }
+        s24 = m2.y * 16777216.0f;
+        s20 = m2.y * 1048576.0f;
+        mn = m2.x;
+        __asm__ volatile("" : "+v"(s24), "+v"(s20), "+v"(mn));
+      } else if (piece == 1) {
+        msk[0] = cw[sl][ct] & 0x000F000Fu;
+        msk[1] = cw[sl][ct] & 0x00F000F0u;
+        __asm__ volatile("" : "+v"(msk[0]), "+v"(msk[1]));
+      } else if (piece == 2) {
+        const uint32_t y = cw[sl][ct] >> 8;
+        msk[2] = y & 0x000F000Fu;
+        msk[3] = y & 0x00F000F0u;
+        __asm__ volatile("" : "+v"(msk[2]), "+v"(msk[3]));
+      } else if (piece == 3) {   // weights 0 and 2: low halves of operand registers 0 and 1
+        fma_mixlo<0>(r01[0], msk[0], s24, mn);
+        fma_mixlo<0>(r01[1], msk[2], s24, mn);
+      } else if (piece == 4) {   // weights 1 and 3: high halves; registers 0 and 1 are complete
+        fma_mixhi<0>(r01[0], msk[1], s20, mn);
+        fma_mixhi<0>(r01[1], msk[3], s20, mn);
+        bop[sl][ct][0] = r01[0];
+        bop[sl][ct][1] = r01[1];
+      } else if (piece == 5) {   // weights 4 and 6
+        fma_mixlo<1>(r01[0], msk[0], s24, mn);
+        fma_mixlo<1>(r01[1], msk[2], s24, mn);
+      } else {                   // weights 5 and 7; registers 2 and 3 are complete
+        fma_mixhi<1>(r01[0], msk[1], s20, mn);
+        fma_mixhi<1>(r01[1], msk[3], s20, mn);
+        bop[sl][ct][2] = r01[0];
+        bop[sl][ct][3] = r01[1];
+      }
+    };
+
+    // no copy of the previous segment may still be in flight towards a stage, and no wave still reads one
+    __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    // the copy groups of steps ks0 - 5 .. ks0 - 1, as the steady state would have issued them
+    copy_one(0, ks0, 0, 0, 0);
+    copy_one(1, ks0, 0, 0, 0);
+    copy_one(0, ks0 + 1, 1, 0, 0);
+    copy_one(1, ks0 + 1, 1, 0, 0);
+#pragma unroll
+    for (int t = 0; t < 3; ++t)
+#pragma unroll
+      for (int c = 0; c < kP16Copies; ++c) copy_one(c, ks0 + 2 + t, 2 + t, ks0 + t, t);
+    __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kP16Copies) : "memory");   // weights ks0 .. ks0 + 2, activations ks0
+    __builtin_amdgcn_s_barrier();
+    read_a(lds0, IdxC<0>{}, aop[0]);
+    read_b(0);
+    lds_wait();
+#pragma unroll
+    for (int m = 0; m < RH; ++m) lds_landed(aop[0][m]);
+    landed_b();
+#pragma unroll
+    for (int q = 0; q < 14; ++q) dq7(0, q / 7, q % 7);
+
+    int stage = 0, wslot = 0;
+    for (int ks = ks0; ks < ks1; ++ks) {
+      const int stage1 = stage + 1 == kP16AStages ? 0 : stage + 1;
+      const int wslot1 = wslot + 1 == kP16WSlots ? 0 : wslot + 1;
+      const uint32_t At = lds0 + stage * kP16AStage;
+      static_for<0, 8>([&](auto Q_) __attribute__((always_inline)) {
+        constexpr int q = decltype(Q_)::value;
+        constexpr int sl = q >> 2, cur = q & 1, nxt = cur ^ 1;
+        if constexpr (q < 7)
+          read_a(At, IdxC<q + 1>{}, aop[nxt]);
+        else
+          read_a(lds0 + stage1 * kP16AStage, IdxC<0>{}, aop[nxt]);
+        if constexpr (q == 4) read_b(wslot1);
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, 2 * RH>([&](auto I) __attribute__((always_inline)) {
+          constexpr int i = decltype(I)::value;
+          constexpr int ct = i / RH, m = i - ct * RH, g = q * 8 + i;
+          mfma16_inplace_v(acc[(q & 3) * RH + m][ct], aop[cur][m], __builtin_bit_cast(h8_t, bop[sl][ct]));
+          __builtin_amdgcn_sched_barrier(0);
+          static_for<0, 14>([&](auto P_) __attribute__((always_inline)) {
+            constexpr int pc = decltype(P_)::value;
+            if constexpr (p16_pos_cur(pc) == g) dq7(1, pc / 7, pc % 7);
+            if constexpr (p16_pos_nxt(pc) == g) dq7(0, pc / 7, pc % 7);
+          });
+          if constexpr (q == 7 && i < kP16Copies) copy_one(i, ks + kP16WSlots, wslot, ks + kP16AStages, stage);
+          __builtin_amdgcn_sched_barrier(0);
+        });
+        lds_wait();
+#pragma unroll
+        for (int m = 0; m < RH; ++m) lds_landed(aop[nxt][m]);
+        if constexpr (q == 4) landed_b();
+        if constexpr (q == 6) {
+          __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"(kP16Copies) : "memory");
+          __builtin_amdgcn_s_barrier();   // bare barrier: no fence, the copies in flight stay in flight
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      stage = stage1;
+      wslot = wslot1;
+    }
+
+    // The MFMAs are opaque instructions to the compiler: wait out the last of them (16 cycles each)
+    // before the accumulators are read.
+    __asm__ volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+    for (int m = 0; m < 16; ++m)
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) __asm__ volatile("" : "+v"(acc[m][ct]));
+    // ---- epilogue: lane holds column l16 of each 16 x 16 tile, rows 4 * g4 + 0..3
+    const bool full = (ks0 == 0) && (ks1 == a.ksteps);
+    if (full) {
+      if (nt0 < a.n32) {
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+          const int col = nt0 * 32 + ct * 16 + l16;
+          const float bvv = a.bias ? (float)a.bias[col] : 0.f;
+          int row = m0 + 4 * g4;
+          int64_t o_off = (int64_t)row * a.ldo + col, r_off = (int64_t)row * a.ldr + col;
+#pragma unroll
+          for (int m = 0; m < 16; ++m) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              if (row < a.M) {
+                float v = acc[m][ct][r] + bvv;
+                if (a.relu) v = fmaxf(v, 0.f);
+                if (a.residual) v += (float)a.residual[r_off];
+                if (a.out32)
+                  a.out32[o_off] = v;
+                else
+                  a.out16[o_off] = (half_t)v;
+              }
+              const int step = r == 3 ? 13 : 1;   // rows 16 m + 4 g4 + r
+              row += step;
+              o_off += step * a.ldo;
+              r_off += step * a.ldr;
+            }
+          }
+        }
+      }
+    } else {
+      // Partial sums in the layout of gemm_stream_kernel<8, 1, 1, 8> (its reduction pass finishes these
+      // tiles too): float4 number (2 m + g4 / 2) of "thread" 64 wave + 32 (g4 % 2) + 16 ct + l16 holds
+      // rows 16 m + 4 g4 + 0..3 of column 32 wave + 16 ct + l16.
+      float4* base = reinterpret_cast<float4*>(a.partial + ((int64_t)p * 2 + (seg == 0 ? 0 : 1)) * ((int64_t)kP16Rows * kBN));
+#pragma unroll
+      for (int m = 0; m < 16; ++m)
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+          if (m0 + 16 * m + 8 * (g4 >> 1) < a.M)   // rows beyond M: padding, never read back
+            base[(2 * m + (g4 >> 1)) * (NW * 64) + wave * 64 + (g4 & 1) * 32 + ct * 16 + l16] =
+                make_float4(acc[m][ct][0], acc[m][ct][1], acc[m][ct][2], acc[m][ct][3]);
+        }
+    }
+    if (whole_round) {
+      ++round;
+    } else {
+      pos += ks1 - ks0;
+      ++seg;
+    }
+  }
+  __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no copy may still target LDS when the wave ends
+}
+
 // Reduction pass for gemm_decode16_kernel: thread tid of a block adds, in ascending K order, the float4s
 // that thread tid of the contributing workgroups wrote, then applies the epilogue.  blockIdx.x counts the
 // tiles after the whole rounds, blockIdx.y spreads a thread's MT16 * 4 items.
@@ -1388,6 +1710,19 @@ int launch_t(const StreamArgs& a, hipStream_t stream) {
 // Eight waves from five row tiles up (measured against four waves in one run, 144 rows: QKV 162-167 vs
 // 176-178 us, FFN1 210-218 vs 225-229, FFN2 219-221 vs 227-230; 112 rows 135-144 vs 151; level at 48 rows,
 // 3-7 % slower at 4 and 16 rows, where a wave has too few MFMAs per step to spread anything between).
+template <bool H16M>
+int launch_prefill16(const StreamArgs& a, hipStream_t stream) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_prefill16_kernel<H16M>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kP16Lds));
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((gemm_prefill16_kernel<H16M>), dim3(a.grid), dim3(512), kP16Lds, stream, a);
+  FG_LAUNCH_CHECK();
+  return FG_OK;
+}
+
 template <int MT16, bool H16M>
 int launch_dec16(const StreamArgs& a, hipStream_t stream) {
   using C = Dec16Cfg<MT16, H16M>;
@@ -1456,8 +1791,8 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
     ProfScope prof(FG_K_GEMM_LARGE_M, stream);
     if (la.dtype != FG_Q4G64_TILED && la.dtype != FG_Q4G64_H16_TILED && la.dtype != FG_F16) return FG_ERR_UNSUPPORTED;
     const int rc = la.dtype == FG_F16               ? launch_t<8, 1, 1, 8, true>(a, stream)
-                   : la.dtype == FG_Q4G64_H16_TILED ? launch_t<8, 1, 1, 8, false, true>(a, stream)
-                                                    : launch_t<8, 1, 1, 8, false>(a, stream);
+                   : la.dtype == FG_Q4G64_H16_TILED ? launch_prefill16<true>(a, stream)
+                                                    : launch_prefill16<false>(a, stream);
     if (rc) return rc;
     if (rem_tiles > 0) {
       hipLaunchKernelGGL(gemm_stream_finish_kernel, dim3((unsigned)rem_tiles, finish_y(sh)), dim3(sh.nw * 64), 0, stream, a, sh.mt,
