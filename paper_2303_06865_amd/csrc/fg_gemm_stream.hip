@@ -1517,34 +1517,47 @@ __global__ __launch_bounds__(512) void gemm_prefill16_kernel(StreamArgs a) {
     for (int m = 0; m < 16; ++m)
 #pragma unroll
       for (int ct = 0; ct < 2; ++ct) __asm__ volatile("" : "+v"(acc[m][ct]));
-    // ---- epilogue: lane holds column l16 of each 16 x 16 tile, rows 4 * g4 + 0..3
+    // ---- epilogue: lane holds column l16 of each 16 x 16 tile, rows 4 * g4 + 0..3.  Neighbouring lanes
+    // swap one value each (even lanes give away their column of column tile 1, odd lanes theirs of column
+    // tile 0), after which every lane owns two adjacent columns and a store instruction covers 64
+    // contiguous bytes of each of its four rows instead of 32.
     const bool full = (ks0 == 0) && (ks1 == a.ksteps);
     if (full) {
       if (nt0 < a.n32) {
+        const bool odd = (l16 & 1) != 0;
+        const int c0 = nt0 * 32 + l16, c1 = c0 + 16;
+        const float b0 = a.bias ? (float)a.bias[c0] : 0.f, b1 = a.bias ? (float)a.bias[c1] : 0.f;
+        const int cs = odd ? c1 - 1 : c0;   // first of the two adjacent columns this lane stores
+        int row = m0 + 4 * g4;
+        int64_t o_off = (int64_t)row * a.ldo + cs, r_off = (int64_t)row * a.ldr + cs;
 #pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {
-          const int col = nt0 * 32 + ct * 16 + l16;
-          const float bvv = a.bias ? (float)a.bias[col] : 0.f;
-          int row = m0 + 4 * g4;
-          int64_t o_off = (int64_t)row * a.ldo + col, r_off = (int64_t)row * a.ldr + col;
+        for (int m = 0; m < 16; ++m) {
 #pragma unroll
-          for (int m = 0; m < 16; ++m) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              if (row < a.M) {
-                float v = acc[m][ct][r] + bvv;
-                if (a.relu) v = fmaxf(v, 0.f);
-                if (a.residual) v += (float)a.residual[r_off];
-                if (a.out32)
-                  a.out32[o_off] = v;
-                else
-                  a.out16[o_off] = (half_t)v;
-              }
-              const int step = r == 3 ? 13 : 1;   // rows 16 m + 4 g4 + r
-              row += step;
-              o_off += step * a.ldo;
-              r_off += step * a.ldr;
+          for (int r = 0; r < 4; ++r) {
+            float x0 = acc[m][0][r] + b0, x1 = acc[m][1][r] + b1;
+            if (a.relu) {
+              x0 = fmaxf(x0, 0.f);
+              x1 = fmaxf(x1, 0.f);
             }
+            const float keep = odd ? x1 : x0, send = odd ? x0 : x1;
+            // lane l <-> lane l ^ 1 (quad_perm [1, 0, 3, 2])
+            const float recv = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));
+            float lo = odd ? recv : keep, hi = odd ? keep : recv;
+            if (row < a.M) {
+              if (a.residual) {
+                const h2_t rr = *reinterpret_cast<const h2_t*>(a.residual + r_off);
+                lo += (float)rr.x;
+                hi += (float)rr.y;
+              }
+              if (a.out32)
+                *reinterpret_cast<float2*>(a.out32 + o_off) = make_float2(lo, hi);
+              else
+                *reinterpret_cast<h2_t*>(a.out16 + o_off) = (h2_t){(half_t)lo, (half_t)hi};
+            }
+            const int step = r == 3 ? 13 : 1;   // rows 16 m + 4 g4 + r
+            row += step;
+            o_off += step * a.ldo;
+            r_off += step * a.ldr;
           }
         }
       }
