@@ -17,6 +17,8 @@
 //            WM = 1; two waves per SIMD, so that one wave's MFMAs overlap the other's LDS reads and
 //            dequantization, and no weight is dequantized twice in a workgroup: measured 2 % faster
 //            than 2 x 4 waves of 128 x 64, which halve the LDS reads but dequantize everything twice).
+//            On 4-bit weights this shape runs in gemm_prefill16_kernel further down (the same tile on
+//            v_mfma_f32_16x16x32_f16); this template still serves it on row-major FP16 weights.
 //   * Nothing but MFMA operands passes through registers.  The activation tile (XOR-swizzled, the A
 //     operand) and the weight tiles (1 KiB of codes + 256 B of {min,scale} each) are copied
 //     global -> LDS asynchronously, several K steps ahead.  A wave reads its codes back, dequantizes
