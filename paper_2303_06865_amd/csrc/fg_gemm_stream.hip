@@ -17,8 +17,10 @@
 //            WM = 1; two waves per SIMD, so that one wave's MFMAs overlap the other's LDS reads and
 //            dequantization, and no weight is dequantized twice in a workgroup: measured 2 % faster
 //            than 2 x 4 waves of 128 x 64, which halve the LDS reads but dequantize everything twice).
-//            On 4-bit weights this shape runs in gemm_prefill16_kernel further down (the same tile on
-//            v_mfma_f32_16x16x32_f16); this template still serves it on row-major FP16 weights.
+//            This shape now runs in gemm_prefill16_kernel / gemm_prefill16_f16_kernel further down (the
+//            same tile, wave layout, tile walk and partial sums on v_mfma_f32_16x16x32_f16, which is
+//            worth 7-10 % under the chip's power limit); the template keeps the parameters, the
+//            launcher no longer instantiates them.
 //   * Nothing but MFMA operands passes through registers.  The activation tile (XOR-swizzled, the A
 //     operand) and the weight tiles (1 KiB of codes + 256 B of {min,scale} each) are copied
 //     global -> LDS asynchronously, several K steps ahead.  A wave reads its codes back, dequantizes
@@ -1285,6 +1287,76 @@ static_assert(kP16Lds <= kLdsBytes, "stages must fit in LDS");
 constexpr int p16_pos_cur(int p) { return p * 30 / 14; }
 constexpr int p16_pos_nxt(int p) { return 41 + p * 21 / 14; }
 
+// What both prefill kernels on 16 x 16 x 32 MFMAs do with a finished segment of a 256 x 256 tile: acc[m][ct]
+// of wave w holds rows 16 m + 4 g4 + 0..3 of column 32 w + 16 ct + l16.
+__device__ __forceinline__ void prefill16_finish_tile(const StreamArgs& a, f4_t (&acc)[16][2], bool full, int m0, int nt0, int p,
+                                                      int seg, int wave, int l16, int g4) {
+  // The MFMAs are opaque instructions to the compiler: wait out the last of them (16 cycles each)
+  // before the accumulators are read.
+  __asm__ volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+  for (int m = 0; m < 16; ++m)
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) __asm__ volatile("" : "+v"(acc[m][ct]));
+  // ---- epilogue: lane holds column l16 of each 16 x 16 tile, rows 4 * g4 + 0..3.  Neighbouring lanes
+  // swap one value each (even lanes give away their column of column tile 1, odd lanes theirs of column
+  // tile 0), after which every lane owns two adjacent columns and a store instruction covers 64
+  // contiguous bytes of each of its four rows instead of 32.
+  if (full) {
+    if (nt0 < a.n32) {
+      const bool odd = (l16 & 1) != 0;
+      const int c0 = nt0 * 32 + l16, c1 = c0 + 16;
+      const float b0 = a.bias ? (float)a.bias[c0] : 0.f, b1 = a.bias ? (float)a.bias[c1] : 0.f;
+      const int cs = odd ? c1 - 1 : c0;   // first of the two adjacent columns this lane stores
+      int row = m0 + 4 * g4;
+      int64_t o_off = (int64_t)row * a.ldo + cs, r_off = (int64_t)row * a.ldr + cs;
+#pragma unroll
+      for (int m = 0; m < 16; ++m) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float x0 = acc[m][0][r] + b0, x1 = acc[m][1][r] + b1;
+          if (a.relu) {
+            x0 = fmaxf(x0, 0.f);
+            x1 = fmaxf(x1, 0.f);
+          }
+          const float keep = odd ? x1 : x0, send = odd ? x0 : x1;
+          // lane l <-> lane l ^ 1 (quad_perm [1, 0, 3, 2])
+          const float recv = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));
+          float lo = odd ? recv : keep, hi = odd ? keep : recv;
+          if (row < a.M) {
+            if (a.residual) {
+              const h2_t rr = *reinterpret_cast<const h2_t*>(a.residual + r_off);
+              lo += (float)rr.x;
+              hi += (float)rr.y;
+            }
+            if (a.out32)
+              *reinterpret_cast<float2*>(a.out32 + o_off) = make_float2(lo, hi);
+            else
+              *reinterpret_cast<h2_t*>(a.out16 + o_off) = (h2_t){(half_t)lo, (half_t)hi};
+          }
+          const int step = r == 3 ? 13 : 1;   // rows 16 m + 4 g4 + r
+          row += step;
+          o_off += step * a.ldo;
+          r_off += step * a.ldr;
+        }
+      }
+    }
+  } else {
+    // Partial sums in the layout of gemm_stream_kernel<8, 1, 1, 8> (its reduction pass finishes these
+    // tiles too): float4 number (2 m + g4 / 2) of "thread" 64 wave + 32 (g4 % 2) + 16 ct + l16 holds
+    // rows 16 m + 4 g4 + 0..3 of column 32 wave + 16 ct + l16.
+    float4* base = reinterpret_cast<float4*>(a.partial + ((int64_t)p * 2 + (seg == 0 ? 0 : 1)) * ((int64_t)kP16Rows * kBN));
+#pragma unroll
+    for (int m = 0; m < 16; ++m)
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) {
+        if (m0 + 16 * m + 8 * (g4 >> 1) < a.M)   // rows beyond M: padding, never read back
+          base[(2 * m + (g4 >> 1)) * 512 + wave * 64 + (g4 & 1) * 32 + ct * 16 + l16] =
+              make_float4(acc[m][ct][0], acc[m][ct][1], acc[m][ct][2], acc[m][ct][3]);
+      }
+  }
+}
+
 template <bool H16M>
 __global__ __launch_bounds__(512) void gemm_prefill16_kernel(StreamArgs a) {
   constexpr int NW = 8, RH = 4;
@@ -1512,71 +1584,199 @@ __global__ __launch_bounds__(512) void gemm_prefill16_kernel(StreamArgs a) {
       wslot = wslot1;
     }
 
-    // The MFMAs are opaque instructions to the compiler: wait out the last of them (16 cycles each)
-    // before the accumulators are read.
-    __asm__ volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    prefill16_finish_tile(a, acc, (ks0 == 0) && (ks1 == a.ksteps), m0, nt0, p, seg, wave, l16, g4);
+    if (whole_round) {
+      ++round;
+    } else {
+      pos += ks1 - ks0;
+      ++seg;
+    }
+  }
+  __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no copy may still target LDS when the wave ends
+}
+
+// The same tile on row-major FP16 weights (the uncompressed workload's prefill projections).  Nothing to
+// dequantize: a wave's B operands are read from LDS like its A operands.  Activations: three stages of
+// 32 KiB behind the per-step barrier, as above.  Weights: wave w copies and reads only rows 32 w .. + 31 of
+// the [256 columns][64 k] block (4 KiB per step), so they sit in two 32 KiB slots that the wave's own vmcnt
+// wait synchronises; the copies of a step are issued weights (for step ks + 2) first, then activations (for
+// step ks + 3), and one count covers "activations of ks + 1 and weights of ks + 1 have landed".
+// Phases as above; slice 1's B operands are read at the start of phase 2, the next step's slice 0 operands at
+// the start of the last phase, after the barrier.
+constexpr int kP16FWSlots = 2;
+constexpr int kP16FLds = kP16WBase + kP16FWSlots * kBStageF16;
+constexpr int kP16FCopies = 8;   // per wave per K step: four 8-row weight pieces, four 8-row activation pieces
+static_assert(kP16FLds <= kLdsBytes, "stages must fit in LDS");
+
+__global__ __launch_bounds__(512) void gemm_prefill16_f16_kernel(StreamArgs a) {
+  constexpr int NW = 8, RH = 4;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, g4 = lane >> 4;
+
+  const int p = (blockIdx.x & 7) * (a.grid >> 3) + (blockIdx.x >> 3);
+  const int64_t rem_begin = work_begin(a.rem_work, a.grid, p), rem_end = work_begin(a.rem_work, a.grid, p + 1);
+  int64_t pos = rem_begin;
+  int round = 0, seg = 0;
+
+  // A operand of (row tile m, slice sl): + m * 16 * kKS * 2
+  int a_off[2];
+  // B operand of (column tile ct, slice sl) in a weight slot: row 32 wave + 16 ct + l16 of the block
+  int b_off[2][2];
+#pragma unroll
+  for (int sl = 0; sl < 2; ++sl) {
+    a_off[sl] = (l16 * kKS + swz(l16, 4 * sl + g4) * 8) * 2;
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct) {
+      const int r = wave * 32 + ct * 16 + l16;
+      b_off[sl][ct] = kP16WBase + (r * kKS + swz(r, 4 * sl + g4) * 8) * 2;
+    }
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)smem;
+
+  while (round < a.rounds || pos < rem_end) {
+    int64_t tile;
+    int ks0, ks1;
+    const bool whole_round = round < a.rounds;
+    if (whole_round) {
+      tile = (int64_t)round * a.grid + p;
+      ks0 = 0;
+      ks1 = a.ksteps;
+    } else {
+      const int64_t t = pos / a.ksteps;
+      tile = (int64_t)a.rounds * a.grid + t;
+      ks0 = (int)(pos - t * a.ksteps);
+      const int64_t left = rem_end - pos;
+      ks1 = (int)((int64_t)(a.ksteps - ks0) < left ? a.ksteps : ks0 + left);
+    }
+    int mblk, n_tile;
+    tile_coords(tile, a.m_blocks, a.n_tiles, mblk, n_tile);
+    const int m0 = mblk * kP16Rows;
+    const int nt0 = n_tile * 8 + wave;   // this wave's 32 columns, as a 32-column tile number
+
+    f4_t acc[16][2];
 #pragma unroll
     for (int m = 0; m < 16; ++m)
 #pragma unroll
-      for (int ct = 0; ct < 2; ++ct) __asm__ volatile("" : "+v"(acc[m][ct]));
-    // ---- epilogue: lane holds column l16 of each 16 x 16 tile, rows 4 * g4 + 0..3.  Neighbouring lanes
-    // swap one value each (even lanes give away their column of column tile 1, odd lanes theirs of column
-    // tile 0), after which every lane owns two adjacent columns and a store instruction covers 64
-    // contiguous bytes of each of its four rows instead of 32.
-    const bool full = (ks0 == 0) && (ks1 == a.ksteps);
-    if (full) {
-      if (nt0 < a.n32) {
-        const bool odd = (l16 & 1) != 0;
-        const int c0 = nt0 * 32 + l16, c1 = c0 + 16;
-        const float b0 = a.bias ? (float)a.bias[c0] : 0.f, b1 = a.bias ? (float)a.bias[c1] : 0.f;
-        const int cs = odd ? c1 - 1 : c0;   // first of the two adjacent columns this lane stores
-        int row = m0 + 4 * g4;
-        int64_t o_off = (int64_t)row * a.ldo + cs, r_off = (int64_t)row * a.ldr + cs;
+      for (int ct = 0; ct < 2; ++ct) acc[m][ct] = (f4_t){0.f, 0.f, 0.f, 0.f};
+
+    // this wave's four activation pieces per step: piece c = wave + 8 i covers rows 8 c .. 8 c + 7 of the tile;
+    // its four weight pieces: rows (output columns) 32 wave + 8 i .. + 7 of the block
+    const half_t* a_src[4];
+    const uint8_t* w_src[4];
 #pragma unroll
-        for (int m = 0; m < 16; ++m) {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            float x0 = acc[m][0][r] + b0, x1 = acc[m][1][r] + b1;
-            if (a.relu) {
-              x0 = fmaxf(x0, 0.f);
-              x1 = fmaxf(x1, 0.f);
-            }
-            const float keep = odd ? x1 : x0, send = odd ? x0 : x1;
-            // lane l <-> lane l ^ 1 (quad_perm [1, 0, 3, 2])
-            const float recv = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));
-            float lo = odd ? recv : keep, hi = odd ? keep : recv;
-            if (row < a.M) {
-              if (a.residual) {
-                const h2_t rr = *reinterpret_cast<const h2_t*>(a.residual + r_off);
-                lo += (float)rr.x;
-                hi += (float)rr.y;
-              }
-              if (a.out32)
-                *reinterpret_cast<float2*>(a.out32 + o_off) = make_float2(lo, hi);
-              else
-                *reinterpret_cast<h2_t*>(a.out16 + o_off) = (h2_t){(half_t)lo, (half_t)hi};
-            }
-            const int step = r == 3 ? 13 : 1;   // rows 16 m + 4 g4 + r
-            row += step;
-            o_off += step * a.ldo;
-            r_off += step * a.ldr;
-          }
-        }
-      }
-    } else {
-      // Partial sums in the layout of gemm_stream_kernel<8, 1, 1, 8> (its reduction pass finishes these
-      // tiles too): float4 number (2 m + g4 / 2) of "thread" 64 wave + 32 (g4 % 2) + 16 ct + l16 holds
-      // rows 16 m + 4 g4 + 0..3 of column 32 wave + 16 ct + l16.
-      float4* base = reinterpret_cast<float4*>(a.partial + ((int64_t)p * 2 + (seg == 0 ? 0 : 1)) * ((int64_t)kP16Rows * kBN));
-#pragma unroll
-      for (int m = 0; m < 16; ++m)
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct) {
-          if (m0 + 16 * m + 8 * (g4 >> 1) < a.M)   // rows beyond M: padding, never read back
-            base[(2 * m + (g4 >> 1)) * (NW * 64) + wave * 64 + (g4 & 1) * 32 + ct * 16 + l16] =
-                make_float4(acc[m][ct][0], acc[m][ct][1], acc[m][ct][2], acc[m][ct][3]);
-        }
+    for (int i = 0; i < 4; ++i) {
+      const int c = wave + NW * i;
+      const int prow = 8 * c + (lane >> 3);
+      int row = m0 + prow;
+      row = row < a.M ? row : a.M - 1;
+      a_src[i] = a.x + (int64_t)row * a.ldx + swz(prow, lane & 7) * 8;
+      const int wrow = wave * 32 + 8 * i + (lane >> 3);
+      int col = n_tile * kBN + wrow;
+      col = col < a.N ? col : a.N - 1;   // ragged last column block: load valid data, never store it
+      w_src[i] = a.w + ((int64_t)col * a.K + swz(wrow, lane & 7) * 8) * 2;
     }
+    // copy c of a step: 0..3 = weight pieces of step ks_w (into weight slot wslot), 4..7 = activation pieces
+    // of step ks_a (into stage).  Past the end of the segment the last step is fetched again: harmless, and it
+    // keeps the VMEM counts uniform.
+    auto copy_one = [&](int c, int ks_w, int wslot, int ks_a, int stage) {
+      if (c < 4) {
+        const int kc = ks_w < ks1 ? ks_w : ks1 - 1;
+        __builtin_amdgcn_global_load_lds((gptr_t)(w_src[c] + (int64_t)kc * (kKS * 2)),
+                                         (lptr_t)(smem + kP16WBase + wslot * kBStageF16 + (wave * 4 + c) * 8 * kKS * 2), 16, 0, 0);
+      } else {
+        const int kc = ks_a < ks1 ? ks_a : ks1 - 1;
+        __builtin_amdgcn_global_load_lds((gptr_t)(a_src[c - 4] + kc * kKS),
+                                         (lptr_t)(smem + stage * kP16AStage + (wave + NW * (c - 4)) * 8 * kKS * 2), 16, 0, 0);
+      }
+    };
+
+    h8_t aop[2][RH];
+    u4_t bop[2][2];   // [slice][column tile]
+    auto read_a = [&](uint32_t st, auto Q_, h8_t* dst) {
+      constexpr int q = decltype(Q_)::value;
+      const uint32_t ad = st + a_off[q >> 2];
+      static_for<0, RH>([&](auto M_) __attribute__((always_inline)) {
+        constexpr int off = ((q & 3) * RH + decltype(M_)::value) * 16 * kKS * 2;
+        dst[decltype(M_)::value] = __builtin_bit_cast(h8_t, lds_read128<off>(ad));
+      });
+    };
+    auto read_b = [&](int wslot, auto SL_) {
+      constexpr int sl = decltype(SL_)::value;
+      const uint32_t st = lds0 + wslot * kBStageF16;
+      bop[sl][0] = lds_read128<0>(st + b_off[sl][0]);
+      bop[sl][1] = lds_read128<0>(st + b_off[sl][1]);
+    };
+
+    // no copy of the previous segment may still be in flight towards a stage, and no wave still reads one
+    __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    // the copy groups of steps ks0 - 3 .. ks0 - 1, as the steady state would have issued them
+#pragma unroll
+    for (int c = 4; c < kP16FCopies; ++c) copy_one(c, 0, 0, ks0, 0);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int c = 0; c < kP16FCopies; ++c) copy_one(c, ks0 + t, t, ks0 + 1 + t, 1 + t);
+    __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"(12) : "memory");   // activations and weights of step ks0
+    __builtin_amdgcn_s_barrier();
+    read_a(lds0, IdxC<0>{}, aop[0]);
+    read_b(0, IdxC<0>{});
+    lds_wait();
+#pragma unroll
+    for (int m = 0; m < RH; ++m) lds_landed(aop[0][m]);
+    lds_landed(bop[0][0]);
+    lds_landed(bop[0][1]);
+
+    int stage = 0, wslot = 0;
+    for (int ks = ks0; ks < ks1; ++ks) {
+      const int stage1 = stage + 1 == kP16AStages ? 0 : stage + 1;
+      const int wslot1 = wslot ^ 1;
+      const uint32_t At = lds0 + stage * kP16AStage;
+      static_for<0, 8>([&](auto Q_) __attribute__((always_inline)) {
+        constexpr int q = decltype(Q_)::value;
+        constexpr int sl = q >> 2, cur = q & 1, nxt = cur ^ 1;
+        if constexpr (q < 7)
+          read_a(At, IdxC<q + 1>{}, aop[nxt]);
+        else
+          read_a(lds0 + stage1 * kP16AStage, IdxC<0>{}, aop[nxt]);
+        if constexpr (q == 2) read_b(wslot, IdxC<1>{});
+        if constexpr (q == 7) read_b(wslot1, IdxC<0>{});
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<0, 2 * RH>([&](auto I) __attribute__((always_inline)) {
+          constexpr int i = decltype(I)::value;
+          constexpr int ct = i / RH, m = i - ct * RH;
+          mfma16_inplace_v(acc[(q & 3) * RH + m][ct], aop[cur][m], __builtin_bit_cast(h8_t, bop[sl][ct]));
+          __builtin_amdgcn_sched_barrier(0);
+          // (weights into the slot whose last operands were read at phase 2 of this step)
+          if constexpr (q == 7) copy_one(i, ks + kP16FWSlots, wslot, ks + kP16AStages, stage);
+          __builtin_amdgcn_sched_barrier(0);
+        });
+        lds_wait();
+#pragma unroll
+        for (int m = 0; m < RH; ++m) lds_landed(aop[nxt][m]);
+        if constexpr (q == 2) {
+          lds_landed(bop[1][0]);
+          lds_landed(bop[1][1]);
+        }
+        if constexpr (q == 7) {
+          lds_landed(bop[0][0]);
+          lds_landed(bop[0][1]);
+        }
+        if constexpr (q == 6) {
+          // outstanding may stay: the four activation pieces of step ks + 2 (issued last in step ks - 1)
+          __asm__ volatile("s_waitcnt vmcnt(%0)" ::"n"(4) : "memory");
+          __builtin_amdgcn_s_barrier();   // bare barrier: no fence, the copies in flight stay in flight
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      });
+      stage = stage1;
+      wslot = wslot1;
+    }
+
+    prefill16_finish_tile(a, acc, (ks0 == 0) && (ks1 == a.ksteps), m0, nt0, p, seg, wave, l16, g4);
     if (whole_round) {
       ++round;
     } else {
@@ -1738,6 +1938,18 @@ int launch_prefill16(const StreamArgs& a, hipStream_t stream) {
   return FG_OK;
 }
 
+int launch_prefill16_f16(const StreamArgs& a, hipStream_t stream) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    FG_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_prefill16_f16_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               kP16FLds));
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(gemm_prefill16_f16_kernel, dim3(a.grid), dim3(512), kP16FLds, stream, a);
+  FG_LAUNCH_CHECK();
+  return FG_OK;
+}
+
 template <int MT16, bool H16M>
 int launch_dec16(const StreamArgs& a, hipStream_t stream) {
   using C = Dec16Cfg<MT16, H16M>;
@@ -1805,7 +2017,7 @@ int gemm_stream_launch(const LinearArgs& la, void* ws, size_t ws_bytes, hipStrea
   if (sh.nw == 8) {   // prefill shape: GEMM and reduction of the last partial round are one profile record
     ProfScope prof(FG_K_GEMM_LARGE_M, stream);
     if (la.dtype != FG_Q4G64_TILED && la.dtype != FG_Q4G64_H16_TILED && la.dtype != FG_F16) return FG_ERR_UNSUPPORTED;
-    const int rc = la.dtype == FG_F16               ? launch_t<8, 1, 1, 8, true>(a, stream)
+    const int rc = la.dtype == FG_F16               ? launch_prefill16_f16(a, stream)
                    : la.dtype == FG_Q4G64_H16_TILED ? launch_prefill16<true>(a, stream)
                                                     : launch_prefill16<false>(a, stream);
     if (rc) return rc;
