@@ -124,8 +124,8 @@ static const int64_t kSmallMLimit = 512;   // rows up to which the weight-stream
 
 // Tiled 4-bit weights always take the stream kernels, and so do row-major FP16 weights whose row count
 // (output columns) is a multiple of 32: the decode phase and the LM head as a pure weight streamer, the
-// prefill phase on 256 x 256 tiles with two LDS stages (measured on the OPT-6.7B prefill shapes in one
-// run: 0.85-1.02 PFLOP/s against 0.74-0.91 for gemm_large_m_kernel).
+// prefill phase on 256 x 256 tiles (measured on the OPT-6.7B prefill shapes in one run: 0.94-1.15 PFLOP/s
+// against 0.74-0.91 for gemm_large_m_kernel).
 static bool use_stream(int dtype, int64_t n, int64_t m) {
   (void)m;
   if (dtype == FG_Q4G64_TILED || dtype == FG_Q4G64_H16_TILED) return true;
