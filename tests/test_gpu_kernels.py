@@ -506,7 +506,9 @@ def test_embed_bit_exact():
     assert np.array_equal(host(out), ref)
 
 
-@pytest.mark.parametrize("rows,vocab,h1", [(4, 50272, 768), (37, 1000, 256), (144, 5000, 1024)])
+# (400 rows: the LM head on the 256-row prefill tiles, binary32 logits stored two columns per lane, ragged
+#  last row block and a last column block of one 32-column tile)
+@pytest.mark.parametrize("rows,vocab,h1", [(4, 50272, 768), (37, 1000, 256), (144, 5000, 1024), (400, 4128, 512)])
 def test_lm_head_greedy(rows, vocab, h1):
     sh = synth.Shape(h1=h1, nh=h1 // 64, h2=4 * h1, vocab=vocab, max_pos=64)
     ocfg = O.ModelCfg(sh.h1, sh.nh, sh.h2, sh.vocab, sh.max_pos)
