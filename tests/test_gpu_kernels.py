@@ -222,6 +222,7 @@ def test_linear_f16_weights_narrow_tiles(m, n, k, bias, relu, residual, cols, mo
     (1100, 544, 448, True, True, False),      # FP16: 256 x 256 tiles with a ragged last column block (544 = 17 x 32)
     (4100, 4352, 128, True, False, True),     # 17 x 17 tiles: one whole round + 33 stream-K tiles, ragged last row block
     (2049, 8224, 192, True, False, False),    # 9 x 33 tiles, ragged rows and a ragged column block
+    (600, 512, 64, True, False, True),        # a single K step: every look-ahead copy is a clamped one
 ])
 def test_linear_large_m(m, n, k, bias, relu, residual, quant):
     got, ref = _linear_case(m, n, k, quant, bias, relu, residual, seed=m + n + k)
