@@ -1286,6 +1286,10 @@ static_assert(kP16Lds <= kLdsBytes, "stages must fit in LDS");
 // this step over MFMAs 0..29, slice 0 of the next step over MFMAs 41..61
 constexpr int p16_pos_cur(int p) { return p * 30 / 14; }
 constexpr int p16_pos_nxt(int p) { return 41 + p * 21 / 14; }
+// slice 1's operands are first used by MFMA 32, the next step's slice 0 operands by MFMA 64 (= 0 of the next
+// step), and the code words they are made from land with the wait that ends phase 4 (behind MFMA 39): a
+// piece writes an operand register at least three MFMAs before the first MFMA that reads it
+static_assert(p16_pos_cur(13) <= 32 - 4 && p16_pos_nxt(0) > 39 && p16_pos_nxt(13) <= 64 - 4, "dequantization windows");
 
 // What both prefill kernels on 16 x 16 x 32 MFMAs do with a finished segment of a 256 x 256 tile: acc[m][ct]
 // of wave w holds rows 16 m + 4 g4 + 0..3 of column 32 w + 16 ct + l16.
